@@ -1,0 +1,228 @@
+/*
+ * lora_mi355x.h -- C ABI of the multi-LoRA batched linear layer for MI355X (gfx950).
+ *
+ * The layer is the "unmerged" LoRA linear of the paper (section 2.2: the
+ * backbone product and the adapter product are computed separately and their
+ * results gathered; section 4.4 and section 5: the shared backbone stays
+ * read-only and the adapter computation is kept distinct), for a batch in
+ * which every request carries its own adapter on one resident backbone:
+ *
+ *     Y[t,:] = X[t,:] W0 + s_a (X[t,:] A_a) B_a ,   a = adapter of row t's request
+ *     Y[t,:] = X[t,:] W0                            for requests with adapter -1
+ *
+ * Conventions
+ *   - Plain C, no exceptions, no global state.  Every function returns an int:
+ *     LORA_OK (0) or a negative lora_status; lora_strerror() names it.
+ *   - "host" / "device" is stated for every pointer.  The library never
+ *     allocates device memory and never synchronises the stream unless a
+ *     function says so: plan storage and workspace are caller-provided device
+ *     buffers (e.g. a torch tensor's data_ptr()).
+ *   - W0, X, A_a, B_a are const: no kernel ever writes them.  W0 is used in the
+ *     layout its owner keeps it in (it may be memory shared by another process,
+ *     section 4.4), never re-laid-out or copied.
+ *   - Storage layouts (row-major; "ld" = row stride in elements):
+ *         X   [T, ldx]   rows of a request contiguous, requests in submission order
+ *         W0  [N, ldw]   nn.Linear.weight, i.e. W0[k,n] of the formula at W0[n*ldw + k]
+ *         A_a [r_a, K]   A_a[k,j] of the formula at A_a[j*K + k]
+ *         B_a [N, r_a]   B_a[j,n] of the formula at B_a[n*r_a + j]
+ *         Y   [T, ldy]
+ *   - dtype LORA_DTYPE_BF16: all five tensors bf16, fp32 accumulation; the
+ *     intermediate s_a (X A_a) is rounded once to bf16 before the second
+ *     product.  dtype LORA_DTYPE_F32: everything fp32.
+ *   - Run-to-run results are bitwise reproducible (no floating-point atomics).
+ *   - Thread safety: a ctx may be shared by threads as long as calls that use
+ *     the same plan_buf / workspace / Y are ordered by the caller; lora_plan()
+ *     takes an internal lock for its pinned staging ring.
+ */
+#ifndef LORA_MI355X_H
+#define LORA_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lora_ctx lora_ctx;
+
+/* A hipStream_t, passed as an opaque pointer so that this header needs no HIP
+ * header (torch.cuda.current_stream().cuda_stream is this value). */
+typedef void *lora_stream_t;
+
+typedef enum lora_dtype { LORA_DTYPE_F32 = 0, LORA_DTYPE_BF16 = 1 } lora_dtype;
+
+typedef enum lora_status {
+    LORA_OK = 0,
+    LORA_ERR_INVALID_ARG = -1,           /* null pointer, negative size, unknown dtype/option   */
+    LORA_ERR_BAD_ADAPTER_ID = -2,        /* request adapter id outside [-1, n_adapters)         */
+    LORA_ERR_LENGTH_MISMATCH = -3,       /* negative token count, or sum of counts != T         */
+    LORA_ERR_ADAPTER_NOT_RESIDENT = -4,  /* a used adapter has rank 0 (or null weights)         */
+    LORA_ERR_RANK_TOO_LARGE = -5,        /* a used adapter's rank exceeds r_max                 */
+    LORA_ERR_WORKSPACE_TOO_SMALL = -6,   /* plan_buf or workspace smaller than *_bytes() says   */
+    LORA_ERR_ALIGNMENT = -7,             /* pointer not 16-byte aligned / stride not 16-byte    */
+    LORA_ERR_SHAPE = -8,                 /* K, N, ld*, rank violate the stated requirements     */
+    LORA_ERR_HIP = -9,                   /* a HIP call failed; see lora_last_hip_error()        */
+    LORA_ERR_PLAN = -10                  /* plan not built by this library / built with errors  */
+} lora_status;
+
+/* Limits (checked, never silently clamped). */
+#define LORA_MAX_REQUESTS 65536   /* requests per batch                                  */
+#define LORA_MAX_ADAPTERS 65536   /* adapter slots in a table                            */
+#define LORA_MAX_RANK 512         /* rank of one adapter; ranks are multiples of 8       */
+
+/*
+ * Adapter pointer table.  A table, not one packed tensor, because adapters are
+ * loaded and evicted one at a time and may have different ranks (sections 4.1
+ * and 4.3 of the paper: artifacts, adapters included, come and go
+ * independently).  The struct itself lives on the HOST; A, B and scale point to
+ * DEVICE arrays of n_adapters entries; A[a] / B[a] are DEVICE pointers to that
+ * adapter's weights (16-byte aligned), or NULL for a slot that is not resident.
+ * The caller owns everything and may edit entries between calls (stream-ordered).
+ */
+typedef struct lora_adapter_table_t {
+    int32_t n_adapters;
+    int32_t reserved;
+    const void *const *A; /* device: [n_adapters] device pointers, A[a] -> [rank[a], K] */
+    const void *const *B; /* device: [n_adapters] device pointers, B[a] -> [N, rank[a]] */
+    const float *scale;   /* device: [n_adapters] fp32 s_a                               */
+} lora_adapter_table_t;
+
+/*
+ * Segment table ("plan"): token rows grouped by adapter.  Plain data, filled by
+ * lora_plan*(): device pointers into the caller's plan_buf plus host copies of
+ * the sizes.  Valid until plan_buf is freed or reused; one plan serves every
+ * projection and layer of the same batch.
+ *
+ * Row order: rows are sorted stably by adapter id (ascending; rows without an
+ * adapter last).  "slot" = position in that order.
+ */
+typedef struct lora_plan_t {
+    int64_t T;              /* token rows                                                   */
+    int32_t n_req;
+    int32_t n_adapters;
+    int32_t r_max;          /* row stride of the intermediate V, >= every used rank         */
+    int32_t seg_cap;        /* capacity of the seg_* arrays                                 */
+    int32_t ext_cap;        /* capacity of ext_rec                                          */
+    int32_t magic;
+    const int32_t *perm;        /* device [T]        slot -> row index of X / Y             */
+    const int32_t *row_seg;     /* device [T]        slot -> segment                        */
+    const int32_t *seg_adapter; /* device [seg_cap]  adapter id of the segment (-1 = none)  */
+    const int32_t *seg_indptr;  /* device [seg_cap+1] first slot of the segment             */
+    const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
+    const int32_t *seg_ext;     /* device [seg_cap+1] exclusive prefix sum of seg_rank      */
+    const int32_t *seg_unit;    /* device [seg_cap+1] prefix sum of ceil(rows/64) (shrink work list) */
+    const int32_t *ext_rec;     /* device [ext_cap*4] per 8 ranks: adapter, rank<<16|j0, slot_lo, slot_hi */
+    const int32_t *tok_off;     /* device [n_req+1]  first row of every request             */
+    int32_t *scalars;           /* device [8]: n_seg, status, ext_total, n_units, ...       */
+} lora_plan_t;
+
+typedef struct lora_linear_desc {
+    int32_t dtype;          /* lora_dtype */
+    int32_t K;              /* d_in:  multiple of 8, > 0                                    */
+    int32_t N;              /* d_out: > 0                                                   */
+    int32_t flags;          /* must be 0                                                    */
+    const void *X;          /* device [T, ldx]                                              */
+    int64_t ldx;            /* >= K, multiple of 8 (bf16) or 4 (fp32)                       */
+    const void *W0;         /* device [N, ldw], const, externally owned                     */
+    int64_t ldw;            /* >= K, multiple of 8 (bf16) or 4 (fp32)                       */
+    void *Y;                /* device [T, ldy]; must not alias X, W0 or the adapters        */
+    int64_t ldy;            /* >= N, multiple of 8 (bf16) or 4 (fp32)                       */
+    const lora_adapter_table_t *tbl; /* host pointer; NULL = backbone product only         */
+    void *workspace;        /* device, 256-byte aligned, lora_linear_workspace_bytes() big  */
+    size_t workspace_bytes;
+} lora_linear_desc;
+
+/* ---- context ----------------------------------------------------------- */
+
+/* Creates a context on device `device_ordinal` (host int).  It caches device
+ * properties and owns a small pinned host staging ring used by lora_plan();
+ * nothing else.  *out is set to NULL on failure.  Errors: INVALID_ARG, HIP. */
+int lora_ctx_create(lora_ctx **out, int device_ordinal);
+int lora_ctx_destroy(lora_ctx *ctx);
+
+/* Tuning overrides for experiments ("gemm_variant", "skinny_ksplit",
+ * "skinny_max_rows", "plan_fused_rows"); value < 0 restores the built-in
+ * heuristic.  Results never depend on them beyond fp32 summation order.
+ * Errors: INVALID_ARG for an unknown name. */
+int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value);
+
+/* ---- step a1: segment / indptr builder ---------------------------------- */
+
+/* Pure host check of a batch (all pointers HOST; adapter_rank has n_adapters
+ * entries, 0 = not resident).  Checks, in this order: argument sanity
+ * (INVALID_ARG), ids in [-1, n_adapters) (BAD_ADAPTER_ID), counts >= 0 and
+ * summing to T_expected without overflow (LENGTH_MISMATCH), every used
+ * adapter resident (ADAPTER_NOT_RESIDENT), rank a multiple of 8 (SHAPE) and
+ * <= r_max (RANK_TOO_LARGE).  Touches no GPU.  Optional outputs (may be
+ * NULL): number of segments and total rank over the used adapters. */
+int lora_plan_validate(const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req,
+                       const int32_t *adapter_rank, int32_t n_adapters, int32_t r_max,
+                       int64_t T_expected, int32_t *n_seg_out, int64_t *ext_total_out);
+
+/* Bytes of device memory a plan for such a batch needs (0 on invalid sizes). */
+size_t lora_plan_bytes(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_max);
+
+/* Builds the plan from HOST request arrays (the batcher is CPU code: section
+ * 4.2, the batching scheduler forms per-function batches on the controller).
+ * Validates as lora_plan_validate() before touching the GPU, copies the three
+ * small arrays through the context's pinned ring (they may be freed on
+ * return) and builds every T-sized array on the device, in plan_buf (DEVICE,
+ * 256-byte aligned, >= lora_plan_bytes()).  Asynchronous on `stream`; may
+ * block only when the pinned ring is full (4 plans in flight).  T == 0 is
+ * valid.  Errors: as lora_plan_validate, plus WORKSPACE_TOO_SMALL, ALIGNMENT, HIP. */
+int lora_plan(lora_ctx *ctx, const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req,
+              const int32_t *adapter_rank, int32_t n_adapters, int32_t r_max, int64_t T_expected,
+              void *plan_buf, size_t plan_buf_bytes, lora_stream_t stream, lora_plan_t *out);
+
+/* Same, with req_adapter, req_ntok and adapter_rank already resident on the
+ * DEVICE (read when the stream reaches the build kernels; keep them alive
+ * until then).  Nothing is validated on the host beyond sizes; the device
+ * records the first lora_status it finds in the plan's status word, and every
+ * kernel that later consumes such a plan does nothing.  Query it with
+ * lora_plan_status(). */
+int lora_plan_device(lora_ctx *ctx, const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req,
+                     const int32_t *adapter_rank, int32_t n_adapters, int32_t r_max, int64_t T_expected,
+                     void *plan_buf, size_t plan_buf_bytes, lora_stream_t stream, lora_plan_t *out);
+
+/* Synchronises `stream` and returns the plan's device-side status (LORA_OK or
+ * the negative lora_status recorded by the build or by a later kernel, e.g.
+ * ADAPTER_NOT_RESIDENT for a NULL table entry); *n_seg_out (HOST, may be NULL)
+ * receives the number of segments. */
+int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t stream, int32_t *n_seg_out);
+
+/* ---- steps a2-a4: the layer --------------------------------------------- */
+
+/* Device bytes lora_linear needs in desc->workspace for T rows, N outputs and
+ * V row stride r_max (holds V, split-K partial tiles and their counters). */
+size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype);
+
+/* a2, shrink: V[slot, :r_a] = s_a * X[perm[slot], :] A_a for every row with an
+ * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).
+ * Asynchronous on `stream`.  No-op when desc->tbl is NULL or T == 0. */
+int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
+
+/* a3 + a4, base GEMM with the expand fused before the single store of Y:
+ * Y[perm[slot], :] = X[perm[slot], :] W0 + V[slot, :r_a] B_a, V taken from the
+ * workspace as lora_shrink() left it.  The expand runs as extra K-steps of the
+ * same MFMA loop, so each Y element is written exactly once. */
+int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
+
+/* The whole layer: lora_shrink() then lora_gemm_expand() on `stream`.  Returns
+ * after enqueueing.  Errors (all found before the first launch): INVALID_ARG,
+ * PLAN, SHAPE, ALIGNMENT, WORKSPACE_TOO_SMALL; HIP if a launch fails. */
+int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
+
+/* Name of the GEMM kernel variant lora_gemm_expand() would launch for this
+ * problem ("skinny_tb4_ks4", "tile_128x128", ...), for reports.  Host only. */
+const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype);
+
+/* ---- errors ------------------------------------------------------------- */
+const char *lora_strerror(int status);
+/* The hipError_t (as int) of the last failing HIP call on this thread, 0 if none. */
+int lora_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LORA_MI355X_H */

@@ -1,0 +1,303 @@
+// LDS-tiled MFMA GEMM with the LoRA expand fused as extra K-steps:
+//
+//     Y[perm[slot], n] = sum_k X[perm[slot], k] W0[n, k]  +  sum_{p in ext(slot)} V[slot, p] B_a[n, p]
+//
+// (paper section 4.4: backbone result and adapter result are combined; here they are combined
+// in the fp32 accumulators, before Y is rounded and stored, once.)
+//
+// Rows are processed in the plan's slot order (sorted by adapter), so the rows of one adapter
+// are contiguous.  For an M-tile the adapters of its rows form a contiguous range of segments,
+// and the concatenation of their ranks is one more stretch of the contraction axis: the "X
+// operand" there is V (zero for rows that belong to another adapter), the "W operand" is the
+// matching B_a slice.  B_a is stored [N, r] (r contiguous) and W0 [N, K] (K contiguous), so both
+// feed the same MFMA operand path unchanged.  MFMA work in the extension is skipped for 32-row
+// blocks that hold no row of the adapter at hand.
+//
+// Tile: BM token rows x BN output columns, BK = 8 chunks (128 bytes) of the contraction axis
+// per stage, double-buffered in LDS, global -> registers -> LDS with the next stage's loads
+// in flight during the current stage's MFMAs.  MFMA orientation: M = output column n (W rows),
+// N = token row t (X rows), so that every lane ends up with 4 consecutive n of one row.
+// LDS rows are 8 chunks long and XOR-swizzled by (row >> 1) & 7 so that both the 16-byte
+// stores (8 lanes per row) and the MFMA operand reads (32 rows, one chunk column) spread
+// over all banks.
+//
+// Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8
+// XCDs, so id % 8 picks the XCD and each XCD walks a contiguous, M-grouped range of tiles
+// that share W0 / X panels in its own L2.
+#include <limits.h>
+
+#include "kernels.h"
+
+namespace lora {
+namespace {
+
+constexpr int kTabCap = 512;  // extension chunk columns described per batch (64 stages)
+
+__device__ __forceinline__ int swz(int row, int c) { return row * 8 + (c ^ ((row >> 1) & 7)); }
+
+struct ExtTable {
+    const void *ptr[kTabCap];  // B_a + j (null = column unused)
+    int r[kTabCap];            // row stride of B_a (its rank)
+    int j[kTabCap];            // column offset inside V / B_a
+    int lo[kTabCap];           // tile-relative rows [lo, hi) that belong to the adapter
+    int hi[kTabCap];
+};
+
+template <typename E, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int tiles_m, int tiles_n, int group_m) {
+    constexpr int CE = Elem<E>::CE;
+    constexpr int NT = WM * WN * 64;
+    constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile: rows t, columns n
+    constexpr int NBT = WTM / 32, NBN = WTN / 32;
+    constexpr int XL = BM * 8 / NT, WL = BN * 8 / NT;  // 16-byte loads per thread per stage
+    constexpr int RPP = NT / 8;                        // rows covered per load pass
+    static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    chunk_t *sW = reinterpret_cast<chunk_t *>(smem);                 // [2][BN*8]
+    chunk_t *sX = sW + 2 * BN * 8;                                   // [2][BM*8]
+    ExtTable *tab = reinterpret_cast<ExtTable *>(sX + 2 * BM * 8);
+
+    if (p.plan.scalars[kScStatus] != 0) return;
+
+    // ---- workgroup -> tile (XCD-aware, M-grouped) --------------------------------------
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) >> 3;
+    const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (lin >= total) return;
+    const int width = group_m * tiles_n;
+    const int grp = lin / width;
+    const int first_m = grp * group_m;
+    const int gsz = min(tiles_m - first_m, group_m);
+    const int pm = first_m + (lin % width) % gsz;
+    const int pn = (lin % width) / gsz;
+    const int m0 = pm * BM, n0 = pn * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wn0 = (wave % WN) * WTN, wm0 = (wave / WN) * WTM;
+    const int l31 = lane & 31, lh = lane >> 5;
+
+    const E *X = static_cast<const E *>(p.X);
+    const E *W = static_cast<const E *>(p.W);
+    const E *V = static_cast<const E *>(p.V);
+
+    // ---- per-thread load slots ------------------------------------------------------------
+    const int lrow = tid >> 3, lc = tid & 7;
+    const E *xsrc[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int t = m0 + lrow + i * RPP;
+        xsrc[i] = t < p.T ? X + (int64_t)p.plan.perm[t] * p.ldx : nullptr;
+    }
+    const E *wsrc[WL];
+#pragma unroll
+    for (int i = 0; i < WL; ++i) {
+        const int n = n0 + lrow + i * RPP;
+        wsrc[i] = n < p.N ? W + (int64_t)n * p.ldw : nullptr;
+    }
+
+    // ---- extension range of this M-tile -----------------------------------------------------
+    int pbeg = 0, pend = 0;
+    if (p.B != nullptr) {
+        const int s_first = p.plan.row_seg[m0];
+        const int s_last = p.plan.row_seg[min(m0 + BM, p.T) - 1];
+        pbeg = p.plan.seg_ext[s_first];
+        pend = p.plan.seg_ext[s_last + 1];
+    }
+    const int ext_chunks = (pend - pbeg) / CE;
+
+    auto build_table = [&](int chunk0) {
+        for (int idx = tid; idx < kTabCap; idx += NT) {
+            const int pe = pbeg + (chunk0 + idx) * CE;
+            const void *ptr = nullptr;
+            int r = 0, j = 0, lo = INT_MAX, hi = INT_MIN;
+            if (pe < pend) {
+                const int4 rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[pe >> 3];
+                const E *b = rec.x >= 0 ? static_cast<const E *>(p.B[rec.x]) : nullptr;
+                if (b != nullptr) {
+                    r = rec.y >> 16;
+                    j = (rec.y & 0xffff) + (pe & 7);
+                    lo = max(rec.z - m0, 0);
+                    hi = min(rec.w - m0, BM);
+                    ptr = b + j;
+                } else {
+                    atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+                }
+            }
+            tab->ptr[idx] = ptr;
+            tab->r[idx] = r;
+            tab->j[idx] = j;
+            tab->lo[idx] = lo;
+            tab->hi[idx] = hi;
+        }
+    };
+    if (ext_chunks > 0) build_table(0);  // visible after the first barrier of the base loop
+
+    f32x16_t acc[NBN][NBT];
+#pragma unroll
+    for (int nb = 0; nb < NBN; ++nb)
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[nb][tb][e] = 0.f;
+
+    chunk_t xr[XL], wr[WL];
+
+    auto load_base = [&](int kt) {
+        const int kc = kt * 8 + lc;
+        const bool kv = kc * CE < p.K;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) xr[i] = (kv && xsrc[i] != nullptr) ? load_chunk(xsrc[i] + kc * CE) : zero_chunk();
+#pragma unroll
+        for (int i = 0; i < WL; ++i) wr[i] = (kv && wsrc[i] != nullptr) ? load_chunk(wsrc[i] + kc * CE) : zero_chunk();
+    };
+    auto load_ext = [&](int se) {  // se = stage inside the current table batch
+        const int idx = se * 8 + lc;
+        const E *bp = static_cast<const E *>(tab->ptr[idx]);
+        const int r = tab->r[idx], j = tab->j[idx], lo = tab->lo[idx], hi = tab->hi[idx];
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int row = lrow + i * RPP;
+            xr[i] = (row >= lo && row < hi) ? load_chunk(V + (int64_t)(m0 + row) * p.r_max + j) : zero_chunk();
+        }
+#pragma unroll
+        for (int i = 0; i < WL; ++i) {
+            const int n = n0 + lrow + i * RPP;
+            wr[i] = (bp != nullptr && n < p.N) ? load_chunk(bp + (int64_t)n * r) : zero_chunk();
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) sX[buf * BM * 8 + swz(lrow + i * RPP, lc)] = xr[i];
+#pragma unroll
+        for (int i = 0; i < WL; ++i) sW[buf * BN * 8 + swz(lrow + i * RPP, lc)] = wr[i];
+    };
+    auto compute = [&](int buf, int se) {  // se < 0: base stage (no skipping)
+        const chunk_t *bw = sW + buf * BN * 8;
+        const chunk_t *bx = sX + buf * BM * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            int lo = 0, hi = BM;
+            if (se >= 0) {
+                const int i0 = se * 8 + 2 * kk;
+                lo = min(tab->lo[i0], tab->lo[i0 + 1]);
+                hi = max(tab->hi[i0], tab->hi[i0 + 1]);
+                if (hi <= lo) continue;
+            }
+            const int cc = 2 * kk + lh;
+            chunk_t wf[NBN], xf[NBT];
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb) wf[nb] = bw[swz(wn0 + nb * 32 + l31, cc)];
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) {
+                const int t0 = wm0 + tb * 32;
+                if (se < 0 || (lo < t0 + 32 && hi > t0)) {
+                    xf[tb] = bx[swz(t0 + l31, cc)];
+#pragma unroll
+                    for (int nb = 0; nb < NBN; ++nb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[tb]);
+                }
+            }
+        }
+    };
+
+    // ---- base product: sum over K ---------------------------------------------------------------
+    const int KT = (p.K + 8 * CE - 1) / (8 * CE);
+    load_base(0);
+    store_stage(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 1 < KT;
+        if (more) load_base(kt + 1);
+        compute(kt & 1, -1);
+        if (more) store_stage((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- extension: sum over the concatenated ranks of this tile's adapters -----------------------
+    for (int chunk0 = 0; chunk0 < ext_chunks; chunk0 += kTabCap) {
+        if (chunk0 > 0) {
+            build_table(chunk0);
+            __syncthreads();
+        }
+        const int nst = (min(ext_chunks - chunk0, kTabCap) + 7) >> 3;
+        load_ext(0);
+        store_stage(0);
+        __syncthreads();
+        for (int se = 0; se < nst; ++se) {
+            const bool more = se + 1 < nst;
+            if (more) load_ext(se + 1);
+            compute(se & 1, se);
+            if (more) store_stage((se + 1) & 1);
+            __syncthreads();
+        }
+    }
+
+    // ---- single store of Y: acc[nb][tb][g*4+e] = D[n = nb*32 + g*8 + lh*4 + e][t = tb*32 + l31] -------
+    E *Y = static_cast<E *>(p.Y);
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) {
+        const int t = m0 + wm0 + tb * 32 + l31;
+        if (t >= p.T) continue;
+        E *yrow = Y + (int64_t)p.plan.perm[t] * p.ldy;
+#pragma unroll
+        for (int nb = 0; nb < NBN; ++nb) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn0 + nb * 32 + g * 8 + lh * 4;
+                const f32x16_t &c = acc[nb][tb];
+                if (n + 3 < p.N) {
+                    store4(yrow + n, c[g * 4 + 0], c[g * 4 + 1], c[g * 4 + 2], c[g * 4 + 3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < p.N) store1(yrow + n + e, c[g * 4 + e]);
+                }
+            }
+        }
+    }
+}
+
+template <typename E, int BM, int BN, int WM, int WN>
+hipError_t launch_tile(const GemmArgs &a, hipStream_t stream) {
+    const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+    const long total = (long)tiles_m * tiles_n;
+    if (total <= 0) return hipSuccess;
+    const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);
+    auto kern = gemm_tile_kernel<E, BM, BN, WM, WN>;
+    static bool attr_set = false;  // per instantiation
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long grid = ((total + 7) / 8) * 8;
+    const int group_m = 8;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, a, tiles_m, tiles_n, group_m);
+    return hipGetLastError();
+}
+
+template <typename E>
+hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream) {
+    switch (variant) {
+        case kGemmTile64x64:
+            return launch_tile<E, 64, 64, 2, 2>(a, stream);
+        case kGemmTile128x128:
+            return launch_tile<E, 128, 128, 2, 2>(a, stream);
+        case kGemmTile256x128:
+            return launch_tile<E, 256, 128, 4, 2>(a, stream);
+        case kGemmTile256x256:
+            return launch_tile<E, 256, 256, 4, 2>(a, stream);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream) {
+    return dtype == 1 ? launch_variant<__bf16>(a, variant, stream) : launch_variant<float>(a, variant, stream);
+}
+
+}  // namespace lora

@@ -1,0 +1,93 @@
+// Host-side launch interface between lora_api.hip and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.hiph"
+
+namespace lora {
+
+struct PlanBuildArgs {
+    const int32_t *req_adapter;  // device [n_req]
+    const int32_t *req_ntok;     // device [n_req]
+    const int32_t *rank;         // device [n_adapters]
+    int32_t n_req, n_adapters, r_max;
+    int32_t T;
+    int32_t seg_cap, ext_cap;
+    // outputs / scratch, all device int32 arrays inside plan_buf
+    int32_t *tok_off;      // [n_req+1]
+    int32_t *req_dst;      // [n_req]  first slot of each request's rows
+    int32_t *hist;         // [n_adapters+1] rows per key (key n_adapters = no adapter)
+    int32_t *cursor;       // [n_adapters+1] running slot per key
+    int32_t *key_seg;      // [n_adapters+1] segment of key or -1
+    int32_t *perm;         // [T]
+    int32_t *row_seg;      // [T]
+    int32_t *seg_adapter;  // [seg_cap]
+    int32_t *seg_indptr;   // [seg_cap+1]
+    int32_t *seg_rank;     // [seg_cap]
+    int32_t *seg_ext;      // [seg_cap+1]
+    int32_t *seg_unit;     // [seg_cap+1]
+    int32_t *ext_rec;      // [ext_cap*4]
+    int32_t *scalars;      // [8]
+};
+
+// Enqueues the segment builder (one or two kernels).  `fuse_fill`: the single
+// workgroup of the first kernel also fills the T-sized arrays.
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream);
+
+struct ShrinkArgs {
+    PlanView plan;
+    const void *X;
+    int64_t ldx;
+    int32_t K;
+    int32_t T;
+    const void *const *A;  // device table
+    const float *scale;    // device table
+    void *V;               // [T, r_max] of E
+    int32_t r_max;
+    int32_t rank_groups;   // ceil(r_max / kShrinkRanks)
+    int32_t max_units;     // upper bound of work units (grid = max_units * rank_groups)
+    int32_t *zero_ptr;     // optional: ints to clear (split-K counters), may be null
+    int32_t zero_count;
+};
+hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream);
+
+// Clears `count` ints (used instead of a memset node so that callers may capture the stream).
+hipError_t launch_zero_ints(int32_t *ptr, int32_t count, hipStream_t stream);
+
+struct GemmArgs {
+    PlanView plan;
+    const void *X;
+    int64_t ldx;
+    const void *W;
+    int64_t ldw;
+    void *Y;
+    int64_t ldy;
+    const void *V;         // [T, r_max] of E, slot order (null when no adapters)
+    const void *const *B;  // device table (null when no adapters)
+    int32_t r_max;
+    int32_t T, K, N;
+    // skinny (split-K) variants only
+    float *partials;
+    int32_t *counters;
+    int32_t ksplit;
+};
+
+enum GemmVariant {
+    kGemmTile128x128 = 0,
+    kGemmTile256x128 = 1,
+    kGemmTile256x256 = 2,
+    kGemmTile64x64 = 3,
+    kGemmSkinny = 4,
+    kGemmVariantCount
+};
+
+hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream);
+hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream);
+
+// Geometry of the skinny kernel shared with the host (workspace sizing).
+constexpr int kSkinnyBN = 64;        // output columns per workgroup
+constexpr int kSkinnyMaxRows = 128;  // rows it accepts
+constexpr int kSkinnyMaxKSplit = 8;
+
+}  // namespace lora

@@ -1,0 +1,647 @@
+// Host side of the C ABI: argument validation, plan storage layout, kernel selection and launch.
+// Every check that can be made without the GPU is made before the first HIP call.
+#include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <new>
+
+#include "../../include/lora_mi355x.h"
+#include "kernels.h"
+
+using namespace lora;
+
+static_assert(LORA_ERR_BAD_ADAPTER_ID == kErrBadAdapterId, "status codes out of sync");
+static_assert(LORA_ERR_LENGTH_MISMATCH == kErrLengthMismatch, "status codes out of sync");
+static_assert(LORA_ERR_ADAPTER_NOT_RESIDENT == kErrNotResident, "status codes out of sync");
+static_assert(LORA_ERR_RANK_TOO_LARGE == kErrRankTooLarge, "status codes out of sync");
+static_assert(LORA_ERR_SHAPE == kErrShape, "status codes out of sync");
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();  // clear the sticky error so that the caller's next HIP call is not blamed
+    return LORA_ERR_HIP;
+}
+#define LORA_HIP(call)                           \
+    do {                                         \
+        hipError_t e_ = (call);                  \
+        if (e_ != hipSuccess) return hip_fail(e_); \
+    } while (0)
+
+constexpr int kRingSlots = 4;
+constexpr size_t kRingSlotInts = 2 * (size_t)LORA_MAX_REQUESTS + LORA_MAX_ADAPTERS;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct lora_ctx {
+    int device = 0;
+    int num_cu = 256;
+    // pinned staging ring for lora_plan's small host arrays
+    int32_t *ring = nullptr;
+    hipEvent_t ring_event[kRingSlots] = {};
+    bool ring_used[kRingSlots] = {};
+    int ring_next = 0;
+    std::mutex ring_mutex;
+    // tuning overrides (-1 = heuristic)
+    int opt_gemm_variant = -1;
+    int opt_skinny_ksplit = -1;
+    int opt_skinny_max_rows = -1;
+    int opt_plan_fused_rows = -1;
+};
+
+namespace {
+
+// Sets the context's device for the duration of a call and restores the caller's.
+struct DeviceGuard {
+    int prev = -1;
+    bool changed = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceGuard(int dev) {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != dev) {
+            err = hipSetDevice(dev);
+            changed = err == hipSuccess;
+        }
+    }
+    ~DeviceGuard() {
+        if (changed) (void)hipSetDevice(prev);
+    }
+};
+
+// ---- plan storage layout ------------------------------------------------------------------------
+struct PlanLayout {
+    size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, seg_adapter, seg_indptr, seg_rank, seg_ext,
+        seg_unit, ext_rec, scalars, total_bytes;
+    int32_t seg_cap, ext_cap;
+};
+
+bool plan_sizes_ok(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_max) {
+    return n_req >= 0 && n_req <= LORA_MAX_REQUESTS && n_adapters >= 0 && n_adapters <= LORA_MAX_ADAPTERS && T >= 0 &&
+           T <= (int64_t)INT32_MAX - 65536 && r_max >= 0 && r_max <= LORA_MAX_RANK && (r_max & 7) == 0;
+}
+
+PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_max) {
+    PlanLayout L;
+    size_t off = 0;  // in int32 units; every section starts on a 256-byte boundary
+    auto take = [&](size_t n) {
+        size_t o = off;
+        off = align_up(off + n, 64);
+        return o;
+    };
+    const size_t R = (size_t)n_req, A = (size_t)n_adapters;
+    L.seg_cap = n_adapters + 1;
+    const size_t used_max = R < A ? R : A;
+    L.ext_cap = (int32_t)(used_max * (size_t)(r_max / 8));
+    L.staged = take(2 * R + A);
+    L.tok_off = take(R + 1);
+    L.req_dst = take(R);
+    L.hist = take(A + 1);
+    L.cursor = take(A + 1);
+    L.key_seg = take(A + 1);
+    L.perm = take((size_t)T);
+    L.row_seg = take((size_t)T);
+    L.seg_adapter = take((size_t)L.seg_cap);
+    L.seg_indptr = take((size_t)L.seg_cap + 1);
+    L.seg_rank = take((size_t)L.seg_cap);
+    L.seg_ext = take((size_t)L.seg_cap + 1);
+    L.seg_unit = take((size_t)L.seg_cap + 1);
+    L.ext_rec = take((size_t)L.ext_cap * 4);
+    L.scalars = take(8);
+    L.total_bytes = off * sizeof(int32_t);
+    return L;
+}
+
+int validate_batch(const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req, const int32_t *adapter_rank,
+                   int32_t n_adapters, int32_t r_max, int64_t T_expected, int32_t *n_seg_out, int64_t *ext_total_out) {
+    if (!plan_sizes_ok(n_req, T_expected, n_adapters, r_max)) return LORA_ERR_INVALID_ARG;
+    if (n_req > 0 && (!req_adapter || !req_ntok)) return LORA_ERR_INVALID_ARG;
+    if (n_adapters > 0 && !adapter_rank) return LORA_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n_req; ++i)
+        if (req_adapter[i] < -1 || req_adapter[i] >= n_adapters) return LORA_ERR_BAD_ADAPTER_ID;
+    int64_t sum = 0;
+    for (int32_t i = 0; i < n_req; ++i) {
+        if (req_ntok[i] < 0) return LORA_ERR_LENGTH_MISMATCH;
+        sum += req_ntok[i];
+    }
+    if (sum != T_expected) return LORA_ERR_LENGTH_MISMATCH;
+    // used adapters: O(R) marks in a bitmap on the stack-free heap (n_adapters <= 65536 -> 8 KiB)
+    const size_t words = ((size_t)n_adapters + 1 + 63) / 64;
+    uint64_t *used = new (std::nothrow) uint64_t[words ? words : 1]();
+    if (!used) return LORA_ERR_INVALID_ARG;
+    bool any_none = false;
+    for (int32_t i = 0; i < n_req; ++i) {
+        if (req_ntok[i] == 0) continue;
+        if (req_adapter[i] < 0)
+            any_none = true;
+        else
+            used[req_adapter[i] >> 6] |= 1ull << (req_adapter[i] & 63);
+    }
+    int rc = LORA_OK;
+    int32_t n_seg = any_none ? 1 : 0;
+    int64_t ext = 0;
+    for (int32_t a = 0; a < n_adapters && rc == LORA_OK; ++a) {
+        if (!(used[a >> 6] >> (a & 63) & 1ull)) continue;
+        const int32_t r = adapter_rank[a];
+        if (r <= 0)
+            rc = LORA_ERR_ADAPTER_NOT_RESIDENT;
+        else if (r & 7)
+            rc = LORA_ERR_SHAPE;
+        else if (r > r_max)
+            rc = LORA_ERR_RANK_TOO_LARGE;
+        ++n_seg;
+        ext += r;
+    }
+    delete[] used;
+    if (rc != LORA_OK) return rc;
+    if (n_seg_out) *n_seg_out = n_seg;
+    if (ext_total_out) *ext_total_out = ext;
+    return LORA_OK;
+}
+
+int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req_ntok_dev, const int32_t *rank_dev,
+               int32_t n_req, int32_t n_adapters, int32_t r_max, int64_t T, const PlanLayout &L, int32_t *base,
+               hipStream_t stream, lora_plan_t *out) {
+    PlanBuildArgs a;
+    a.req_adapter = req_adapter_dev;
+    a.req_ntok = req_ntok_dev;
+    a.rank = rank_dev;
+    a.n_req = n_req;
+    a.n_adapters = n_adapters;
+    a.r_max = r_max;
+    a.T = (int32_t)T;
+    a.seg_cap = L.seg_cap;
+    a.ext_cap = L.ext_cap;
+    a.tok_off = base + L.tok_off;
+    a.req_dst = base + L.req_dst;
+    a.hist = base + L.hist;
+    a.cursor = base + L.cursor;
+    a.key_seg = base + L.key_seg;
+    a.perm = base + L.perm;
+    a.row_seg = base + L.row_seg;
+    a.seg_adapter = base + L.seg_adapter;
+    a.seg_indptr = base + L.seg_indptr;
+    a.seg_rank = base + L.seg_rank;
+    a.seg_ext = base + L.seg_ext;
+    a.seg_unit = base + L.seg_unit;
+    a.ext_rec = base + L.ext_rec;
+    a.scalars = base + L.scalars;
+    const int fused_rows = ctx->opt_plan_fused_rows >= 0 ? ctx->opt_plan_fused_rows : 4096;
+    const bool fuse = T <= fused_rows && L.ext_cap <= 8192;
+    LORA_HIP(launch_plan_build(a, fuse, stream));
+
+    out->T = T;
+    out->n_req = n_req;
+    out->n_adapters = n_adapters;
+    out->r_max = r_max;
+    out->seg_cap = L.seg_cap;
+    out->ext_cap = L.ext_cap;
+    out->magic = kPlanMagic;
+    out->perm = a.perm;
+    out->row_seg = a.row_seg;
+    out->seg_adapter = a.seg_adapter;
+    out->seg_indptr = a.seg_indptr;
+    out->seg_rank = a.seg_rank;
+    out->seg_ext = a.seg_ext;
+    out->seg_unit = a.seg_unit;
+    out->ext_rec = a.ext_rec;
+    out->tok_off = a.tok_off;
+    out->scalars = a.scalars;
+    return LORA_OK;
+}
+
+int check_plan_buf(const void *plan_buf, size_t plan_buf_bytes, const PlanLayout &L, lora_plan_t *out) {
+    if (!out) return LORA_ERR_INVALID_ARG;
+    if (!plan_buf) return LORA_ERR_INVALID_ARG;
+    if (((uintptr_t)plan_buf & 255u) != 0) return LORA_ERR_ALIGNMENT;
+    if (plan_buf_bytes < L.total_bytes) return LORA_ERR_WORKSPACE_TOO_SMALL;
+    return LORA_OK;
+}
+
+// ---- kernel selection ---------------------------------------------------------------------------------
+int skinny_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : 8; }
+
+struct GemmChoice {
+    int variant;
+    int tblk;    // skinny only
+    int ksplit;  // skinny only
+};
+
+GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
+    GemmChoice c{kGemmTile128x128, 0, 1};
+    const int max_rows = ctx && ctx->opt_skinny_max_rows >= 0 ? ctx->opt_skinny_max_rows : kSkinnyMaxRows;
+    int forced = ctx ? ctx->opt_gemm_variant : -1;
+    if (forced == kGemmSkinny && (dtype != LORA_DTYPE_BF16 || T > kSkinnyMaxRows)) forced = -1;
+    const bool skinny = forced == kGemmSkinny || (forced < 0 && dtype == LORA_DTYPE_BF16 && T <= max_rows && T <= kSkinnyMaxRows);
+    if (skinny) {
+        c.variant = kGemmSkinny;
+        c.tblk = skinny_tblk(T);
+        const int n_tiles = (N + kSkinnyBN - 1) / kSkinnyBN;
+        const int cus = ctx ? ctx->num_cu : 256;
+        int ks = 1;
+        while (ks < kSkinnyMaxKSplit && n_tiles * ks < 2 * cus && K / (ks * 2) >= 256) ks *= 2;
+        if (ctx && ctx->opt_skinny_ksplit >= 1) ks = ctx->opt_skinny_ksplit;
+        if (ks > kSkinnyMaxKSplit) ks = kSkinnyMaxKSplit;
+        c.ksplit = ks;
+        return c;
+    }
+    if (forced >= 0 && forced < kGemmSkinny) {
+        c.variant = forced;
+        return c;
+    }
+    // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency.
+    struct Cand {
+        int variant, bm, bn;
+        double eff;
+    };
+    const Cand cands[] = {{kGemmTile256x256, 256, 256, 1.00},
+                          {kGemmTile256x128, 256, 128, 0.90},
+                          {kGemmTile128x128, 128, 128, 0.80},
+                          {kGemmTile64x64, 64, 64, 0.45}};
+    const int cus = ctx ? ctx->num_cu : 256;
+    double best = 0.0;
+    bool have = false;
+    for (const Cand &cd : cands) {
+        const int64_t tiles = ((T + cd.bm - 1) / cd.bm) * (int64_t)((N + cd.bn - 1) / cd.bn);
+        const int64_t rounds = (tiles + cus - 1) / cus;
+        const double cost = (double)rounds * cd.bm * cd.bn / cd.eff;
+        if (!have || cost < best) {
+            best = cost;
+            have = true;
+            c.variant = cd.variant;
+        }
+    }
+    return c;
+}
+
+struct WorkspaceLayout {
+    size_t v_off, counters_off, partials_off, total;
+    int n_tiles;
+};
+
+WorkspaceLayout workspace_layout(int64_t T, int32_t N, int32_t r_max, int32_t dtype) {
+    WorkspaceLayout w;
+    const size_t es = dtype == LORA_DTYPE_BF16 ? 2 : 4;
+    w.n_tiles = (N + kSkinnyBN - 1) / kSkinnyBN;
+    size_t off = 0;
+    w.v_off = off;
+    off = align_up(off + (size_t)T * (size_t)r_max * es, 256);
+    w.counters_off = off;
+    off = align_up(off + (size_t)w.n_tiles * sizeof(int32_t), 256);
+    w.partials_off = off;
+    if (dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && T > 0)
+        off = align_up(off + (size_t)w.n_tiles * kSkinnyMaxKSplit * skinny_tblk(T) * 256 * sizeof(float4), 256);
+    w.total = off < 256 ? 256 : off;
+    return w;
+}
+
+int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d) {
+    if (!plan || !d) return LORA_ERR_INVALID_ARG;
+    if (plan->magic != kPlanMagic || plan->T < 0 || !plan->scalars) return LORA_ERR_PLAN;
+    if (d->dtype != LORA_DTYPE_BF16 && d->dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
+    if (d->flags != 0) return LORA_ERR_INVALID_ARG;
+    const int ce = d->dtype == LORA_DTYPE_BF16 ? 8 : 4;
+    if (d->K <= 0 || d->N <= 0 || (d->K & 7) != 0) return LORA_ERR_SHAPE;
+    if (d->ldx < d->K || d->ldw < d->K || d->ldy < d->N) return LORA_ERR_SHAPE;
+    if (d->ldx % ce || d->ldw % ce || d->ldy % ce) return LORA_ERR_ALIGNMENT;
+    if (plan->T > 0) {
+        if (!d->X || !d->W0 || !d->Y) return LORA_ERR_INVALID_ARG;
+        if (((uintptr_t)d->X | (uintptr_t)d->W0 | (uintptr_t)d->Y) & 15u) return LORA_ERR_ALIGNMENT;
+        if (d->Y == d->X || d->Y == d->W0) return LORA_ERR_INVALID_ARG;
+    }
+    if (d->tbl) {
+        if (d->tbl->n_adapters < plan->n_adapters) return LORA_ERR_INVALID_ARG;
+        if (plan->n_adapters > 0 && (!d->tbl->A || !d->tbl->B || !d->tbl->scale)) return LORA_ERR_INVALID_ARG;
+    }
+    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    if (plan->T > 0) {
+        if (!d->workspace) return LORA_ERR_INVALID_ARG;
+        if ((uintptr_t)d->workspace & 255u) return LORA_ERR_ALIGNMENT;
+        if (d->workspace_bytes < w.total) return LORA_ERR_WORKSPACE_TOO_SMALL;
+    }
+    if (!ctx) return LORA_ERR_INVALID_ARG;  // last, so that the checks above run on a GPU-less host too
+    return LORA_OK;
+}
+
+PlanView view_of(const lora_plan_t *plan) {
+    PlanView v;
+    v.perm = plan->perm;
+    v.row_seg = plan->row_seg;
+    v.seg_adapter = plan->seg_adapter;
+    v.seg_indptr = plan->seg_indptr;
+    v.seg_rank = plan->seg_rank;
+    v.seg_ext = plan->seg_ext;
+    v.seg_unit = plan->seg_unit;
+    v.ext_rec = plan->ext_rec;
+    v.scalars = plan->scalars;
+    return v;
+}
+
+bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
+    return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
+}
+
+int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream, bool zero_counters) {
+    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    unsigned char *ws = static_cast<unsigned char *>(d->workspace);
+    int32_t *counters = reinterpret_cast<int32_t *>(ws + w.counters_off);
+    if (!has_adapters(plan, d)) {
+        if (zero_counters) LORA_HIP(launch_zero_ints(counters, w.n_tiles, stream));
+        return LORA_OK;
+    }
+    ShrinkArgs a;
+    a.plan = view_of(plan);
+    a.X = d->X;
+    a.ldx = d->ldx;
+    a.K = d->K;
+    a.T = (int32_t)plan->T;
+    a.A = d->tbl->A;
+    a.scale = d->tbl->scale;
+    a.V = ws + w.v_off;
+    a.r_max = plan->r_max;
+    a.rank_groups = (plan->r_max + kShrinkRanks - 1) / kShrinkRanks;
+    // units <= sum over segments of ceil(rows/64) <= T/64 + number of adapter segments
+    const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
+    const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
+    a.max_units = (int32_t)(plan->T / kShrinkRows + seg_bound2);
+    a.zero_ptr = zero_counters ? counters : nullptr;
+    a.zero_count = zero_counters ? w.n_tiles : 0;
+    (void)ctx;
+    LORA_HIP(launch_shrink(a, d->dtype, stream));
+    return LORA_OK;
+}
+
+int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
+    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    unsigned char *ws = static_cast<unsigned char *>(d->workspace);
+    GemmArgs a;
+    a.plan = view_of(plan);
+    a.X = d->X;
+    a.ldx = d->ldx;
+    a.W = d->W0;
+    a.ldw = d->ldw;
+    a.Y = d->Y;
+    a.ldy = d->ldy;
+    const bool ad = has_adapters(plan, d);
+    a.V = ad ? ws + w.v_off : nullptr;
+    a.B = ad ? d->tbl->B : nullptr;
+    a.r_max = plan->r_max;
+    a.T = (int32_t)plan->T;
+    a.K = d->K;
+    a.N = d->N;
+    a.partials = reinterpret_cast<float *>(ws + w.partials_off);
+    a.counters = reinterpret_cast<int32_t *>(ws + w.counters_off);
+    const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
+    a.ksplit = c.ksplit;
+    if (c.variant == kGemmSkinny)
+        LORA_HIP(launch_gemm_skinny(a, c.tblk, stream));
+    else
+        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream));
+    return LORA_OK;
+}
+
+}  // namespace
+
+// =========================================================================================================
+extern "C" {
+
+int lora_ctx_create(lora_ctx **out, int device_ordinal) {
+    if (!out) return LORA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    int count = 0;
+    LORA_HIP(hipGetDeviceCount(&count));
+    if (device_ordinal >= count) return LORA_ERR_INVALID_ARG;
+    lora_ctx *ctx = new (std::nothrow) lora_ctx();
+    if (!ctx) return LORA_ERR_INVALID_ARG;
+    ctx->device = device_ordinal;
+    DeviceGuard guard(device_ordinal);
+    hipError_t e = guard.err;
+    hipDeviceProp_t prop;
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, device_ordinal);
+    if (e == hipSuccess) {
+        ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        e = hipHostMalloc(reinterpret_cast<void **>(&ctx->ring), kRingSlots * kRingSlotInts * sizeof(int32_t), hipHostMallocDefault);
+    }
+    for (int i = 0; i < kRingSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->ring_event[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+        for (int i = 0; i < kRingSlots; ++i)
+            if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
+        if (ctx->ring) (void)hipHostFree(ctx->ring);
+        delete ctx;
+        return hip_fail(e);
+    }
+    *out = ctx;
+    return LORA_OK;
+}
+
+int lora_ctx_destroy(lora_ctx *ctx) {
+    if (!ctx) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    for (int i = 0; i < kRingSlots; ++i) {
+        if (ctx->ring_event[i]) {
+            if (ctx->ring_used[i]) (void)hipEventSynchronize(ctx->ring_event[i]);
+            (void)hipEventDestroy(ctx->ring_event[i]);
+        }
+    }
+    if (ctx->ring) (void)hipHostFree(ctx->ring);
+    delete ctx;
+    return LORA_OK;
+}
+
+int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
+    if (!ctx || !name) return LORA_ERR_INVALID_ARG;
+    if (!strcmp(name, "gemm_variant")) {
+        if (value >= kGemmVariantCount) return LORA_ERR_INVALID_ARG;
+        ctx->opt_gemm_variant = value;
+    } else if (!strcmp(name, "skinny_ksplit")) {
+        if (value > kSkinnyMaxKSplit) return LORA_ERR_INVALID_ARG;
+        ctx->opt_skinny_ksplit = value;
+    } else if (!strcmp(name, "skinny_max_rows")) {
+        ctx->opt_skinny_max_rows = value;
+    } else if (!strcmp(name, "plan_fused_rows")) {
+        ctx->opt_plan_fused_rows = value;
+    } else {
+        return LORA_ERR_INVALID_ARG;
+    }
+    return LORA_OK;
+}
+
+int lora_plan_validate(const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req, const int32_t *adapter_rank,
+                       int32_t n_adapters, int32_t r_max, int64_t T_expected, int32_t *n_seg_out, int64_t *ext_total_out) {
+    return validate_batch(req_adapter, req_ntok, n_req, adapter_rank, n_adapters, r_max, T_expected, n_seg_out, ext_total_out);
+}
+
+size_t lora_plan_bytes(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_max) {
+    if (!plan_sizes_ok(n_req, T, n_adapters, r_max)) return 0;
+    return plan_layout(n_req, T, n_adapters, r_max).total_bytes;
+}
+
+int lora_plan(lora_ctx *ctx, const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req, const int32_t *adapter_rank,
+              int32_t n_adapters, int32_t r_max, int64_t T_expected, void *plan_buf, size_t plan_buf_bytes,
+              lora_stream_t stream_, lora_plan_t *out) {
+    int rc = validate_batch(req_adapter, req_ntok, n_req, adapter_rank, n_adapters, r_max, T_expected, nullptr, nullptr);
+    if (rc != LORA_OK) return rc;
+    const PlanLayout L = plan_layout(n_req, T_expected, n_adapters, r_max);
+    rc = check_plan_buf(plan_buf, plan_buf_bytes, L, out);
+    if (rc != LORA_OK) return rc;
+    if (!ctx) return LORA_ERR_INVALID_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    int32_t *base = static_cast<int32_t *>(plan_buf);
+    int32_t *staged = base + L.staged;
+    const size_t n_ints = 2 * (size_t)n_req + (size_t)n_adapters;
+    if (n_ints > 0) {
+        std::lock_guard<std::mutex> lock(ctx->ring_mutex);
+        const int slot = ctx->ring_next;
+        ctx->ring_next = (slot + 1) % kRingSlots;
+        if (ctx->ring_used[slot]) LORA_HIP(hipEventSynchronize(ctx->ring_event[slot]));
+        int32_t *host = ctx->ring + (size_t)slot * kRingSlotInts;
+        if (n_req > 0) {
+            memcpy(host, req_adapter, sizeof(int32_t) * (size_t)n_req);
+            memcpy(host + n_req, req_ntok, sizeof(int32_t) * (size_t)n_req);
+        }
+        if (n_adapters > 0) memcpy(host + 2 * (size_t)n_req, adapter_rank, sizeof(int32_t) * (size_t)n_adapters);
+        LORA_HIP(hipMemcpyAsync(staged, host, n_ints * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+        LORA_HIP(hipEventRecord(ctx->ring_event[slot], stream));
+        ctx->ring_used[slot] = true;
+    }
+    return build_plan(ctx, staged, staged + n_req, staged + 2 * (size_t)n_req, n_req, n_adapters, r_max, T_expected, L, base,
+                      stream, out);
+}
+
+int lora_plan_device(lora_ctx *ctx, const int32_t *req_adapter, const int32_t *req_ntok, int32_t n_req,
+                     const int32_t *adapter_rank, int32_t n_adapters, int32_t r_max, int64_t T_expected, void *plan_buf,
+                     size_t plan_buf_bytes, lora_stream_t stream_, lora_plan_t *out) {
+    if (!plan_sizes_ok(n_req, T_expected, n_adapters, r_max)) return LORA_ERR_INVALID_ARG;
+    if (n_req > 0 && (!req_adapter || !req_ntok)) return LORA_ERR_INVALID_ARG;
+    if (n_adapters > 0 && !adapter_rank) return LORA_ERR_INVALID_ARG;
+    const PlanLayout L = plan_layout(n_req, T_expected, n_adapters, r_max);
+    int rc = check_plan_buf(plan_buf, plan_buf_bytes, L, out);
+    if (rc != LORA_OK) return rc;
+    if (!ctx) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    return build_plan(ctx, req_adapter, req_ntok, adapter_rank, n_req, n_adapters, r_max, T_expected, L,
+                      static_cast<int32_t *>(plan_buf), static_cast<hipStream_t>(stream_), out);
+}
+
+int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t stream_, int32_t *n_seg_out) {
+    if (!ctx || !plan) return LORA_ERR_INVALID_ARG;
+    if (plan->magic != kPlanMagic || !plan->scalars) return LORA_ERR_PLAN;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    LORA_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream_)));
+    int32_t sc[8];
+    LORA_HIP(hipMemcpy(sc, plan->scalars, sizeof sc, hipMemcpyDeviceToHost));
+    if (n_seg_out) *n_seg_out = sc[kScNSeg];
+    return sc[kScStatus];
+}
+
+size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype) {
+    if (T < 0 || N <= 0 || r_max < 0 || (dtype != LORA_DTYPE_BF16 && dtype != LORA_DTYPE_F32)) return 0;
+    return workspace_layout(T, N, r_max, dtype).total;
+}
+
+int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {
+    int rc = check_linear(ctx, plan, desc);
+    if (rc != LORA_OK) return rc;
+    if (plan->T == 0) return LORA_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    return do_shrink(ctx, plan, desc, static_cast<hipStream_t>(stream), false);
+}
+
+int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {
+    int rc = check_linear(ctx, plan, desc);
+    if (rc != LORA_OK) return rc;
+    if (plan->T == 0) return LORA_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the split-K counters must be zero when the GEMM starts
+    if (choose_gemm(ctx, plan->T, desc->K, desc->N, desc->dtype).variant == kGemmSkinny) {
+        const WorkspaceLayout w = workspace_layout(plan->T, desc->N, plan->r_max, desc->dtype);
+        LORA_HIP(launch_zero_ints(reinterpret_cast<int32_t *>(static_cast<unsigned char *>(desc->workspace) + w.counters_off),
+                                  w.n_tiles, s));
+    }
+    return do_gemm(ctx, plan, desc, s);
+}
+
+int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {
+    int rc = check_linear(ctx, plan, desc);
+    if (rc != LORA_OK) return rc;
+    if (plan->T == 0) return LORA_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool skinny = choose_gemm(ctx, plan->T, desc->K, desc->N, desc->dtype).variant == kGemmSkinny;
+    rc = do_shrink(ctx, plan, desc, s, skinny);
+    if (rc != LORA_OK) return rc;
+    return do_gemm(ctx, plan, desc, s);
+}
+
+const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
+    static thread_local char buf[64];
+    const GemmChoice c = choose_gemm(ctx, T, K, N, dtype);
+    switch (c.variant) {
+        case kGemmSkinny:
+            snprintf(buf, sizeof buf, "skinny_tb%d_ks%d", c.tblk, c.ksplit);
+            break;
+        case kGemmTile64x64:
+            snprintf(buf, sizeof buf, "tile_64x64");
+            break;
+        case kGemmTile128x128:
+            snprintf(buf, sizeof buf, "tile_128x128");
+            break;
+        case kGemmTile256x128:
+            snprintf(buf, sizeof buf, "tile_256x128");
+            break;
+        case kGemmTile256x256:
+            snprintf(buf, sizeof buf, "tile_256x256");
+            break;
+        default:
+            snprintf(buf, sizeof buf, "unknown");
+    }
+    return buf;
+}
+
+const char *lora_strerror(int status) {
+    switch (status) {
+        case LORA_OK:
+            return "ok";
+        case LORA_ERR_INVALID_ARG:
+            return "invalid argument";
+        case LORA_ERR_BAD_ADAPTER_ID:
+            return "adapter id outside [-1, n_adapters)";
+        case LORA_ERR_LENGTH_MISMATCH:
+            return "negative token count or token counts do not add up to T";
+        case LORA_ERR_ADAPTER_NOT_RESIDENT:
+            return "a used adapter is not resident (rank 0 or null weights)";
+        case LORA_ERR_RANK_TOO_LARGE:
+            return "a used adapter's rank exceeds r_max";
+        case LORA_ERR_WORKSPACE_TOO_SMALL:
+            return "plan buffer or workspace too small";
+        case LORA_ERR_ALIGNMENT:
+            return "pointer or row stride not aligned";
+        case LORA_ERR_SHAPE:
+            return "unsupported shape (K, N, leading dimension or rank)";
+        case LORA_ERR_HIP:
+            return "HIP runtime error";
+        case LORA_ERR_PLAN:
+            return "not a valid plan";
+        default:
+            return "unknown status";
+    }
+}
+
+int lora_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

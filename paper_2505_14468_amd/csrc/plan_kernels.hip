@@ -1,0 +1,293 @@
+// Device-side segment / indptr builder: groups the token rows of a batch by adapter.
+//
+// Input is one (adapter id, token count) pair per request, as a batching scheduler hands a
+// batch over (paper section 4.2).  Output is a stable counting sort of the rows by adapter:
+// histogram of rows per adapter -> exclusive scans -> per-request destination -> per-row
+// scatter, plus the derived tables the compute kernels index (per-segment rank prefix, the
+// shrink work list and one record per 8 ranks of the concatenated rank space).
+//
+// All arithmetic is integer, so integer atomics keep the result deterministic.
+#include "kernels.h"
+
+namespace lora {
+namespace {
+
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanWaves = kPlanThreads / 64;
+
+// Exclusive scan of one int per thread over the whole workgroup.  Every thread calls it.
+__device__ int block_exscan(int v, int &total, int *wave_sums) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    __syncthreads();  // wave_sums may still be read from the previous call
+    if (lane == 63) wave_sums[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+        int s = wave_sums[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    total = tot;
+    return base + inc - v;
+}
+
+// perm / row_seg: one thread per original row.
+__device__ void fill_rows(const PlanBuildArgs &p, int start, int stride) {
+    const int T = p.T, R = p.n_req;
+    for (int t = start; t < T; t += stride) {
+        int lo = 0, hi = R;  // first request whose end offset exceeds t
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if (p.tok_off[mid + 1] > t)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int i = lo;
+        const int a = p.req_adapter[i];
+        const int key = a < 0 ? p.n_adapters : a;
+        const int slot = p.req_dst[i] + (t - p.tok_off[i]);
+        p.perm[slot] = t;
+        p.row_seg[slot] = p.key_seg[key];
+    }
+}
+
+// ext_rec: one record per 8 consecutive ranks of the concatenation of all segments' ranks.
+__device__ void fill_ext(const PlanBuildArgs &p, int start, int stride) {
+    const int n_rec = p.scalars[kScExtTotal] >> 3;
+    const int n_seg = p.scalars[kScNSeg];
+    for (int q = start; q < n_rec; q += stride) {
+        const int pel = q << 3;
+        int lo = 0, hi = n_seg;  // first segment whose rank range ends beyond pel
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if (p.seg_ext[mid + 1] > pel)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int s = lo;
+        int4 rec;
+        rec.x = p.seg_adapter[s];
+        rec.y = (p.seg_rank[s] << 16) | (pel - p.seg_ext[s]);
+        rec.z = p.seg_indptr[s];
+        rec.w = p.seg_indptr[s + 1];
+        reinterpret_cast<int4 *>(p.ext_rec)[q] = rec;
+    }
+}
+
+__device__ void write_failed(const PlanBuildArgs &p, int status) {
+    p.scalars[kScNSeg] = 0;
+    p.scalars[kScStatus] = status;
+    p.scalars[kScExtTotal] = 0;
+    p.scalars[kScNUnits] = 0;
+    p.scalars[kScT] = 0;
+    p.seg_indptr[0] = 0;
+    p.seg_ext[0] = 0;
+    p.seg_unit[0] = 0;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildArgs p, int fuse_fill) {
+    __shared__ int wave_sums[4][kPlanWaves];
+    __shared__ int s_status;
+    __shared__ unsigned long long s_sum;
+    const int tid = threadIdx.x;
+    const int R = p.n_req, n_ad = p.n_adapters;
+
+    if (tid == 0) {
+        s_status = 0;
+        s_sum = 0ull;
+    }
+    for (int k = tid; k <= n_ad; k += kPlanThreads) p.hist[k] = 0;
+    __syncthreads();
+
+    // 1. validate the requests, histogram of rows per key (key n_ad = "no adapter")
+    {
+        unsigned long long local = 0ull;
+        int st = 0;
+        for (int i = tid; i < R; i += kPlanThreads) {
+            const int a = p.req_adapter[i], L = p.req_ntok[i];
+            if (a < -1 || a >= n_ad) {
+                st = min(st, kErrBadAdapterId);
+            } else if (L < 0) {
+                st = min(st, kErrLengthMismatch);
+            } else if (L > 0) {
+                local += (unsigned long long)L;
+                atomicAdd(&p.hist[a < 0 ? n_ad : a], L);
+            }
+        }
+        if (st != 0) atomicMin(&s_status, st);
+        if (local != 0ull) atomicAdd(&s_sum, local);
+    }
+    __syncthreads();
+    if (tid == 0 && s_status == 0 && s_sum != (unsigned long long)(unsigned)p.T) s_status = kErrLengthMismatch;
+    __syncthreads();
+    if (s_status != 0) {
+        if (tid == 0) write_failed(p, s_status);
+        return;
+    }
+
+    // 2. first row of every request
+    {
+        int carry = 0;
+        for (int base = 0; base < R; base += kPlanThreads) {
+            const int i = base + tid;
+            const int v = i < R ? p.req_ntok[i] : 0;
+            int tot;
+            const int ex = block_exscan(v, tot, wave_sums[0]);
+            if (i < R) p.tok_off[i] = carry + ex;
+            carry += tot;
+        }
+        if (tid == 0) p.tok_off[R] = carry;
+    }
+
+    // 3. segments = keys with rows, in ascending key order; four prefix sums at once
+    int c_seg = 0, c_row = 0, c_ext = 0, c_unit = 0;
+    {
+        int st = 0;
+        for (int base = 0; base <= n_ad; base += kPlanThreads) {
+            const int k = base + tid;
+            const int h = k <= n_ad ? p.hist[k] : 0;
+            const int flag = h > 0 ? 1 : 0;
+            int rk = 0, units = 0;
+            if (flag && k < n_ad) {
+                rk = p.rank[k];
+                if (rk <= 0) {
+                    st = min(st, kErrNotResident);
+                    rk = 0;
+                } else if (rk & 7) {
+                    st = min(st, kErrShape);
+                    rk = 0;
+                } else if (rk > p.r_max) {
+                    st = min(st, kErrRankTooLarge);
+                    rk = 0;
+                }
+                units = (h + kShrinkRows - 1) / kShrinkRows;
+            }
+            int t_seg, t_row, t_ext, t_unit;
+            const int e_seg = block_exscan(flag, t_seg, wave_sums[0]);
+            const int e_row = block_exscan(h, t_row, wave_sums[1]);
+            const int e_ext = block_exscan(rk, t_ext, wave_sums[2]);
+            const int e_unit = block_exscan(units, t_unit, wave_sums[3]);
+            if (flag) {
+                const int s = c_seg + e_seg;
+                p.seg_adapter[s] = k < n_ad ? k : -1;
+                p.seg_indptr[s] = c_row + e_row;
+                p.seg_rank[s] = rk;
+                p.seg_ext[s] = c_ext + e_ext;
+                p.seg_unit[s] = c_unit + e_unit;
+                p.cursor[k] = c_row + e_row;
+                p.key_seg[k] = s;
+            } else if (k <= n_ad) {
+                p.key_seg[k] = -1;
+            }
+            c_seg += t_seg;
+            c_row += t_row;
+            c_ext += t_ext;
+            c_unit += t_unit;
+        }
+        if (st != 0) atomicMin(&s_status, st);
+    }
+    __syncthreads();
+    if (s_status != 0) {
+        if (tid == 0) write_failed(p, s_status);
+        return;
+    }
+    if (tid == 0) {
+        p.seg_indptr[c_seg] = c_row;
+        p.seg_ext[c_seg] = c_ext;
+        p.seg_unit[c_seg] = c_unit;
+        p.scalars[kScNSeg] = c_seg;
+        p.scalars[kScStatus] = 0;
+        p.scalars[kScExtTotal] = c_ext;
+        p.scalars[kScNUnits] = c_unit;
+        p.scalars[kScT] = c_row;
+    }
+    __syncthreads();
+
+    // 4. first slot of every request: requests of one key keep their order (stable).
+    //    One wave walks the requests 64 at a time; lanes with the same key are ranked
+    //    against each other with cross-lane reads, then the running slot of each key moves on.
+    if (tid < 64) {
+        volatile int32_t *cur = p.cursor;
+        const int lane = tid;
+        for (int base = 0; base < R; base += 64) {
+            const int i = base + lane;
+            const bool valid = i < R;
+            const int a = valid ? p.req_adapter[i] : 0;
+            const int L = valid ? p.req_ntok[i] : 0;
+            const int key = valid ? (a < 0 ? n_ad : a) : -2;
+            int off = 0;
+            bool last = true;
+            for (int l2 = 0; l2 < 64; ++l2) {
+                const int k2 = __shfl(key, l2);
+                const int L2 = __shfl(L, l2);
+                if (k2 == key) {
+                    if (l2 < lane)
+                        off += L2;
+                    else if (l2 > lane)
+                        last = false;
+                }
+            }
+            int b = 0;
+            if (valid) {
+                b = cur[key];
+                p.req_dst[i] = b + off;
+            }
+            __threadfence();  // every lane has read its key's running slot before any lane moves one
+            if (valid && last) cur[key] = b + off + L;
+            __threadfence();
+        }
+    }
+    __syncthreads();
+
+    if (fuse_fill) {
+        fill_rows(p, tid, kPlanThreads);
+        fill_ext(p, tid, kPlanThreads);
+    }
+}
+
+__global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
+    if (p.scalars[kScStatus] != 0) return;
+    const int start = blockIdx.x * 256 + threadIdx.x;
+    const int stride = gridDim.x * 256;
+    fill_rows(p, start, stride);
+    fill_ext(p, start, stride);
+}
+
+__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t *ptr, int32_t count) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < count) ptr[i] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream) {
+    hipLaunchKernelGGL(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, a, fuse_fill ? 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (!fuse_fill) {
+        long work = a.T > (long)a.ext_cap ? (long)a.T : (long)a.ext_cap;
+        int grid = (int)((work + 255) / 256);
+        if (grid < 1) grid = 1;
+        if (grid > 2048) grid = 2048;
+        hipLaunchKernelGGL(plan_fill_kernel, dim3(grid), dim3(256), 0, stream, a);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_zero_ints(int32_t *ptr, int32_t count, hipStream_t stream) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_ints_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, ptr, count);
+    return hipGetLastError();
+}
+
+}  // namespace lora

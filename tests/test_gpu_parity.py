@@ -1,0 +1,221 @@
+"""GPU parity of the layer (steps a2-a4) against the fp64 CPU oracle, element by element,
+through the C ABI.  Tolerance: max |Y_gpu - Y_oracle| <= 2e-2 * RMS(Y_oracle) for bf16 inputs
+with fp32 accumulation, 1e-5 * RMS for the fp32 configuration."""
+import numpy as np
+import pytest
+
+from workloads import make_custom, make_workload, same_adapter_decode, to_f64
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = {"tile_128x128": 0, "tile_256x128": 1, "tile_256x256": 2, "tile_64x64": 3, "skinny": 4}
+
+
+def _mixed_batch(seed, R, n_ad, max_len, with_none=True, zero_len=True):
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(-1 if with_none else 0, n_ad, size=R)
+    L = rng.integers(0 if zero_len else 1, max_len + 1, size=R)
+    return ids, L
+
+
+def test_config0_fp32_all_tile_variants():
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
+    wl = make_workload(0)
+    for name in ("tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256", None):
+        ctx().set_option("gemm_variant", VARIANTS[name] if name else -1)
+        Y = gpu_linear(wl)
+        e = check_against_oracle(wl, Y)
+        print(f"config0 fp32 {name}: err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
+@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tile_kernels_ragged_multi_tile(variant, dtype):
+    """Several tiles in both directions, ragged tails in T, N and K, mixed ranks, rows without
+    an adapter, zero-length requests; host-built and device-built plans."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
+    ids, L = _mixed_batch(3, R=37, n_ad=6, max_len=24)
+    wl = make_custom(seed=31, dtype=dtype, K=328, N=300, ranks=(8, 16, 64, 32, 8, 24), scales=(2.0, 0.5, 1.0, 0.25, 1.5, 1.0),
+                     req_adapter=ids, req_ntok=L, name=f"ragged_{variant}_{dtype}")
+    assert wl.T > 256
+    ctx().set_option("gemm_variant", VARIANTS[variant])
+    for device_plan in (False, True):
+        Y = gpu_linear(wl, device_plan=device_plan)
+        e = check_against_oracle(wl, Y)
+    print(f"{wl.name}: T={wl.T} err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
+@pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
+def test_skinny_kernel_row_counts(T):
+    """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, B
+    rng = np.random.default_rng(T)
+    n_ad = 12
+    ids = rng.integers(-1, n_ad, size=T)
+    wl = make_custom(seed=40 + T, dtype="bf16", K=520, N=200, ranks=rng.choice([8, 16, 32], size=n_ad),
+                     scales=rng.choice([0.5, 1.0, 2.0], size=n_ad), req_adapter=ids, req_ntok=np.ones(T, int),
+                     name=f"skinny_T{T}")
+    assert B.lora_gemm_kernel_name(ctx().handle, T, 520, 200, B.LORA_DTYPE_BF16).startswith("skinny")
+    for ks in (1, 2, 3, 8, -1):
+        ctx().set_option("skinny_ksplit", ks)
+        Y = gpu_linear(wl, device_plan=(ks == 2))
+        e = check_against_oracle(wl, Y)
+    print(f"{wl.name}: err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
+def test_skinny_equals_tile_path_within_tolerance_and_tile_handles_small_T():
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
+    ids, L = _mixed_batch(8, R=20, n_ad=5, max_len=6)
+    wl = make_custom(seed=77, dtype="bf16", K=1024, N=512, ranks=(16, 8, 32, 16, 64), scales=(1.0, 2.0, 0.5, 1.0, 1.0),
+                     req_adapter=ids, req_ntok=L, name="small_T_both_paths")
+    assert wl.T <= 128
+    ctx().set_option("skinny_max_rows", 0)  # force the tiled kernel
+    check_against_oracle(wl, gpu_linear(wl))
+    reset_options()
+    check_against_oracle(wl, gpu_linear(wl))
+
+
+def test_shrink_stage_matches_oracle_intermediate():
+    """Step a2 alone: V = s_a X A_a in the plan's slot order (bf16 path: rounded once to bf16)."""
+    import torch
+    from gpu_common import ctx, gpu_linear, rt
+    from oracle import oracle_workload, plan_reference
+    for dtype, tol in (("bf16", 2 ** -8), ("f32", 1e-5)):
+        ids, L = _mixed_batch(12, R=30, n_ad=5, max_len=90)
+        wl = make_custom(seed=5, dtype=dtype, K=456, N=64, ranks=(8, 72, 16, 128, 32), scales=(2.0, 0.5, 1.0, 0.25, 1.5),
+                         req_adapter=ids, req_ntok=L, name=f"shrink_{dtype}")
+        _, (X, W0, table, pl, Y) = gpu_linear(wl, stage="shrink", return_all=True)
+        c = ctx()
+        ws = rt.workspace(wl.T, 64, wl.r_max, X.dtype, X.device)
+        rt.linear(c, pl, X, W0, table, Y=Y, ws=ws, stage="shrink")
+        torch.cuda.synchronize()
+        es = 2 if dtype == "bf16" else 4
+        vbytes = ws[: wl.T * wl.r_max * es]
+        Vg = vbytes.view(torch.bfloat16 if dtype == "bf16" else torch.float32).reshape(wl.T, wl.r_max)
+        Vg = to_f64(rt.bits_from_tensor(Vg))
+        _, Vo = oracle_workload(wl, return_v=True)
+        ref = plan_reference(wl.req_adapter, wl.req_ntok, wl.ranks)
+        ra = wl.row_adapter()
+        worst = 0.0
+        for slot, row in enumerate(ref["perm"]):
+            a = ra[row]
+            if a < 0:
+                continue
+            r = int(wl.ranks[a])
+            want = float(wl.scales[a]) * Vo[row, :r]
+            scale = max(np.abs(want).max(), 1e-3)
+            worst = max(worst, np.abs(Vg[slot, :r] - want).max() / scale)
+        assert worst <= tol, (dtype, worst)
+        print(f"shrink {dtype}: worst rel err {worst:.2e}", flush=True)
+
+
+def test_zero_b_reproduces_base_and_no_table_equals_all_minus_one():
+    """Zero-B adapters give exactly the backbone product; so do tbl = NULL and ids = -1 (bitwise on GPU)."""
+    import torch
+    from gpu_common import ctx, rt
+    from paper_2505_14468_amd.runtime import tensor_from_bits, bits_from_tensor
+    c = ctx()
+    for T in (40, 400):
+        ids = np.arange(10) % 4
+        L = np.full(10, T // 10)
+        wl = make_custom(seed=9, dtype="bf16", K=256, N=192, ranks=(8, 16, 8, 32), scales=(1.0,) * 4,
+                         req_adapter=ids, req_ntok=L)
+        X, W0, table = rt.upload_workload(wl, 0, c.device)
+        for b in table.B:
+            b.zero_()
+        pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks)
+        Y0 = bits_from_tensor(rt.linear(c, pl, X, W0, table))
+        Y1 = bits_from_tensor(rt.linear(c, pl, X, W0, None))
+        pl2 = rt.plan(c, np.full(10, -1), wl.req_ntok, wl.ranks)
+        Y2 = bits_from_tensor(rt.linear(c, pl2, X, W0, table))
+        torch.cuda.synchronize()
+        assert np.array_equal(Y1, Y2)
+        assert np.array_equal(to_f64(Y0), to_f64(Y1))  # +0 contributions: equal as values
+
+
+def test_determinism_w0_untouched_and_permutation_invariance():
+    import torch
+    from gpu_common import ctx, rt, reset_options
+    from paper_2505_14468_amd.runtime import bits_from_tensor
+    c = ctx()
+    for T_scale, opts in ((1, {}), (12, {})):
+        rng = np.random.default_rng(T_scale)
+        R, n_ad = 24, 6
+        ids = rng.integers(-1, n_ad, size=R)
+        L = rng.integers(1, 4, size=R) * T_scale
+        wl = make_custom(seed=123, dtype="bf16", K=512, N=384, ranks=(8, 16, 32, 64, 16, 8), scales=(1.0, 2.0, 0.5, 1.0, 1.0, 2.0),
+                         req_adapter=ids, req_ntok=L)
+        X, W0, table = rt.upload_workload(wl, 0, c.device)
+        frozen = [t.clone() for t in [W0, X] + table.A + table.B]
+        pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks)
+        Y1 = bits_from_tensor(rt.linear(c, pl, X, W0, table))
+        Y2 = bits_from_tensor(rt.linear(c, pl, X, W0, table))
+        assert np.array_equal(Y1, Y2), "run-to-run results differ"
+        for before, after in zip(frozen, [W0, X] + table.A + table.B):
+            assert torch.equal(before, after), "an input tensor was written"
+        # permute the requests (and X's row blocks): output row blocks permute with them
+        off = np.concatenate([[0], np.cumsum(L)])
+        order = rng.permutation(R)
+        rows = np.concatenate([np.arange(off[i], off[i + 1]) for i in order])
+        Xp = X[torch.from_numpy(rows).to(c.device)].contiguous()
+        plp = rt.plan(c, ids[order], L[order], wl.ranks)
+        Yp = bits_from_tensor(rt.linear(c, plp, Xp, W0, table))
+        assert np.array_equal(Yp, Y1[rows]), "a row's result depends on the order of the batch"
+    reset_options()
+
+
+def test_p5_exact_integers_on_gpu():
+    """Small integers, power-of-two scales: every product and sum is exact in bf16 x bf16 -> fp32,
+    so the GPU must equal the oracle exactly (|Y| stays representable in bf16)."""
+    from gpu_common import gpu_linear
+    from oracle import oracle_workload
+    for dtype in ("bf16", "f32"):
+        wl = make_custom(seed=3, dtype=dtype, K=16, N=8, ranks=(8, 8), scales=(0.5, 0.25),
+                         req_adapter=(0, 1, -1, 0), req_ntok=(2, 3, 1, 2), integer_valued=True)
+        Y = gpu_linear(wl)
+        Yo = oracle_workload(wl)
+        if dtype == "bf16":  # one rounding of the exact result to bf16
+            from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+            Yo = f32_from_bf16_bits(bf16_bits_from_f32(Yo.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(Y, Yo), dtype
+
+
+def test_strided_inputs_and_adapter_eviction():
+    """ld > width for X, W0 and Y; a NULL table slot that the batch uses is reported, not dereferenced."""
+    import torch
+    from gpu_common import ctx, rt, check_against_oracle, B
+    from paper_2505_14468_amd.runtime import bits_from_tensor
+    c = ctx()
+    wl = make_custom(seed=55, dtype="bf16", K=128, N=96, ranks=(8, 16), scales=(1.0, 2.0),
+                     req_adapter=(0, 1, 0), req_ntok=(30, 50, 70))
+    X, W0, table = rt.upload_workload(wl, 0, c.device)
+    Xs = torch.zeros((wl.T, 128 + 64), dtype=X.dtype, device=c.device)
+    Xs[:, :128] = X
+    Ws = torch.zeros((96, 128 + 8), dtype=X.dtype, device=c.device)
+    Ws[:, :128] = W0
+    Ys = torch.full((wl.T, 96 + 32), 3.0, dtype=X.dtype, device=c.device)
+    pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks)
+    rt.linear(c, pl, Xs[:, :128], Ws[:, :128], table, Y=Ys[:, :96])
+    torch.cuda.synchronize()
+    check_against_oracle(wl, to_f64(bits_from_tensor(Ys[:, :96])))
+    assert bool((Ys[:, 96:] == 3.0).all()), "wrote outside Y's N columns"
+    # evict adapter 1 after planning: the kernels skip it and record ADAPTER_NOT_RESIDENT
+    table.set_slot(1, None, None)
+    rt.linear(c, pl, X, W0, table)
+    status, _ = pl.status(c)
+    assert status == B.LORA_ERR_ADAPTER_NOT_RESIDENT
+
+
+def test_empty_batch_is_a_noop():
+    import torch
+    from gpu_common import ctx, rt
+    c = ctx()
+    pl = rt.plan(c, [0, 1], [0, 0], [8, 8])
+    X = torch.zeros((0, 64), dtype=torch.bfloat16, device=c.device)
+    W0 = torch.zeros((32, 64), dtype=torch.bfloat16, device=c.device)
+    Y = rt.linear(c, pl, X, W0, None)
+    torch.cuda.synchronize()
+    assert Y.shape == (0, 32)
