@@ -70,6 +70,7 @@ typedef enum lora_status {
 #define LORA_MAX_REQUESTS 65536   /* requests per batch                                  */
 #define LORA_MAX_ADAPTERS 65536   /* adapter slots in a table                            */
 #define LORA_MAX_RANK 512         /* rank of one adapter; ranks are multiples of 8       */
+#define LORA_WORKSPACE_HEADER_BYTES 16384 /* start of the workspace: split-K arrival counters */
 
 /*
  * Adapter pointer table.  A table, not one packed tensor, because adapters are
@@ -129,7 +130,10 @@ typedef struct lora_linear_desc {
     void *Y;                /* device [T, ldy]; must not alias X, W0 or the adapters        */
     int64_t ldy;            /* >= N, multiple of 8 (bf16) or 4 (fp32)                       */
     const lora_adapter_table_t *tbl; /* host pointer; NULL = backbone product only         */
-    void *workspace;        /* device, 256-byte aligned, lora_linear_workspace_bytes() big  */
+    void *workspace;        /* device, 256-byte aligned, lora_linear_workspace_bytes() big;
+                               its first LORA_WORKSPACE_HEADER_BYTES must be zero on first
+                               use (clear them once after allocating); the kernels keep
+                               them zero from then on                                       */
     size_t workspace_bytes;
 } lora_linear_desc;
 
@@ -194,7 +198,10 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 /* ---- steps a2-a4: the layer --------------------------------------------- */
 
 /* Device bytes lora_linear needs in desc->workspace for T rows, N outputs and
- * V row stride r_max (holds V, split-K partial tiles and their counters). */
+ * V row stride r_max: a header of split-K arrival counters
+ * (LORA_WORKSPACE_HEADER_BYTES, zero between calls), V, and split-K partial
+ * tiles.  One workspace may serve calls of different shapes as long as it is
+ * big enough for each and the calls do not overlap in time. */
 size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype);
 
 /* a2, shrink: V[slot, :r_a] = s_a * X[perm[slot], :] A_a for every row with an
@@ -212,6 +219,17 @@ int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
  * after enqueueing.  Errors (all found before the first launch): INVALID_ARG,
  * PLAN, SHAPE, ALIGNMENT, WORKSPACE_TOO_SMALL; HIP if a launch fails. */
 int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
+
+/* Profiling mode, for benchmarks: between lora_profile_begin() and
+ * lora_profile_end() every kernel the library launches through `ctx` is
+ * bracketed by its own pair of HIP events (at most max_launches per kernel
+ * kind; later launches run untimed).  lora_profile_end() synchronises `stream`
+ * and writes, for the four kernel kinds in the order {plan segments, plan
+ * fill, shrink, GEMM+expand}, the average execution time in microseconds into
+ * avg_us[4] (HOST) and the number of timed launches into counts[4] (HOST).
+ * Errors: INVALID_ARG, HIP. */
+int lora_profile_begin(lora_ctx *ctx, int max_launches);
+int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_t *counts);
 
 /* Name of the GEMM kernel variant lora_gemm_expand() would launch for this
  * problem ("skinny_tb4_ks4", "tile_128x128", ...), for reports.  Host only. */

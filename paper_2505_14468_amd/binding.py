@@ -30,11 +30,13 @@ LORA_ERR_ALIGNMENT = -7
 LORA_ERR_SHAPE = -8
 LORA_ERR_HIP = -9
 LORA_ERR_PLAN = -10
+LORA_WORKSPACE_HEADER_BYTES = 16384
 
 EXPORTS = [
     "lora_ctx_create", "lora_ctx_destroy", "lora_ctx_set_option",
     "lora_plan_validate", "lora_plan_bytes", "lora_plan", "lora_plan_device", "lora_plan_status",
     "lora_linear_workspace_bytes", "lora_shrink", "lora_gemm_expand", "lora_linear",
+    "lora_profile_begin", "lora_profile_end",
     "lora_gemm_kernel_name", "lora_strerror", "lora_last_hip_error",
 ]
 
@@ -96,14 +98,13 @@ def lib():
         L.lora_linear_workspace_bytes.restype = C.c_size_t
         for name in ("lora_shrink", "lora_gemm_expand", "lora_linear"):
             getattr(L, name).argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(lora_linear_desc), C.c_void_p]
+        L.lora_profile_begin.argtypes = [C.c_void_p, C.c_int]
+        L.lora_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), i32p]
         L.lora_gemm_kernel_name.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
         L.lora_gemm_kernel_name.restype = C.c_char_p
         L.lora_strerror.argtypes = [C.c_int]
         L.lora_strerror.restype = C.c_char_p
         L.lora_last_hip_error.restype = C.c_int
-        for name in EXPORTS:
-            if getattr(L, name).restype is C.c_int or name in ("lora_ctx_create",):
-                pass
         _lib = L
     return _lib
 
@@ -230,6 +231,21 @@ def lora_gemm_expand(ctx, plan, desc, stream: int, *, raw: bool = False):
 
 def lora_linear(ctx, plan, desc, stream: int, *, raw: bool = False):
     return _stage("lora_linear", ctx, plan, desc, stream, raw)
+
+
+PROFILE_KINDS = ("plan_segments", "plan_fill", "shrink", "gemm_expand")
+
+
+def lora_profile_begin(ctx, max_launches: int) -> None:
+    _check(lib().lora_profile_begin(C.c_void_p(ctx), int(max_launches)), "lora_profile_begin")
+
+
+def lora_profile_end(ctx, stream: int) -> dict:
+    """{kind: (average microseconds, timed launches)} for the four kernel kinds."""
+    avg = (C.c_double * 4)()
+    cnt = (C.c_int32 * 4)()
+    _check(lib().lora_profile_end(C.c_void_p(ctx), C.c_void_p(stream), avg, cnt), "lora_profile_end")
+    return {k: (float(avg[i]), int(cnt[i])) for i, k in enumerate(PROFILE_KINDS)}
 
 
 def lora_gemm_kernel_name(ctx, T: int, K: int, N: int, dtype: int) -> str:

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p, int
 }
 
 template <int TBLK>
-hipError_t launch_sk(const GemmArgs &a, hipStream_t stream) {
+hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
     const int n_tiles = (a.N + kSkinnyBN - 1) / kSkinnyBN;
     const size_t smem = 2 * kSkStageBytes + sizeof(SkTable);
     auto kern = gemm_skinny_kernel<TBLK>;
@@ -261,23 +261,22 @@ hipError_t launch_sk(const GemmArgs &a, hipStream_t stream) {
         attr_set = true;
     }
     const long grid = (long)((n_tiles + 7) / 8) * 8 * a.ksplit;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kSkThreads), smem, stream, a, n_tiles);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3((unsigned)grid), dim3(kSkThreads), smem, stream, timer, a, n_tiles);
 }
 
 }  // namespace
 
-hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream) {
+hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer) {
     if (a.T <= 0 || a.N <= 0) return hipSuccess;
     switch (tblk) {
         case 1:
-            return launch_sk<1>(a, stream);
+            return launch_sk<1>(a, stream, timer);
         case 2:
-            return launch_sk<2>(a, stream);
+            return launch_sk<2>(a, stream, timer);
         case 4:
-            return launch_sk<4>(a, stream);
+            return launch_sk<4>(a, stream, timer);
         case 8:
-            return launch_sk<8>(a, stream);
+            return launch_sk<8>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

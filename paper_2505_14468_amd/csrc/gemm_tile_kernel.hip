@@ -259,7 +259,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 }
 
 template <typename E, int BM, int BN, int WM, int WN>
-hipError_t launch_tile(const GemmArgs &a, hipStream_t stream) {
+hipError_t launch_tile(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
     const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const long total = (long)tiles_m * tiles_n;
     if (total <= 0) return hipSuccess;
@@ -274,21 +274,20 @@ hipError_t launch_tile(const GemmArgs &a, hipStream_t stream) {
     }
     const long grid = ((total + 7) / 8) * 8;
     const int group_m = 8;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, a, tiles_m, tiles_n, group_m);
-    return hipGetLastError();
+    return launch_kernel(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, timer, a, tiles_m, tiles_n, group_m);
 }
 
 template <typename E>
-hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream) {
+hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, const KernelTimer *timer) {
     switch (variant) {
         case kGemmTile64x64:
-            return launch_tile<E, 64, 64, 2, 2>(a, stream);
+            return launch_tile<E, 64, 64, 2, 2>(a, stream, timer);
         case kGemmTile128x128:
-            return launch_tile<E, 128, 128, 2, 2>(a, stream);
+            return launch_tile<E, 128, 128, 2, 2>(a, stream, timer);
         case kGemmTile256x128:
-            return launch_tile<E, 256, 128, 4, 2>(a, stream);
+            return launch_tile<E, 256, 128, 4, 2>(a, stream, timer);
         case kGemmTile256x256:
-            return launch_tile<E, 256, 256, 4, 2>(a, stream);
+            return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }
@@ -296,8 +295,8 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream) {
 
 }  // namespace
 
-hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream) {
-    return dtype == 1 ? launch_variant<__bf16>(a, variant, stream) : launch_variant<float>(a, variant, stream);
+hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer) {
+    return dtype == 1 ? launch_variant<__bf16>(a, variant, stream, timer) : launch_variant<float>(a, variant, stream, timer);
 }
 
 }  // namespace lora

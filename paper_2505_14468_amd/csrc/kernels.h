@@ -1,5 +1,6 @@
 // Host-side launch interface between lora_api.hip and the kernel translation units.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -31,9 +32,26 @@ struct PlanBuildArgs {
     int32_t *scalars;      // [8]
 };
 
+// Optional pair of events recorded tightly around one kernel (profiling mode): the elapsed time
+// between them is the kernel's own execution time, as a profiler reports it.
+struct KernelTimer {
+    hipEvent_t start, stop;
+};
+
+// Launch with or without a timer.
+template <typename F, typename... Args>
+inline hipError_t launch_kernel(F kernel, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const KernelTimer *timer,
+                                Args... args) {
+    if (timer != nullptr)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, stream, timer->start, timer->stop, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, smem, stream, args...);
+    return hipGetLastError();
+}
+
 // Enqueues the segment builder (one or two kernels).  `fuse_fill`: the single
-// workgroup of the first kernel also fills the T-sized arrays.
-hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream);
+// workgroup of the first kernel also fills the T-sized arrays.  timers: [0] segments, [1] fill.
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream, const KernelTimer *timers);
 
 struct ShrinkArgs {
     PlanView plan;
@@ -47,13 +65,8 @@ struct ShrinkArgs {
     int32_t r_max;
     int32_t rank_groups;   // ceil(r_max / kShrinkRanks)
     int32_t max_units;     // upper bound of work units (grid = max_units * rank_groups)
-    int32_t *zero_ptr;     // optional: ints to clear (split-K counters), may be null
-    int32_t zero_count;
 };
-hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream);
-
-// Clears `count` ints (used instead of a memset node so that callers may capture the stream).
-hipError_t launch_zero_ints(int32_t *ptr, int32_t count, hipStream_t stream);
+hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 
 struct GemmArgs {
     PlanView plan;
@@ -82,12 +95,15 @@ enum GemmVariant {
     kGemmVariantCount
 };
 
-hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream);
-hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream);
+hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
+hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
 
 // Geometry of the skinny kernel shared with the host (workspace sizing).
 constexpr int kSkinnyBN = 64;        // output columns per workgroup
 constexpr int kSkinnyMaxRows = 128;  // rows it accepts
 constexpr int kSkinnyMaxKSplit = 8;
+// The workspace starts with a header of split-K arrival counters, one per 64-column tile.  They
+// are zero between calls: the caller clears the header once, the kernels restore zero themselves.
+constexpr int kWorkspaceHeaderInts = 4096;
 
 }  // namespace lora

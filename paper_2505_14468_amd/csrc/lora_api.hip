@@ -33,6 +33,8 @@ int hip_fail(hipError_t e) {
         if (e_ != hipSuccess) return hip_fail(e_); \
     } while (0)
 
+enum ProfKind { kProfPlanSegments = 0, kProfPlanFill = 1, kProfShrink = 2, kProfGemm = 3, kProfKinds = 4 };
+
 constexpr int kRingSlots = 4;
 constexpr size_t kRingSlotInts = 2 * (size_t)LORA_MAX_REQUESTS + LORA_MAX_ADAPTERS;
 
@@ -54,6 +56,12 @@ struct lora_ctx {
     int opt_skinny_ksplit = -1;
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
+    // profiling mode: event pairs recorded tightly around each kernel
+    bool prof_on = false;
+    int prof_cap = 0;
+    int prof_used[kProfKinds] = {};
+    hipEvent_t *prof_start[kProfKinds] = {};
+    hipEvent_t *prof_stop[kProfKinds] = {};
 };
 
 namespace {
@@ -74,6 +82,30 @@ struct DeviceGuard {
         if (changed) (void)hipSetDevice(prev);
     }
 };
+
+// Next event pair of a kernel kind while profiling (null otherwise, or when the pairs ran out).
+bool next_timer(lora_ctx *ctx, int kind, KernelTimer *out) {
+    if (!ctx->prof_on || ctx->prof_used[kind] >= ctx->prof_cap) return false;
+    const int i = ctx->prof_used[kind]++;
+    out->start = ctx->prof_start[kind][i];
+    out->stop = ctx->prof_stop[kind][i];
+    return true;
+}
+
+void free_profiler(lora_ctx *ctx) {
+    for (int k = 0; k < kProfKinds; ++k) {
+        for (int i = 0; i < ctx->prof_cap; ++i) {
+            if (ctx->prof_start[k] && ctx->prof_start[k][i]) (void)hipEventDestroy(ctx->prof_start[k][i]);
+            if (ctx->prof_stop[k] && ctx->prof_stop[k][i]) (void)hipEventDestroy(ctx->prof_stop[k][i]);
+        }
+        delete[] ctx->prof_start[k];
+        delete[] ctx->prof_stop[k];
+        ctx->prof_start[k] = ctx->prof_stop[k] = nullptr;
+        ctx->prof_used[k] = 0;
+    }
+    ctx->prof_cap = 0;
+    ctx->prof_on = false;
+}
 
 // ---- plan storage layout ------------------------------------------------------------------------
 struct PlanLayout {
@@ -194,7 +226,9 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.scalars = base + L.scalars;
     const int fused_rows = ctx->opt_plan_fused_rows >= 0 ? ctx->opt_plan_fused_rows : 4096;
     const bool fuse = T <= fused_rows && L.ext_cap <= 8192;
-    LORA_HIP(launch_plan_build(a, fuse, stream));
+    KernelTimer timers[2];
+    const bool timed = next_timer(ctx, kProfPlanSegments, &timers[0]) && (fuse || next_timer(ctx, kProfPlanFill, &timers[1]));
+    LORA_HIP(launch_plan_build(a, fuse, stream, timed ? timers : nullptr));
 
     out->T = T;
     out->n_req = n_req;
@@ -237,8 +271,9 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
     GemmChoice c{kGemmTile128x128, 0, 1};
     const int max_rows = ctx && ctx->opt_skinny_max_rows >= 0 ? ctx->opt_skinny_max_rows : kSkinnyMaxRows;
     int forced = ctx ? ctx->opt_gemm_variant : -1;
-    if (forced == kGemmSkinny && (dtype != LORA_DTYPE_BF16 || T > kSkinnyMaxRows)) forced = -1;
-    const bool skinny = forced == kGemmSkinny || (forced < 0 && dtype == LORA_DTYPE_BF16 && T <= max_rows && T <= kSkinnyMaxRows);
+    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && (N + kSkinnyBN - 1) / kSkinnyBN <= kWorkspaceHeaderInts;
+    if (forced == kGemmSkinny && !fits) forced = -1;
+    const bool skinny = forced == kGemmSkinny || (forced < 0 && fits && T <= max_rows);
     if (skinny) {
         c.variant = kGemmSkinny;
         c.tblk = skinny_tblk(T);
@@ -281,7 +316,7 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 }
 
 struct WorkspaceLayout {
-    size_t v_off, counters_off, partials_off, total;
+    size_t counters_off, v_off, partials_off, total;
     int n_tiles;
 };
 
@@ -290,14 +325,14 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t N, int32_t r_max, int32_t dt
     const size_t es = dtype == LORA_DTYPE_BF16 ? 2 : 4;
     w.n_tiles = (N + kSkinnyBN - 1) / kSkinnyBN;
     size_t off = 0;
+    w.counters_off = off;  // header: split-K arrival counters, zero between calls
+    off += (size_t)kWorkspaceHeaderInts * sizeof(int32_t);
     w.v_off = off;
     off = align_up(off + (size_t)T * (size_t)r_max * es, 256);
-    w.counters_off = off;
-    off = align_up(off + (size_t)w.n_tiles * sizeof(int32_t), 256);
     w.partials_off = off;
-    if (dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && T > 0)
+    if (dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && T > 0 && w.n_tiles <= kWorkspaceHeaderInts)
         off = align_up(off + (size_t)w.n_tiles * kSkinnyMaxKSplit * skinny_tblk(T) * 256 * sizeof(float4), 256);
-    w.total = off < 256 ? 256 : off;
+    w.total = off;
     return w;
 }
 
@@ -347,14 +382,10 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
 }
 
-int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream, bool zero_counters) {
+int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
+    if (!has_adapters(plan, d)) return LORA_OK;
     const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
-    int32_t *counters = reinterpret_cast<int32_t *>(ws + w.counters_off);
-    if (!has_adapters(plan, d)) {
-        if (zero_counters) LORA_HIP(launch_zero_ints(counters, w.n_tiles, stream));
-        return LORA_OK;
-    }
     ShrinkArgs a;
     a.plan = view_of(plan);
     a.X = d->X;
@@ -370,10 +401,9 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
     a.max_units = (int32_t)(plan->T / kShrinkRows + seg_bound2);
-    a.zero_ptr = zero_counters ? counters : nullptr;
-    a.zero_count = zero_counters ? w.n_tiles : 0;
-    (void)ctx;
-    LORA_HIP(launch_shrink(a, d->dtype, stream));
+    KernelTimer timer;
+    const bool timed = next_timer(ctx, kProfShrink, &timer);
+    LORA_HIP(launch_shrink(a, d->dtype, stream, timed ? &timer : nullptr));
     return LORA_OK;
 }
 
@@ -399,10 +429,12 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.counters = reinterpret_cast<int32_t *>(ws + w.counters_off);
     const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
     a.ksplit = c.ksplit;
+    KernelTimer timer;
+    const bool timed = next_timer(ctx, kProfGemm, &timer);
     if (c.variant == kGemmSkinny)
-        LORA_HIP(launch_gemm_skinny(a, c.tblk, stream));
+        LORA_HIP(launch_gemm_skinny(a, c.tblk, stream, timed ? &timer : nullptr));
     else
-        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream));
+        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
 }
 
@@ -451,6 +483,7 @@ int lora_ctx_destroy(lora_ctx *ctx) {
         }
     }
     if (ctx->ring) (void)hipHostFree(ctx->ring);
+    free_profiler(ctx);
     delete ctx;
     return LORA_OK;
 }
@@ -556,7 +589,7 @@ int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
     if (plan->T == 0) return LORA_OK;
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return hip_fail(guard.err);
-    return do_shrink(ctx, plan, desc, static_cast<hipStream_t>(stream), false);
+    return do_shrink(ctx, plan, desc, static_cast<hipStream_t>(stream));
 }
 
 int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {
@@ -566,12 +599,6 @@ int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return hip_fail(guard.err);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // the split-K counters must be zero when the GEMM starts
-    if (choose_gemm(ctx, plan->T, desc->K, desc->N, desc->dtype).variant == kGemmSkinny) {
-        const WorkspaceLayout w = workspace_layout(plan->T, desc->N, plan->r_max, desc->dtype);
-        LORA_HIP(launch_zero_ints(reinterpret_cast<int32_t *>(static_cast<unsigned char *>(desc->workspace) + w.counters_off),
-                                  w.n_tiles, s));
-    }
     return do_gemm(ctx, plan, desc, s);
 }
 
@@ -582,10 +609,53 @@ int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
     DeviceGuard guard(ctx->device);
     if (guard.err != hipSuccess) return hip_fail(guard.err);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool skinny = choose_gemm(ctx, plan->T, desc->K, desc->N, desc->dtype).variant == kGemmSkinny;
-    rc = do_shrink(ctx, plan, desc, s, skinny);
+    rc = do_shrink(ctx, plan, desc, s);
     if (rc != LORA_OK) return rc;
     return do_gemm(ctx, plan, desc, s);
+}
+
+int lora_profile_begin(lora_ctx *ctx, int max_launches) {
+    if (!ctx || max_launches <= 0 || max_launches > (1 << 20)) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    if (max_launches > ctx->prof_cap) {
+        free_profiler(ctx);
+        for (int k = 0; k < kProfKinds; ++k) {
+            ctx->prof_start[k] = new (std::nothrow) hipEvent_t[max_launches]();
+            ctx->prof_stop[k] = new (std::nothrow) hipEvent_t[max_launches]();
+            if (!ctx->prof_start[k] || !ctx->prof_stop[k]) return LORA_ERR_INVALID_ARG;
+        }
+        ctx->prof_cap = max_launches;
+        for (int k = 0; k < kProfKinds; ++k)
+            for (int i = 0; i < max_launches; ++i) {
+                LORA_HIP(hipEventCreate(&ctx->prof_start[k][i]));
+                LORA_HIP(hipEventCreate(&ctx->prof_stop[k][i]));
+            }
+    }
+    for (int k = 0; k < kProfKinds; ++k) ctx->prof_used[k] = 0;
+    ctx->prof_on = true;
+    return LORA_OK;
+}
+
+int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_t *counts) {
+    if (!ctx || !avg_us || !counts) return LORA_ERR_INVALID_ARG;
+    if (!ctx->prof_on) return LORA_ERR_INVALID_ARG;
+    ctx->prof_on = false;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    LORA_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    for (int k = 0; k < kProfKinds; ++k) {
+        double sum = 0.0;
+        for (int i = 0; i < ctx->prof_used[k]; ++i) {
+            float ms = 0.f;
+            LORA_HIP(hipEventElapsedTime(&ms, ctx->prof_start[k][i], ctx->prof_stop[k][i]));
+            sum += (double)ms * 1000.0;
+        }
+        counts[k] = ctx->prof_used[k];
+        avg_us[k] = ctx->prof_used[k] > 0 ? sum / ctx->prof_used[k] : 0.0;
+        ctx->prof_used[k] = 0;
+    }
+    return LORA_OK;
 }
 
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {

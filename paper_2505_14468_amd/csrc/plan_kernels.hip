@@ -262,32 +262,20 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
     fill_ext(p, start, stride);
 }
 
-__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t *ptr, int32_t count) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < count) ptr[i] = 0;
-}
-
 }  // namespace
 
-hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream) {
-    hipLaunchKernelGGL(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, a, fuse_fill ? 1 : 0);
-    hipError_t e = hipGetLastError();
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream, const KernelTimer *timers) {
+    hipError_t e = launch_kernel(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a,
+                                 fuse_fill ? 1 : 0);
     if (e != hipSuccess) return e;
     if (!fuse_fill) {
         long work = a.T > (long)a.ext_cap ? (long)a.T : (long)a.ext_cap;
         int grid = (int)((work + 255) / 256);
         if (grid < 1) grid = 1;
         if (grid > 2048) grid = 2048;
-        hipLaunchKernelGGL(plan_fill_kernel, dim3(grid), dim3(256), 0, stream, a);
-        e = hipGetLastError();
+        e = launch_kernel(plan_fill_kernel, dim3(grid), dim3(256), 0, stream, timers ? &timers[1] : nullptr, a);
     }
     return e;
-}
-
-hipError_t launch_zero_ints(int32_t *ptr, int32_t count, hipStream_t stream) {
-    if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(zero_ints_kernel, dim3((count + 255) / 256), dim3(256), 0, stream, ptr, count);
-    return hipGetLastError();
 }
 
 }  // namespace lora

@@ -27,10 +27,6 @@ __global__ __launch_bounds__(NW * 64) void shrink_kernel(ShrinkArgs p) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
 
-    // the first workgroups clear the split-K counters of the GEMM that follows
-    if (p.zero_ptr != nullptr) {
-        for (int i = blockIdx.x * (NW * 64) + tid; i < p.zero_count; i += gridDim.x * (NW * 64)) p.zero_ptr[i] = 0;
-    }
     if (p.plan.scalars[kScStatus] != 0) return;
 
     const int jg = blockIdx.x % p.rank_groups;
@@ -156,15 +152,13 @@ __global__ __launch_bounds__(NW * 64) void shrink_kernel(ShrinkArgs p) {
 
 }  // namespace
 
-hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream) {
+hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
     constexpr int NW = 8;
     const long grid = (long)a.max_units * a.rank_groups;
     if (grid <= 0) return hipSuccess;
     if (dtype == 1)
-        hipLaunchKernelGGL((shrink_kernel<__bf16, NW>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
-    else
-        hipLaunchKernelGGL((shrink_kernel<float, NW>), dim3((unsigned)grid), dim3(NW * 64), 0, stream, a);
-    return hipGetLastError();
+        return launch_kernel(shrink_kernel<__bf16, NW>, dim3((unsigned)grid), dim3(NW * 64), 0, stream, timer, a);
+    return launch_kernel(shrink_kernel<float, NW>, dim3((unsigned)grid), dim3(NW * 64), 0, stream, timer, a);
 }
 
 }  // namespace lora

@@ -175,7 +175,9 @@ def plan_device(ctx: Context, req_adapter: torch.Tensor, req_ntok: torch.Tensor,
 
 def workspace(T: int, N: int, r_max: int, dtype: torch.dtype, device) -> torch.Tensor:
     nbytes = B.lora_linear_workspace_bytes(T, N, r_max, dtype_code(dtype))
-    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    ws = torch.empty(max(nbytes, B.LORA_WORKSPACE_HEADER_BYTES), dtype=torch.uint8, device=device)
+    ws[: B.LORA_WORKSPACE_HEADER_BYTES].zero_()  # the split-K counters start at zero, once
+    return ws
 
 
 def linear_desc(pl: Plan, X: torch.Tensor, W0: torch.Tensor, Y: torch.Tensor, table: Optional[AdapterTable],

@@ -93,7 +93,8 @@ def test_shrink_stage_matches_oracle_intermediate():
         rt.linear(c, pl, X, W0, table, Y=Y, ws=ws, stage="shrink")
         torch.cuda.synchronize()
         es = 2 if dtype == "bf16" else 4
-        vbytes = ws[: wl.T * wl.r_max * es]
+        from paper_2505_14468_amd.binding import LORA_WORKSPACE_HEADER_BYTES as HDR
+        vbytes = ws[HDR: HDR + wl.T * wl.r_max * es]  # V follows the counter header
         Vg = vbytes.view(torch.bfloat16 if dtype == "bf16" else torch.float32).reshape(wl.T, wl.r_max)
         Vg = to_f64(rt.bits_from_tensor(Vg))
         _, Vo = oracle_workload(wl, return_v=True)
