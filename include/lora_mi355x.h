@@ -70,7 +70,6 @@ typedef enum lora_status {
 #define LORA_MAX_REQUESTS 65536   /* requests per batch                                  */
 #define LORA_MAX_ADAPTERS 65536   /* adapter slots in a table                            */
 #define LORA_MAX_RANK 512         /* rank of one adapter; ranks are multiples of 8       */
-#define LORA_WORKSPACE_HEADER_BYTES 16384 /* start of the workspace: split-K arrival counters */
 
 /*
  * Adapter pointer table.  A table, not one packed tensor, because adapters are
@@ -108,6 +107,7 @@ typedef struct lora_plan_t {
     int32_t magic;
     const int32_t *perm;        /* device [T]        slot -> row index of X / Y             */
     const int32_t *row_seg;     /* device [T]        slot -> segment                        */
+    const int32_t *row_adapter; /* device [T]        row (original order) -> adapter id     */
     const int32_t *seg_adapter; /* device [seg_cap]  adapter id of the segment (-1 = none)  */
     const int32_t *seg_indptr;  /* device [seg_cap+1] first slot of the segment             */
     const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
@@ -130,10 +130,7 @@ typedef struct lora_linear_desc {
     void *Y;                /* device [T, ldy]; must not alias X, W0 or the adapters        */
     int64_t ldy;            /* >= N, multiple of 8 (bf16) or 4 (fp32)                       */
     const lora_adapter_table_t *tbl; /* host pointer; NULL = backbone product only         */
-    void *workspace;        /* device, 256-byte aligned, lora_linear_workspace_bytes() big;
-                               its first LORA_WORKSPACE_HEADER_BYTES must be zero on first
-                               use (clear them once after allocating); the kernels keep
-                               them zero from then on                                       */
+    void *workspace;        /* device, 256-byte aligned, lora_linear_workspace_bytes() big  */
     size_t workspace_bytes;
 } lora_linear_desc;
 
@@ -145,7 +142,7 @@ typedef struct lora_linear_desc {
 int lora_ctx_create(lora_ctx **out, int device_ordinal);
 int lora_ctx_destroy(lora_ctx *ctx);
 
-/* Tuning overrides for experiments ("gemm_variant", "skinny_ksplit",
+/* Tuning overrides for experiments ("gemm_variant", "skinny_nb",
  * "skinny_max_rows", "plan_fused_rows"); value < 0 restores the built-in
  * heuristic.  Results never depend on them beyond fp32 summation order.
  * Errors: INVALID_ARG for an unknown name. */
@@ -198,19 +195,18 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 /* ---- steps a2-a4: the layer --------------------------------------------- */
 
 /* Device bytes lora_linear needs in desc->workspace for T rows, N outputs and
- * V row stride r_max: a header of split-K arrival counters
- * (LORA_WORKSPACE_HEADER_BYTES, zero between calls), V, and split-K partial
- * tiles.  One workspace may serve calls of different shapes as long as it is
- * big enough for each and the calls do not overlap in time. */
+ * V row stride r_max (it holds the intermediate V = s_a X A_a, [T, r_max]).
+ * One workspace may serve calls of different shapes as long as it is big
+ * enough for each and the calls do not overlap in time. */
 size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype);
 
-/* a2, shrink: V[slot, :r_a] = s_a * X[perm[slot], :] A_a for every row with an
+/* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an
  * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).
  * Asynchronous on `stream`.  No-op when desc->tbl is NULL or T == 0. */
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* a3 + a4, base GEMM with the expand fused before the single store of Y:
- * Y[perm[slot], :] = X[perm[slot], :] W0 + V[slot, :r_a] B_a, V taken from the
+ * Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V taken from the
  * workspace as lora_shrink() left it.  The expand runs as extra K-steps of the
  * same MFMA loop, so each Y element is written exactly once. */
 int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
@@ -232,7 +228,7 @@ int lora_profile_begin(lora_ctx *ctx, int max_launches);
 int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_t *counts);
 
 /* Name of the GEMM kernel variant lora_gemm_expand() would launch for this
- * problem ("skinny_tb4_ks4", "tile_128x128", ...), for reports.  Host only. */
+ * problem ("skinny_tb4_nb1", "tile_128x128", ...), for reports.  Host only. */
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype);
 
 /* ---- errors ------------------------------------------------------------- */

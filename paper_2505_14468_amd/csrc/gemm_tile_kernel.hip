@@ -1,6 +1,6 @@
 // LDS-tiled MFMA GEMM with the LoRA expand fused as extra K-steps:
 //
-//     Y[perm[slot], n] = sum_k X[perm[slot], k] W0[n, k]  +  sum_{p in ext(slot)} V[slot, p] B_a[n, p]
+//     Y[row, n] = sum_k X[row, k] W0[n, k]  +  sum_{p in ext(row)} V[row, p] B_a[n, p],   row = perm[slot]
 //
 // (paper section 4.4: backbone result and adapter result are combined; here they are combined
 // in the fp32 accumulators, before Y is rounded and stored, once.)
@@ -85,10 +85,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // ---- per-thread load slots ------------------------------------------------------------
     const int lrow = tid >> 3, lc = tid & 7;
     const E *xsrc[XL];
+    int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
         const int t = m0 + lrow + i * RPP;
-        xsrc[i] = t < p.T ? X + (int64_t)p.plan.perm[t] * p.ldx : nullptr;
+        xrowi[i] = t < p.T ? p.plan.perm[t] : 0;
+        xsrc[i] = t < p.T ? X + (int64_t)xrowi[i] * p.ldx : nullptr;
     }
     const E *wsrc[WL];
 #pragma unroll
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             const int row = lrow + i * RPP;
-            xr[i] = (row >= lo && row < hi) ? load_chunk(V + (int64_t)(m0 + row) * p.r_max + j) : zero_chunk();
+            xr[i] = (row >= lo && row < hi) ? load_chunk(V + (int64_t)xrowi[i] * p.r_max + j) : zero_chunk();
         }
 #pragma unroll
         for (int i = 0; i < WL; ++i) {

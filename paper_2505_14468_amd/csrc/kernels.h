@@ -23,6 +23,7 @@ struct PlanBuildArgs {
     int32_t *key_seg;      // [n_adapters+1] segment of key or -1
     int32_t *perm;         // [T]
     int32_t *row_seg;      // [T]
+    int32_t *row_adapter;  // [T]  adapter of every row, original order
     int32_t *seg_adapter;  // [seg_cap]
     int32_t *seg_indptr;   // [seg_cap+1]
     int32_t *seg_rank;     // [seg_cap]
@@ -76,14 +77,10 @@ struct GemmArgs {
     int64_t ldw;
     void *Y;
     int64_t ldy;
-    const void *V;         // [T, r_max] of E, slot order (null when no adapters)
+    const void *V;         // [T, r_max] of E, original row order (null when no adapters)
     const void *const *B;  // device table (null when no adapters)
     int32_t r_max;
     int32_t T, K, N;
-    // skinny (split-K) variants only
-    float *partials;
-    int32_t *counters;
-    int32_t ksplit;
 };
 
 enum GemmVariant {
@@ -96,14 +93,9 @@ enum GemmVariant {
 };
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
-hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
+hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer);
 
 // Geometry of the skinny kernel shared with the host (workspace sizing).
-constexpr int kSkinnyBN = 64;        // output columns per workgroup
 constexpr int kSkinnyMaxRows = 128;  // rows it accepts
-constexpr int kSkinnyMaxKSplit = 8;
-// The workspace starts with a header of split-K arrival counters, one per 64-column tile.  They
-// are zero between calls: the caller clears the header once, the kernels restore zero themselves.
-constexpr int kWorkspaceHeaderInts = 4096;
 
 }  // namespace lora

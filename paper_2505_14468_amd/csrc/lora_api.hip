@@ -53,7 +53,7 @@ struct lora_ctx {
     std::mutex ring_mutex;
     // tuning overrides (-1 = heuristic)
     int opt_gemm_variant = -1;
-    int opt_skinny_ksplit = -1;
+    int opt_skinny_nb = -1;
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
     // profiling mode: event pairs recorded tightly around each kernel
@@ -109,7 +109,7 @@ void free_profiler(lora_ctx *ctx) {
 
 // ---- plan storage layout ------------------------------------------------------------------------
 struct PlanLayout {
-    size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, seg_adapter, seg_indptr, seg_rank, seg_ext,
+    size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, row_adapter, seg_adapter, seg_indptr, seg_rank, seg_ext,
         seg_unit, ext_rec, scalars, total_bytes;
     int32_t seg_cap, ext_cap;
 };
@@ -139,6 +139,7 @@ PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_m
     L.key_seg = take(A + 1);
     L.perm = take((size_t)T);
     L.row_seg = take((size_t)T);
+    L.row_adapter = take((size_t)T);
     L.seg_adapter = take((size_t)L.seg_cap);
     L.seg_indptr = take((size_t)L.seg_cap + 1);
     L.seg_rank = take((size_t)L.seg_cap);
@@ -217,6 +218,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.key_seg = base + L.key_seg;
     a.perm = base + L.perm;
     a.row_seg = base + L.row_seg;
+    a.row_adapter = base + L.row_adapter;
     a.seg_adapter = base + L.seg_adapter;
     a.seg_indptr = base + L.seg_indptr;
     a.seg_rank = base + L.seg_rank;
@@ -239,6 +241,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     out->magic = kPlanMagic;
     out->perm = a.perm;
     out->row_seg = a.row_seg;
+    out->row_adapter = a.row_adapter;
     out->seg_adapter = a.seg_adapter;
     out->seg_indptr = a.seg_indptr;
     out->seg_rank = a.seg_rank;
@@ -263,27 +266,29 @@ int skinny_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : 8;
 
 struct GemmChoice {
     int variant;
-    int tblk;    // skinny only
-    int ksplit;  // skinny only
+    int tblk;  // skinny only: 16-row blocks
+    int nb;    // skinny only: 16-column blocks per workgroup
 };
 
 GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
     GemmChoice c{kGemmTile128x128, 0, 1};
+    (void)K;
+    const int cus = ctx ? ctx->num_cu : 256;
     const int max_rows = ctx && ctx->opt_skinny_max_rows >= 0 ? ctx->opt_skinny_max_rows : kSkinnyMaxRows;
     int forced = ctx ? ctx->opt_gemm_variant : -1;
-    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && (N + kSkinnyBN - 1) / kSkinnyBN <= kWorkspaceHeaderInts;
+    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows;
     if (forced == kGemmSkinny && !fits) forced = -1;
     const bool skinny = forced == kGemmSkinny || (forced < 0 && fits && T <= max_rows);
     if (skinny) {
         c.variant = kGemmSkinny;
         c.tblk = skinny_tblk(T);
-        const int n_tiles = (N + kSkinnyBN - 1) / kSkinnyBN;
-        const int cus = ctx ? ctx->num_cu : 256;
-        int ks = 1;
-        while (ks < kSkinnyMaxKSplit && n_tiles * ks < 2 * cus && K / (ks * 2) >= 256) ks *= 2;
-        if (ctx && ctx->opt_skinny_ksplit >= 1) ks = ctx->opt_skinny_ksplit;
-        if (ks > kSkinnyMaxKSplit) ks = kSkinnyMaxKSplit;
-        c.ksplit = ks;
+        // widest column block that still gives every CU a workgroup (fewer re-reads of X)
+        int nb = 8 / c.tblk > 4 ? 4 : 8 / c.tblk;
+        while (nb > 1 && (N + 16 * nb - 1) / (16 * nb) < cus) nb >>= 1;
+        if (ctx && ctx->opt_skinny_nb >= 1 && ctx->opt_skinny_nb * c.tblk <= 8 && ctx->opt_skinny_nb <= 4 &&
+            (ctx->opt_skinny_nb & (ctx->opt_skinny_nb - 1)) == 0)
+            nb = ctx->opt_skinny_nb;
+        c.nb = nb;
         return c;
     }
     if (forced >= 0 && forced < kGemmSkinny) {
@@ -299,7 +304,6 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
                           {kGemmTile256x128, 256, 128, 0.90},
                           {kGemmTile128x128, 128, 128, 0.80},
                           {kGemmTile64x64, 64, 64, 0.45}};
-    const int cus = ctx ? ctx->num_cu : 256;
     double best = 0.0;
     bool have = false;
     for (const Cand &cd : cands) {
@@ -316,23 +320,16 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 }
 
 struct WorkspaceLayout {
-    size_t counters_off, v_off, partials_off, total;
-    int n_tiles;
+    size_t v_off, total;
 };
 
 WorkspaceLayout workspace_layout(int64_t T, int32_t N, int32_t r_max, int32_t dtype) {
     WorkspaceLayout w;
+    (void)N;
     const size_t es = dtype == LORA_DTYPE_BF16 ? 2 : 4;
-    w.n_tiles = (N + kSkinnyBN - 1) / kSkinnyBN;
-    size_t off = 0;
-    w.counters_off = off;  // header: split-K arrival counters, zero between calls
-    off += (size_t)kWorkspaceHeaderInts * sizeof(int32_t);
-    w.v_off = off;
-    off = align_up(off + (size_t)T * (size_t)r_max * es, 256);
-    w.partials_off = off;
-    if (dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && T > 0 && w.n_tiles <= kWorkspaceHeaderInts)
-        off = align_up(off + (size_t)w.n_tiles * kSkinnyMaxKSplit * skinny_tblk(T) * 256 * sizeof(float4), 256);
-    w.total = off;
+    w.v_off = 0;
+    w.total = align_up((size_t)T * (size_t)r_max * es, 256);
+    if (w.total < 256) w.total = 256;
     return w;
 }
 
@@ -368,6 +365,7 @@ PlanView view_of(const lora_plan_t *plan) {
     PlanView v;
     v.perm = plan->perm;
     v.row_seg = plan->row_seg;
+    v.row_adapter = plan->row_adapter;
     v.seg_adapter = plan->seg_adapter;
     v.seg_indptr = plan->seg_indptr;
     v.seg_rank = plan->seg_rank;
@@ -425,14 +423,11 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.T = (int32_t)plan->T;
     a.K = d->K;
     a.N = d->N;
-    a.partials = reinterpret_cast<float *>(ws + w.partials_off);
-    a.counters = reinterpret_cast<int32_t *>(ws + w.counters_off);
     const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
-    a.ksplit = c.ksplit;
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
     if (c.variant == kGemmSkinny)
-        LORA_HIP(launch_gemm_skinny(a, c.tblk, stream, timed ? &timer : nullptr));
+        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
@@ -493,9 +488,8 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     if (!strcmp(name, "gemm_variant")) {
         if (value >= kGemmVariantCount) return LORA_ERR_INVALID_ARG;
         ctx->opt_gemm_variant = value;
-    } else if (!strcmp(name, "skinny_ksplit")) {
-        if (value > kSkinnyMaxKSplit) return LORA_ERR_INVALID_ARG;
-        ctx->opt_skinny_ksplit = value;
+    } else if (!strcmp(name, "skinny_nb")) {
+        ctx->opt_skinny_nb = value;
     } else if (!strcmp(name, "skinny_max_rows")) {
         ctx->opt_skinny_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
@@ -663,7 +657,7 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
     const GemmChoice c = choose_gemm(ctx, T, K, N, dtype);
     switch (c.variant) {
         case kGemmSkinny:
-            snprintf(buf, sizeof buf, "skinny_tb%d_ks%d", c.tblk, c.ksplit);
+            snprintf(buf, sizeof buf, "skinny_tb%d_nb%d", c.tblk, c.nb);
             break;
         case kGemmTile64x64:
             snprintf(buf, sizeof buf, "tile_64x64");

@@ -56,6 +56,7 @@ __device__ void fill_rows(const PlanBuildArgs &p, int start, int stride) {
         const int slot = p.req_dst[i] + (t - p.tok_off[i]);
         p.perm[slot] = t;
         p.row_seg[slot] = p.key_seg[key];
+        p.row_adapter[t] = a;
     }
 }
 

@@ -129,7 +129,7 @@ class Plan:
             return out
         T = self.T
         sc = self._arr("scalars", 8)
-        out.update(perm=self._arr("perm", T), row_seg=self._arr("row_seg", T),
+        out.update(perm=self._arr("perm", T), row_seg=self._arr("row_seg", T), row_adapter=self._arr("row_adapter", T),
                    seg_adapter=self._arr("seg_adapter", n_seg), seg_indptr=self._arr("seg_indptr", n_seg + 1),
                    seg_rank=self._arr("seg_rank", n_seg), seg_ext=self._arr("seg_ext", n_seg + 1),
                    seg_unit=self._arr("seg_unit", n_seg + 1), ext_total=int(sc[2]), n_units=int(sc[3]),
@@ -175,9 +175,7 @@ def plan_device(ctx: Context, req_adapter: torch.Tensor, req_ntok: torch.Tensor,
 
 def workspace(T: int, N: int, r_max: int, dtype: torch.dtype, device) -> torch.Tensor:
     nbytes = B.lora_linear_workspace_bytes(T, N, r_max, dtype_code(dtype))
-    ws = torch.empty(max(nbytes, B.LORA_WORKSPACE_HEADER_BYTES), dtype=torch.uint8, device=device)
-    ws[: B.LORA_WORKSPACE_HEADER_BYTES].zero_()  # the split-K counters start at zero, once
-    return ws
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
 def linear_desc(pl: Plan, X: torch.Tensor, W0: torch.Tensor, Y: torch.Tensor, table: Optional[AdapterTable],

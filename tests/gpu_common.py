@@ -20,7 +20,7 @@ def ctx():
 
 
 def reset_options():
-    for name in ("gemm_variant", "skinny_ksplit", "skinny_max_rows", "plan_fused_rows"):
+    for name in ("gemm_variant", "skinny_nb", "skinny_max_rows", "plan_fused_rows"):
         ctx().set_option(name, -1)
 
 

@@ -58,9 +58,9 @@ def test_skinny_kernel_row_counts(T):
                      scales=rng.choice([0.5, 1.0, 2.0], size=n_ad), req_adapter=ids, req_ntok=np.ones(T, int),
                      name=f"skinny_T{T}")
     assert B.lora_gemm_kernel_name(ctx().handle, T, 520, 200, B.LORA_DTYPE_BF16).startswith("skinny")
-    for ks in (1, 2, 3, 8, -1):
-        ctx().set_option("skinny_ksplit", ks)
-        Y = gpu_linear(wl, device_plan=(ks == 2))
+    for nb in (1, 2, 4, -1):
+        ctx().set_option("skinny_nb", nb)
+        Y = gpu_linear(wl, device_plan=(nb == 2))
         e = check_against_oracle(wl, Y)
     print(f"{wl.name}: err/rms {e:.2e}", flush=True)
     reset_options()
@@ -79,10 +79,10 @@ def test_skinny_equals_tile_path_within_tolerance_and_tile_handles_small_T():
 
 
 def test_shrink_stage_matches_oracle_intermediate():
-    """Step a2 alone: V = s_a X A_a in the plan's slot order (bf16 path: rounded once to bf16)."""
+    """Step a2 alone: V = s_a X A_a, one row per token row (bf16 path: rounded once to bf16)."""
     import torch
     from gpu_common import ctx, gpu_linear, rt
-    from oracle import oracle_workload, plan_reference
+    from oracle import oracle_workload
     for dtype, tol in (("bf16", 2 ** -8), ("f32", 1e-5)):
         ids, L = _mixed_batch(12, R=30, n_ad=5, max_len=90)
         wl = make_custom(seed=5, dtype=dtype, K=456, N=64, ranks=(8, 72, 16, 128, 32), scales=(2.0, 0.5, 1.0, 0.25, 1.5),
@@ -93,22 +93,20 @@ def test_shrink_stage_matches_oracle_intermediate():
         rt.linear(c, pl, X, W0, table, Y=Y, ws=ws, stage="shrink")
         torch.cuda.synchronize()
         es = 2 if dtype == "bf16" else 4
-        from paper_2505_14468_amd.binding import LORA_WORKSPACE_HEADER_BYTES as HDR
-        vbytes = ws[HDR: HDR + wl.T * wl.r_max * es]  # V follows the counter header
+        vbytes = ws[: wl.T * wl.r_max * es]
         Vg = vbytes.view(torch.bfloat16 if dtype == "bf16" else torch.float32).reshape(wl.T, wl.r_max)
         Vg = to_f64(rt.bits_from_tensor(Vg))
         _, Vo = oracle_workload(wl, return_v=True)
-        ref = plan_reference(wl.req_adapter, wl.req_ntok, wl.ranks)
         ra = wl.row_adapter()
         worst = 0.0
-        for slot, row in enumerate(ref["perm"]):
+        for row in range(wl.T):  # V is stored in original row order
             a = ra[row]
             if a < 0:
                 continue
             r = int(wl.ranks[a])
             want = float(wl.scales[a]) * Vo[row, :r]
             scale = max(np.abs(want).max(), 1e-3)
-            worst = max(worst, np.abs(Vg[slot, :r] - want).max() / scale)
+            worst = max(worst, np.abs(Vg[row, :r] - want).max() / scale)
         assert worst <= tol, (dtype, worst)
         print(f"shrink {dtype}: worst rel err {worst:.2e}", flush=True)
 

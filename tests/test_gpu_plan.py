@@ -27,6 +27,7 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1):
     for k in ("perm", "row_seg", "seg_adapter", "seg_indptr", "seg_rank", "seg_ext"):
         assert np.array_equal(got[k], ref[k]), k
     assert got["ext_total"] == int(ref["seg_ext"][-1])
+    assert np.array_equal(got["row_adapter"], np.repeat(ids, L))
     # derived tables: shrink work list and one record per 8 ranks
     rows = np.diff(ref["seg_indptr"])
     units = np.where(ref["seg_adapter"] >= 0, (rows + 63) // 64, 0)
