@@ -93,7 +93,7 @@ def main():
     r_max = wl.r_max
     plan_bytes = B.lora_plan_bytes(wl.n_req, T, wl.n_adapters, r_max)
     plan_buf = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
-    ws = rt.workspace(T, N, r_max, tdtype, dev)
+    ws = rt.workspace(T, K, N, r_max, tdtype, dev)
     stream = int(torch.cuda.current_stream().cuda_stream)
 
     plan0 = rt.plan_device(ctx, req_adapter, req_ntok, ranks, r_max, T, buf=plan_buf)

@@ -113,6 +113,7 @@ typedef struct lora_plan_t {
     const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
     const int32_t *seg_ext;     /* device [seg_cap+1] exclusive prefix sum of seg_rank      */
     const int32_t *seg_unit;    /* device [seg_cap+1] prefix sum of ceil(rows/64) (shrink work list) */
+    const int32_t *unit_rec;    /* device [(T/64+seg_cap)*4] shrink work units: adapter, rank, first slot, rows */
     const int32_t *ext_rec;     /* device [ext_cap*4] per 8 ranks: adapter, rank<<16|j0, slot_lo, slot_hi */
     const int32_t *tok_off;     /* device [n_req+1]  first row of every request             */
     int32_t *scalars;           /* device [8]: n_seg, status, ext_total, n_units, ...       */
@@ -194,20 +195,25 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 
 /* ---- steps a2-a4: the layer --------------------------------------------- */
 
-/* Device bytes lora_linear needs in desc->workspace for T rows, N outputs and
- * V row stride r_max (it holds the intermediate V = s_a X A_a, [T, r_max]).
- * One workspace may serve calls of different shapes as long as it is big
- * enough for each and the calls do not overlap in time. */
-size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype);
+/* Device bytes lora_linear needs in desc->workspace for T rows, K inputs, N
+ * outputs and V row stride r_max.  It holds the intermediate V = s_a X A_a
+ * ([T, r_max]) and, for decode-sized bf16 batches, a copy of X re-ordered into
+ * matrix-core operand order.  One workspace may serve calls of different
+ * shapes as long as it is big enough for each and the calls do not overlap in
+ * time.  Returns 0 for invalid arguments. */
+size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
 
 /* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an
  * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).
- * Asynchronous on `stream`.  No-op when desc->tbl is NULL or T == 0. */
+ * The same launch prepares whatever else lora_gemm_expand() expects to find in
+ * the workspace (the re-ordered copy of X for decode-sized batches), so it is
+ * the first half of the layer even when desc->tbl is NULL.
+ * Asynchronous on `stream`.  No-op when T == 0. */
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* a3 + a4, base GEMM with the expand fused before the single store of Y:
- * Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V taken from the
- * workspace as lora_shrink() left it.  The expand runs as extra K-steps of the
+ * Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V (and the copy of X) taken from
+ * the workspace as lora_shrink() left them for the same plan, desc->X and K.  The expand runs as extra K-steps of the
  * same MFMA loop, so each Y element is written exactly once. */
 int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 

@@ -50,7 +50,7 @@ class lora_plan_t(C.Structure):
                 ("seg_cap", C.c_int32), ("ext_cap", C.c_int32), ("magic", C.c_int32),
                 ("perm", C.c_void_p), ("row_seg", C.c_void_p), ("row_adapter", C.c_void_p), ("seg_adapter", C.c_void_p),
                 ("seg_indptr", C.c_void_p), ("seg_rank", C.c_void_p), ("seg_ext", C.c_void_p),
-                ("seg_unit", C.c_void_p), ("ext_rec", C.c_void_p), ("tok_off", C.c_void_p),
+                ("seg_unit", C.c_void_p), ("unit_rec", C.c_void_p), ("ext_rec", C.c_void_p), ("tok_off", C.c_void_p),
                 ("scalars", C.c_void_p)]
 
 
@@ -93,7 +93,7 @@ def lib():
         L.lora_plan.argtypes = plan_args
         L.lora_plan_device.argtypes = plan_args
         L.lora_plan_status.argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.c_void_p, i32p]
-        L.lora_linear_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32]
+        L.lora_linear_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.lora_linear_workspace_bytes.restype = C.c_size_t
         for name in ("lora_shrink", "lora_gemm_expand", "lora_linear"):
             getattr(L, name).argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(lora_linear_desc), C.c_void_p]
@@ -193,8 +193,8 @@ def lora_plan_status(ctx, plan: lora_plan_t, stream: int):
 
 
 # ---- the layer ------------------------------------------------------------------
-def lora_linear_workspace_bytes(T: int, N: int, r_max: int, dtype: int) -> int:
-    return int(lib().lora_linear_workspace_bytes(int(T), int(N), int(r_max), int(dtype)))
+def lora_linear_workspace_bytes(T: int, K: int, N: int, r_max: int, dtype: int) -> int:
+    return int(lib().lora_linear_workspace_bytes(int(T), int(K), int(N), int(r_max), int(dtype)))
 
 
 def make_adapter_table(n_adapters: int, A_ptrs: int, B_ptrs: int, scale_ptr: int) -> lora_adapter_table_t:

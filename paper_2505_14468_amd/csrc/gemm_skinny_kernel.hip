@@ -4,16 +4,22 @@
 //     Y[t, n] = sum_k X[t, k] W0[n, k]  +  sum_p V[t, p] B_a(p)[n, p]
 //
 // (paper section 4.4: backbone and adapter results combined) -- but organised around the
-// weight stream and around memory latency instead of around LDS tiles:
-//   * the whole batch is one M tile, so rows stay in their original order: no gather, no
-//     dependent index load in front of the first weight load;
+// weight stream, memory latency and the vector cache's line rate instead of around LDS tiles:
+//   * the whole batch is one M tile, so rows stay in their original order: no gather;
 //   * a workgroup owns 16*NB output columns and the whole contraction axis; its 8 waves
-//     split that axis between them, so every wave streams its own slice of W0 and of X
-//     global -> VGPR -> MFMA (each element is used by exactly one wave: LDS would only add
-//     a hop and a barrier).  No workgroup depends on another one: no split-K through memory;
-//   * loads are issued in batches of several MFMA steps, two batches in flight per wave,
-//     so that a CU keeps >100 KB of loads outstanding -- a kernel this short (microseconds)
-//     is otherwise spent waiting on a handful of round trips to HBM;
+//     split that axis between them and no workgroup depends on another (no split-K through
+//     memory, no fences, nothing to reduce across CUs);
+//   * every CU needs all of X for its few columns, so X is the larger stream into a CU (from
+//     L2).  An MFMA operand wants "row i, 16 bytes of k" per lane, which read straight from a
+//     row-major matrix touches 16 cache lines per quarter-wave; the vector cache then runs at
+//     a quarter of its rate and becomes the bound.  So X is read from the fragment-major copy
+//     the shrink launch leaves in the workspace (one contiguous 1 KiB block per MFMA step
+//     and 16-row block), and W0 -- which must stay in its owner's layout -- is loaded with
+//     rows contiguous across lanes (8 rows x 128 bytes per instruction) and turned into MFMA
+//     layout through a small wave-private, XOR-swizzled LDS buffer (no barrier needed);
+//   * loads are issued in batches of several MFMA steps, two batches in flight per wave, so
+//     that a CU keeps >100 KB outstanding: a kernel this short is otherwise a handful of
+//     serial round trips to HBM;
 //   * MFMA 16x16x32: M = 16 output columns, N = 16 token rows; the matrix core idles most of
 //     the time, as it should in a bandwidth-bound kernel;
 //   * the extension (V against B_a, rows of other adapters masked to zero) is dealt
@@ -42,13 +48,15 @@ template <int TBLK, int NB>
 __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     typedef __bf16 E;
     constexpr int CE = 8;
-    constexpr int LPS = TBLK + NB;                    // 16-byte loads per lane per MFMA step
-    constexpr int SB = 20 / LPS;                       // MFMA steps per load batch (2 batches in flight)
+    constexpr int LPG = 2 * NB + 2 * TBLK;             // 16-byte loads per lane per stage (2 MFMA steps = 64 k)
+    constexpr int SGB = (20 / LPG) > 0 ? 20 / LPG : 1;  // stages per load batch; two batches in flight
     constexpr int TILE = NB * TBLK * 256;              // floats of one wave's partial tile
+    constexpr int WBUF = NB * 16 * 8;                  // chunks of one W staging buffer (16*NB rows x 128 B)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *red = reinterpret_cast<float *>(smem);  // [kSkWaves][TILE]
-    SkTable *tab = reinterpret_cast<SkTable *>(smem + (size_t)kSkWaves * TILE * sizeof(float));
+    chunk_t *wstage = reinterpret_cast<chunk_t *>(smem + (size_t)kSkWaves * TILE * sizeof(float));  // [kSkWaves][WBUF]
+    SkTable *tab = reinterpret_cast<SkTable *>(wstage + kSkWaves * WBUF);
 
     if (p.plan.scalars[kScStatus] != 0) return;
 
@@ -56,18 +64,28 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     const int li = lane & 15, lg = lane >> 4;
     const int n0 = blockIdx.x * (16 * NB);
 
-    const E *X = static_cast<const E *>(p.X);
     const E *V = static_cast<const E *>(p.V);
     const E *W = static_cast<const E *>(p.W);
+    const chunk_t *Xp = static_cast<const chunk_t *>(p.Xpack);
 
-    // weight rows and token rows this lane feeds to the MFMAs.  Rows past the end are clamped to
-    // the last valid row: they only feed accumulator entries that are never stored.
-    const E *wrow[NB];
+    // W loads: lane -> (row lane/8 + 8*i of the 16-row block, chunk lane%8 of the 128-byte stage).
+    // Rows past N are clamped to the last row: they only feed accumulator entries never stored.
+    const int wr = lane >> 3, wc = lane & 7;
+    const E *wrow[NB][2];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) wrow[nb] = W + (int64_t)min(n0 + nb * 16 + li, p.N - 1) * p.ldw;
-    const E *xrow[TBLK];
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int tb = 0; tb < TBLK; ++tb) xrow[tb] = X + (int64_t)min(tb * 16 + li, p.T - 1) * p.ldx;
+        for (int i = 0; i < 2; ++i) wrow[nb][i] = W + (int64_t)min(n0 + nb * 16 + wr + 8 * i, p.N - 1) * p.ldw;
+    // swizzled positions inside the wave's staging buffer
+    int wdst[NB][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = wr + 8 * i;
+            wdst[nb][i] = (nb * 16 + row) * 8 + (wc ^ ((row >> 1) & 7));
+        }
+    chunk_t *buf = wstage + wave * WBUF;  // one buffer is enough: a wave's LDS operations execute in order
 
     f32x4_t acc[NB][TBLK];
 #pragma unroll
@@ -75,34 +93,53 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 #pragma unroll
         for (int tb = 0; tb < TBLK; ++tb) acc[nb][tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // ---- base product: this wave's share of the MFMA steps along K ------------------------------
+    // ---- base product: this wave's share of the stages (64 k each) along K ---------------------------
     const int kchunks = p.K / CE;
-    const int steps = (kchunks + 3) >> 2;
-    const int st0 = (int)((int64_t)steps * wave / kSkWaves), st1 = (int)((int64_t)steps * (wave + 1) / kSkWaves);
+    const int stages = (kchunks + 7) >> 3;
+    const int sg0 = (int)((int64_t)stages * wave / kSkWaves), sg1 = (int)((int64_t)stages * (wave + 1) / kSkWaves);
 
-    chunk_t wa[SB][NB], xa[SB][TBLK], wb[SB][NB], xb[SB][TBLK];
-    auto load_batch = [&](int s0, chunk_t (&wf)[SB][NB], chunk_t (&xf)[SB][TBLK]) {
+    chunk_t wa[SGB][NB][2], xa[SGB][2][TBLK], wb[SGB][NB][2], xb[SGB][2][TBLK];
+    auto load_batch = [&](int g0, chunk_t (&wf)[SGB][NB][2], chunk_t (&xf)[SGB][2][TBLK]) {
 #pragma unroll
-        for (int s = 0; s < SB; ++s) {
-            const int kc = (s0 + s) * 4 + lg;
-            const bool ok = (s0 + s) < st1 && kc < kchunks;  // beyond the range: load chunk 0, drop it
+        for (int g = 0; g < SGB; ++g) {
+            const int sg = g0 + g;
+            const int kc = sg * 8 + wc;
+            const bool ok = sg < sg1 && kc < kchunks;  // beyond the range: load chunk 0, drop it
             const int koff = ok ? kc * CE : 0;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) wf[s][nb] = keep_if(ok, load_chunk(wrow[nb] + koff));
-#pragma unroll
-            for (int tb = 0; tb < TBLK; ++tb) xf[s][tb] = keep_if(ok, load_chunk(xrow[tb] + koff));
-        }
-    };
-    auto mma_batch = [&](const chunk_t (&wf)[SB][NB], const chunk_t (&xf)[SB][TBLK]) {
-#pragma unroll
-        for (int s = 0; s < SB; ++s)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], wf[s][nb], xf[s][tb]);
+                for (int i = 0; i < 2; ++i) wf[g][nb][i] = keep_if(ok, load_chunk(wrow[nb][i] + koff));
+            const int sgc = min(sg, stages - 1);  // X of a stage beyond the range meets zeroed weights
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int tb = 0; tb < TBLK; ++tb) xf[g][h][tb] = Xp[((int64_t)(sgc * 2 + h) * TBLK + tb) * 64 + lane];
+        }
+    };
+    auto mma_batch = [&](const chunk_t (&wf)[SGB][NB][2], const chunk_t (&xf)[SGB][2][TBLK]) {
+#pragma unroll
+        for (int g = 0; g < SGB; ++g) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) buf[wdst[nb][i]] = wf[g][nb][i];
+            // lanes exchange data through the wave's own buffer: LDS operations of one wave execute in
+            // order, the fences only keep the compiler from reordering across the exchange
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const chunk_t w = buf[(nb * 16 + li) * 8 + ((h * 4 + lg) ^ ((li >> 1) & 7))];
+#pragma unroll
+                    for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], w, xf[g][h][tb]);
+                }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
     };
 
-    load_batch(st0, wa, xa);
+    load_batch(sg0, wa, xa);
 
     // ---- extension table: one entry per 8 ranks of the batch's concatenated rank space ----------------
     const int ext_chunks = p.B != nullptr ? p.plan.scalars[kScExtTotal] / CE : 0;
@@ -141,10 +178,10 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
         build_table(0);
     }
 
-    for (int s0 = st0; s0 < st1; s0 += 2 * SB) {
-        load_batch(s0 + SB, wb, xb);
+    for (int g0 = sg0; g0 < sg1; g0 += 2 * SGB) {
+        load_batch(g0 + SGB, wb, xb);
         mma_batch(wa, xa);
-        load_batch(s0 + 2 * SB, wa, xa);
+        load_batch(g0 + 2 * SGB, wa, xa);
         mma_batch(wb, xb);
     }
 
@@ -227,7 +264,8 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 template <int TBLK, int NB>
 hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
     const int n_tiles = (a.N + 16 * NB - 1) / (16 * NB);
-    const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + sizeof(SkTable);
+    const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t) +
+                        sizeof(SkTable);
     auto kern = gemm_skinny_kernel<TBLK, NB>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -244,6 +282,7 @@ hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *t
 // tblk: 16-row blocks (1, 2, 4, 8); nb: 16-column blocks per workgroup (1, 2, 4; nb * tblk <= 8).
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer) {
     if (a.T <= 0 || a.N <= 0) return hipSuccess;
+    if (a.Xpack == nullptr) return hipErrorInvalidValue;
 #define LORA_SK_CASE(TB_, NB_) \
     if (tblk == TB_ && nb == NB_) return launch_sk<TB_, NB_>(a, stream, timer)
     LORA_SK_CASE(1, 1);

@@ -29,6 +29,7 @@ struct PlanBuildArgs {
     int32_t *seg_rank;     // [seg_cap]
     int32_t *seg_ext;      // [seg_cap+1]
     int32_t *seg_unit;     // [seg_cap+1]
+    int32_t *unit_rec;     // [unit_cap*4] shrink work list: adapter, rank, first slot, rows
     int32_t *ext_rec;      // [ext_cap*4]
     int32_t *scalars;      // [8]
 };
@@ -65,7 +66,13 @@ struct ShrinkArgs {
     void *V;               // [T, r_max] of E
     int32_t r_max;
     int32_t rank_groups;   // ceil(r_max / kShrinkRanks)
-    int32_t max_units;     // upper bound of work units (grid = max_units * rank_groups)
+    int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
+    // Fragment-major copy of X for the decode-sized GEMM (null = not needed): for MFMA step s
+    // (32 k) and 16-row block tb, the 64 lanes' 16-byte operands are stored contiguously at
+    // xpack[(s * pack_tblk + tb) * 64 + lane], lane = 16 * kgroup + row, zero past T and K.
+    void *xpack;
+    int32_t pack_tblk;
+    int32_t pack_wgs;      // extra workgroups in front of the shrink units that write the copy
 };
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 
@@ -78,6 +85,7 @@ struct GemmArgs {
     void *Y;
     int64_t ldy;
     const void *V;         // [T, r_max] of E, original row order (null when no adapters)
+    const void *Xpack;     // fragment-major copy of X (decode-sized kernel only)
     const void *const *B;  // device table (null when no adapters)
     int32_t r_max;
     int32_t T, K, N;

@@ -110,7 +110,7 @@ void free_profiler(lora_ctx *ctx) {
 // ---- plan storage layout ------------------------------------------------------------------------
 struct PlanLayout {
     size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, row_adapter, seg_adapter, seg_indptr, seg_rank, seg_ext,
-        seg_unit, ext_rec, scalars, total_bytes;
+        seg_unit, unit_rec, ext_rec, scalars, total_bytes;
     int32_t seg_cap, ext_cap;
 };
 
@@ -145,6 +145,7 @@ PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_m
     L.seg_rank = take((size_t)L.seg_cap);
     L.seg_ext = take((size_t)L.seg_cap + 1);
     L.seg_unit = take((size_t)L.seg_cap + 1);
+    L.unit_rec = take(((size_t)T / kShrinkRows + (size_t)L.seg_cap) * 4);
     L.ext_rec = take((size_t)L.ext_cap * 4);
     L.scalars = take(8);
     L.total_bytes = off * sizeof(int32_t);
@@ -224,6 +225,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.seg_rank = base + L.seg_rank;
     a.seg_ext = base + L.seg_ext;
     a.seg_unit = base + L.seg_unit;
+    a.unit_rec = base + L.unit_rec;
     a.ext_rec = base + L.ext_rec;
     a.scalars = base + L.scalars;
     const int fused_rows = ctx->opt_plan_fused_rows >= 0 ? ctx->opt_plan_fused_rows : 4096;
@@ -247,6 +249,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     out->seg_rank = a.seg_rank;
     out->seg_ext = a.seg_ext;
     out->seg_unit = a.seg_unit;
+    out->unit_rec = a.unit_rec;
     out->ext_rec = a.ext_rec;
     out->tok_off = a.tok_off;
     out->scalars = a.scalars;
@@ -320,16 +323,25 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 }
 
 struct WorkspaceLayout {
-    size_t v_off, total;
+    size_t v_off, xpack_off, xpack_bytes, total;
 };
 
-WorkspaceLayout workspace_layout(int64_t T, int32_t N, int32_t r_max, int32_t dtype) {
+// Bytes of the fragment-major copy of X the decode-sized GEMM reads (whole 64-k stages, 16-row blocks).
+size_t xpack_bytes_for(int64_t T, int32_t K) {
+    const size_t stages = ((size_t)K / 8 + 7) / 8;
+    return stages * 2 * (size_t)skinny_tblk(T) * 64 * 16;
+}
+
+WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
     WorkspaceLayout w;
     (void)N;
     const size_t es = dtype == LORA_DTYPE_BF16 ? 2 : 4;
     w.v_off = 0;
-    w.total = align_up((size_t)T * (size_t)r_max * es, 256);
-    if (w.total < 256) w.total = 256;
+    size_t off = align_up((size_t)T * (size_t)r_max * es, 256);
+    w.xpack_off = off;
+    w.xpack_bytes = (dtype == LORA_DTYPE_BF16 && T > 0 && T <= kSkinnyMaxRows) ? xpack_bytes_for(T, K) : 0;
+    off = align_up(off + w.xpack_bytes, 256);
+    w.total = off < 256 ? 256 : off;
     return w;
 }
 
@@ -351,7 +363,7 @@ int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
         if (d->tbl->n_adapters < plan->n_adapters) return LORA_ERR_INVALID_ARG;
         if (plan->n_adapters > 0 && (!d->tbl->A || !d->tbl->B || !d->tbl->scale)) return LORA_ERR_INVALID_ARG;
     }
-    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     if (plan->T > 0) {
         if (!d->workspace) return LORA_ERR_INVALID_ARG;
         if ((uintptr_t)d->workspace & 255u) return LORA_ERR_ALIGNMENT;
@@ -371,6 +383,7 @@ PlanView view_of(const lora_plan_t *plan) {
     v.seg_rank = plan->seg_rank;
     v.seg_ext = plan->seg_ext;
     v.seg_unit = plan->seg_unit;
+    v.unit_rec = plan->unit_rec;
     v.ext_rec = plan->ext_rec;
     v.scalars = plan->scalars;
     return v;
@@ -381,8 +394,10 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
 }
 
 int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
-    if (!has_adapters(plan, d)) return LORA_OK;
-    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    const bool ad = has_adapters(plan, d);
+    const bool pack = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny;
+    if (!ad && !pack) return LORA_OK;
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     ShrinkArgs a;
     a.plan = view_of(plan);
@@ -390,15 +405,18 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.ldx = d->ldx;
     a.K = d->K;
     a.T = (int32_t)plan->T;
-    a.A = d->tbl->A;
-    a.scale = d->tbl->scale;
+    a.A = ad ? d->tbl->A : nullptr;
+    a.scale = ad ? d->tbl->scale : nullptr;
     a.V = ws + w.v_off;
     a.r_max = plan->r_max;
-    a.rank_groups = (plan->r_max + kShrinkRanks - 1) / kShrinkRanks;
+    a.rank_groups = ad ? (plan->r_max + kShrinkRanks - 1) / kShrinkRanks : 1;
     // units <= sum over segments of ceil(rows/64) <= T/64 + number of adapter segments
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
-    a.max_units = (int32_t)(plan->T / kShrinkRows + seg_bound2);
+    a.max_units = ad ? (int32_t)(plan->T / kShrinkRows + seg_bound2) : 0;
+    a.xpack = pack ? ws + w.xpack_off : nullptr;
+    a.pack_tblk = pack ? skinny_tblk(plan->T) : 0;
+    a.pack_wgs = pack ? (int32_t)((w.xpack_bytes / 16 + 2047) / 2048) : 0;  // 4 chunks per thread
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfShrink, &timer);
     LORA_HIP(launch_shrink(a, d->dtype, stream, timed ? &timer : nullptr));
@@ -406,7 +424,7 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
 }
 
 int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
-    const WorkspaceLayout w = workspace_layout(plan->T, d->N, plan->r_max, d->dtype);
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     GemmArgs a;
     a.plan = view_of(plan);
@@ -418,6 +436,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.ldy = d->ldy;
     const bool ad = has_adapters(plan, d);
     a.V = ad ? ws + w.v_off : nullptr;
+    a.Xpack = w.xpack_bytes ? ws + w.xpack_off : nullptr;
     a.B = ad ? d->tbl->B : nullptr;
     a.r_max = plan->r_max;
     a.T = (int32_t)plan->T;
@@ -572,9 +591,9 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
     return sc[kScStatus];
 }
 
-size_t lora_linear_workspace_bytes(int64_t T, int32_t N, int32_t r_max, int32_t dtype) {
-    if (T < 0 || N <= 0 || r_max < 0 || (dtype != LORA_DTYPE_BF16 && dtype != LORA_DTYPE_F32)) return 0;
-    return workspace_layout(T, N, r_max, dtype).total;
+size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
+    if (T < 0 || K <= 0 || N <= 0 || r_max < 0 || (dtype != LORA_DTYPE_BF16 && dtype != LORA_DTYPE_F32)) return 0;
+    return workspace_layout(T, K, N, r_max, dtype).total;
 }
 
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {

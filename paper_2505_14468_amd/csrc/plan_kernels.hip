@@ -84,6 +84,30 @@ __device__ void fill_ext(const PlanBuildArgs &p, int start, int stride) {
     }
 }
 
+// unit_rec: one record per shrink work unit (<= 64 rows of one adapter segment).
+__device__ void fill_units(const PlanBuildArgs &p, int start, int stride) {
+    const int n_units = p.scalars[kScNUnits];
+    const int n_seg = p.scalars[kScNSeg];
+    for (int u = start; u < n_units; u += stride) {
+        int lo = 0, hi = n_seg;  // first segment whose unit range ends beyond u
+        while (lo < hi) {
+            int mid = (lo + hi) >> 1;
+            if (p.seg_unit[mid + 1] > u)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int s = lo;
+        const int slot0 = p.seg_indptr[s] + (u - p.seg_unit[s]) * kShrinkRows;
+        int4 rec;
+        rec.x = p.seg_adapter[s];
+        rec.y = p.seg_rank[s];
+        rec.z = slot0;
+        rec.w = min(kShrinkRows, p.seg_indptr[s + 1] - slot0);
+        reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
+    }
+}
+
 __device__ void write_failed(const PlanBuildArgs &p, int status) {
     p.scalars[kScNSeg] = 0;
     p.scalars[kScStatus] = status;
@@ -252,6 +276,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
     if (fuse_fill) {
         fill_rows(p, tid, kPlanThreads);
         fill_ext(p, tid, kPlanThreads);
+        fill_units(p, tid, kPlanThreads);
     }
 }
 
@@ -261,6 +286,7 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
     const int stride = gridDim.x * 256;
     fill_rows(p, start, stride);
     fill_ext(p, start, stride);
+    fill_units(p, start, stride);
 }
 
 }  // namespace

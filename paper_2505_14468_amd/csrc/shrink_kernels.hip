@@ -2,8 +2,8 @@
 // adapter segment (first half of the adapter product of paper section 4.4).
 //
 // One workgroup = one work unit = (segment, block of <= 64 of its rows, group of <= 64 ranks).
-// The unit list is the plan's seg_unit prefix sum; the grid is an upper bound and surplus
-// workgroups leave at once.  Inside a unit the NW waves split the contraction axis K between
+// The unit list is part of the plan; the grid is an upper bound and surplus workgroups
+// leave at once.  Inside a unit the NW waves split the contraction axis K between
 // them; each wave runs 16x16 MFMA tiles with the adapter rows (ranks) as the MFMA M dimension
 // and the token rows as the N dimension, both operands loaded straight from global memory as
 // 16-byte chunks (A_a is [r, K] and X is [T, K]: both are contiguous along K, which is what
@@ -114,34 +114,44 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
     }
 }
 
+// Fragment-major copy of X for the decode-sized GEMM: output-ordered, so the writes are contiguous.
+template <typename E>
+__device__ __forceinline__ void pack_x(const ShrinkArgs &p, int wg) {
+    constexpr int CE = Elem<E>::CE;
+    const int kchunks = p.K / CE;
+    const int steps = ((kchunks + 7) >> 3) * 2;  // whole 64-k stages
+    const int64_t total = (int64_t)steps * p.pack_tblk * 64;
+    chunk_t *dst = static_cast<chunk_t *>(p.xpack);
+    for (int64_t idx = (int64_t)wg * (kShWaves * 64) + threadIdx.x; idx < total; idx += (int64_t)p.pack_wgs * (kShWaves * 64)) {
+        const int lane = (int)(idx & 63);
+        const int64_t blk = idx >> 6;
+        const int tb = (int)(blk % p.pack_tblk), s = (int)(blk / p.pack_tblk);
+        const int t = tb * 16 + (lane & 15), kc = s * 4 + (lane >> 4);
+        dst[idx] = (t < p.T && kc < kchunks) ? load_chunk(static_cast<const E *>(p.X) + (int64_t)t * p.ldx + kc * CE) : zero_chunk();
+    }
+}
+
 template <typename E>
 __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     __shared__ float red[kShrinkRows * kRS];
     const int tid = threadIdx.x;
 
     if (p.plan.scalars[kScStatus] != 0) return;
-    const int jg = blockIdx.x % p.rank_groups;
-    const int unit = blockIdx.x / p.rank_groups;
+    if ((int)blockIdx.x < p.pack_wgs) {
+        pack_x<E>(p, blockIdx.x);
+        return;
+    }
+    const int bid = blockIdx.x - p.pack_wgs;
+    const int jg = bid % p.rank_groups;
+    const int unit = bid / p.rank_groups;
     if (unit >= p.plan.scalars[kScNUnits]) return;
 
-    // segment of this unit: last s with seg_unit[s] <= unit
-    int lo = 0, hi = p.plan.scalars[kScNSeg];
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (p.plan.seg_unit[mid + 1] > unit)
-            hi = mid;
-        else
-            lo = mid + 1;
-    }
-    const int s = lo;
-    const int a = p.plan.seg_adapter[s];
-    const int r = p.plan.seg_rank[s];
+    // the plan's work list names the unit: adapter, rank, first slot, rows (one load, no search)
+    const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
+    const int a = rec.x, r = rec.y, slot0 = rec.z, nrows = rec.w;
     const int j0 = jg * kShrinkRanks;
-    if (a < 0 || j0 >= r) return;
+    if (a < 0 || j0 >= r || nrows <= 0) return;
     const int nj = min(kShrinkRanks, r - j0);
-    const int slot0 = p.plan.seg_indptr[s] + (unit - p.plan.seg_unit[s]) * kShrinkRows;
-    const int nrows = min(kShrinkRows, p.plan.seg_indptr[s + 1] - slot0);
-    if (nrows <= 0) return;
     const E *Aa = static_cast<const E *>(p.A[a]);
 
     if (Aa == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
 }  // namespace
 
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    const long grid = (long)a.max_units * a.rank_groups;
+    const long grid = (long)a.max_units * a.rank_groups + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (dtype == 1) return launch_kernel(shrink_kernel<__bf16>, dim3((unsigned)grid), dim3(kShWaves * 64), 0, stream, timer, a);
     return launch_kernel(shrink_kernel<float>, dim3((unsigned)grid), dim3(kShWaves * 64), 0, stream, timer, a);

@@ -134,6 +134,7 @@ class Plan:
                    seg_rank=self._arr("seg_rank", n_seg), seg_ext=self._arr("seg_ext", n_seg + 1),
                    seg_unit=self._arr("seg_unit", n_seg + 1), ext_total=int(sc[2]), n_units=int(sc[3]),
                    ext_rec=self._arr("ext_rec", (int(sc[2]) // 8) * 4).reshape(-1, 4),
+                   unit_rec=self._arr("unit_rec", int(sc[3]) * 4).reshape(-1, 4),
                    tok_off=self._arr("tok_off", int(self.struct.n_req) + 1))
         return out
 
@@ -173,8 +174,8 @@ def plan_device(ctx: Context, req_adapter: torch.Tensor, req_ntok: torch.Tensor,
     return Plan(st, buf, keep=(req_adapter, req_ntok, adapter_rank))
 
 
-def workspace(T: int, N: int, r_max: int, dtype: torch.dtype, device) -> torch.Tensor:
-    nbytes = B.lora_linear_workspace_bytes(T, N, r_max, dtype_code(dtype))
+def workspace(T: int, K: int, N: int, r_max: int, dtype: torch.dtype, device) -> torch.Tensor:
+    nbytes = B.lora_linear_workspace_bytes(T, K, N, r_max, dtype_code(dtype))
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
@@ -200,7 +201,7 @@ def linear(ctx: Context, pl: Plan, X: torch.Tensor, W0: torch.Tensor, table: Opt
         ce = 8 if X.dtype == torch.bfloat16 else 4
         Y = torch.empty((pl.T, (N + ce - 1) // ce * ce), dtype=X.dtype, device=X.device)[:, :N]
     if ws is None:
-        ws = workspace(pl.T, N, pl.r_max, X.dtype, X.device)
+        ws = workspace(pl.T, W0.shape[1], N, pl.r_max, X.dtype, X.device)
     d = linear_desc(pl, X, W0, Y, table, ws)
     fn = {"linear": B.lora_linear, "shrink": B.lora_shrink, "gemm_expand": B.lora_gemm_expand}[stage]
     fn(ctx.handle, pl.struct, d, _stream())

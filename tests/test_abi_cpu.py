@@ -38,7 +38,7 @@ def test_status_codes_match_header():
 def test_struct_layouts_match_c():
     # sizes as a C compiler lays the header's structs out on x86-64
     assert C.sizeof(B.lora_adapter_table_t) == 32
-    assert C.sizeof(B.lora_plan_t) == 8 + 6 * 4 + 11 * 8
+    assert C.sizeof(B.lora_plan_t) == 8 + 6 * 4 + 12 * 8
     assert C.sizeof(B.lora_linear_desc) == 16 + 6 * 8 + 8 + 8 + 8
 
 
@@ -67,10 +67,10 @@ def test_plan_bytes_and_workspace_bytes():
     big = B.lora_plan_bytes(512, 2048, 512, 128)
     assert 0 < small < big
     assert small % 256 == 0
-    assert B.lora_linear_workspace_bytes(0, 256, 8, 0) == 256
-    assert B.lora_linear_workspace_bytes(64, 4096, 16, 1) >= 64 * 16 * 2
-    assert B.lora_linear_workspace_bytes(8, 0, 8, 1) == 0
-    assert B.lora_linear_workspace_bytes(8, 8, 8, 7) == 0
+    assert B.lora_linear_workspace_bytes(0, 256, 256, 8, 0) == 256
+    assert B.lora_linear_workspace_bytes(64, 4096, 4096, 16, 1) >= 64 * 16 * 2 + 64 * 4096 * 2
+    assert B.lora_linear_workspace_bytes(8, 64, 0, 8, 1) == 0
+    assert B.lora_linear_workspace_bytes(8, 64, 8, 8, 7) == 0
 
 
 def test_lora_plan_validates_before_touching_the_gpu():
@@ -93,7 +93,7 @@ def _fake_plan(T=4, n_adapters=2, r_max=16):
 
 def test_lora_linear_validates_before_touching_the_gpu():
     plan = _fake_plan()
-    ws_bytes = B.lora_linear_workspace_bytes(4, 64, 16, B.LORA_DTYPE_BF16)
+    ws_bytes = B.lora_linear_workspace_bytes(4, 64, 64, 16, B.LORA_DTYPE_BF16)
 
     def run(**kw):
         a = dict(dtype=B.LORA_DTYPE_BF16, K=64, N=64, X=4096, ldx=64, W0=8192, ldw=64, Y=16384, ldy=64,

@@ -89,7 +89,7 @@ def test_shrink_stage_matches_oracle_intermediate():
                          req_adapter=ids, req_ntok=L, name=f"shrink_{dtype}")
         _, (X, W0, table, pl, Y) = gpu_linear(wl, stage="shrink", return_all=True)
         c = ctx()
-        ws = rt.workspace(wl.T, 64, wl.r_max, X.dtype, X.device)
+        ws = rt.workspace(wl.T, 456, 64, wl.r_max, X.dtype, X.device)
         rt.linear(c, pl, X, W0, table, Y=Y, ws=ws, stage="shrink")
         torch.cuda.synchronize()
         es = 2 if dtype == "bf16" else 4

@@ -32,6 +32,14 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1):
     rows = np.diff(ref["seg_indptr"])
     units = np.where(ref["seg_adapter"] >= 0, (rows + 63) // 64, 0)
     assert np.array_equal(got["seg_unit"], np.concatenate([[0], np.cumsum(units)]))
+    want_units = []
+    for s in range(ref["n_seg"]):
+        if ref["seg_adapter"][s] < 0:
+            continue
+        for slot0 in range(int(ref["seg_indptr"][s]), int(ref["seg_indptr"][s + 1]), 64):
+            want_units.append([int(ref["seg_adapter"][s]), int(ref["seg_rank"][s]), slot0,
+                               min(64, int(ref["seg_indptr"][s + 1]) - slot0)])
+    assert got["unit_rec"].tolist() == want_units
     rec = got["ext_rec"]
     q = 0
     for s in range(ref["n_seg"]):
