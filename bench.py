@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
     ap.add_argument("--option", action="append", default=[], help="tuning override name=value (lora_ctx_set_option)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 256 MiB device copy kernel 5 times and exit (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU (the layer shards by requests, one library instance "
@@ -58,6 +60,15 @@ def main():
 
     import numpy as np
     import torch
+    if args.calibrate_copy:
+        n = 256 << 20
+        src = torch.ones(n // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 5}))
+        return
     from paper_2505_14468_amd import binding as B
     from paper_2505_14468_amd import runtime as rt
     from workloads import make_workload, to_f64

@@ -87,17 +87,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     const E *xsrc[XL];
     int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
-    for (int i = 0; i < XL; ++i) {
-        const int t = m0 + lrow + i * RPP;
-        xrowi[i] = t < p.T ? p.plan.perm[t] : 0;
-        xsrc[i] = t < p.T ? X + (int64_t)xrowi[i] * p.ldx : nullptr;
+    for (int i = 0; i < XL; ++i) {  // rows past T / N are clamped: they only feed outputs that are never stored
+        xrowi[i] = p.plan.perm[min(m0 + lrow + i * RPP, p.T - 1)];
+        xsrc[i] = X + (int64_t)xrowi[i] * p.ldx;
     }
     const E *wsrc[WL];
 #pragma unroll
-    for (int i = 0; i < WL; ++i) {
-        const int n = n0 + lrow + i * RPP;
-        wsrc[i] = n < p.N ? W + (int64_t)n * p.ldw : nullptr;
-    }
+    for (int i = 0; i < WL; ++i) wsrc[i] = W + (int64_t)min(n0 + lrow + i * RPP, p.N - 1) * p.ldw;
 
     // ---- extension range of this M-tile -----------------------------------------------------
     int pbeg = 0, pend = 0;
@@ -146,13 +142,23 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 
     chunk_t xr[XL], wr[WL];
 
-    auto load_base = [&](int kt) {
+    // Loads are branch-free so that all of a stage's loads are in flight together.  Full stages need
+    // no mask at all; the last, partial stage of K loads chunk 0 instead and drops it.
+    auto load_base = [&](int kt, bool partial) {
         const int kc = kt * 8 + lc;
-        const bool kv = kc * CE < p.K;
+        if (!partial) {
 #pragma unroll
-        for (int i = 0; i < XL; ++i) xr[i] = (kv && xsrc[i] != nullptr) ? load_chunk(xsrc[i] + kc * CE) : zero_chunk();
+            for (int i = 0; i < XL; ++i) xr[i] = load_chunk(xsrc[i] + kc * CE);
 #pragma unroll
-        for (int i = 0; i < WL; ++i) wr[i] = (kv && wsrc[i] != nullptr) ? load_chunk(wsrc[i] + kc * CE) : zero_chunk();
+            for (int i = 0; i < WL; ++i) wr[i] = load_chunk(wsrc[i] + kc * CE);
+        } else {
+            const bool kv = kc * CE < p.K;
+            const int off = kv ? kc * CE : 0;
+#pragma unroll
+            for (int i = 0; i < XL; ++i) xr[i] = keep_if(kv, load_chunk(xsrc[i] + off));
+#pragma unroll
+            for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, load_chunk(wsrc[i] + off));
+        }
     };
     auto load_ext = [&](int se) {  // se = stage inside the current table batch
         const int idx = se * 8 + lc;
@@ -161,12 +167,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             const int row = lrow + i * RPP;
-            xr[i] = (row >= lo && row < hi) ? load_chunk(V + (int64_t)xrowi[i] * p.r_max + j) : zero_chunk();
+            const bool ok = row >= lo && row < hi;  // rows of other adapters contribute nothing
+            xr[i] = keep_if(ok, load_chunk(V + (ok ? (int64_t)xrowi[i] * p.r_max + j : 0)));
         }
+        const bool wok = bp != nullptr;
+        const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
 #pragma unroll
         for (int i = 0; i < WL; ++i) {
-            const int n = n0 + lrow + i * RPP;
-            wr[i] = (bp != nullptr && n < p.N) ? load_chunk(bp + (int64_t)n * r) : zero_chunk();
+            const int n = min(n0 + lrow + i * RPP, p.N - 1);
+            wr[i] = keep_if(wok, load_chunk(bsrc + (wok ? (int64_t)n * r : 0)));
         }
     };
     auto store_stage = [&](int buf) {
@@ -205,12 +214,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 
     // ---- base product: sum over K ---------------------------------------------------------------
     const int KT = (p.K + 8 * CE - 1) / (8 * CE);
-    load_base(0);
+    const int KT_full = p.K / (8 * CE);  // stages that lie entirely inside K
+    load_base(0, KT_full < 1);
     store_stage(0);
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
         const bool more = kt + 1 < KT;
-        if (more) load_base(kt + 1);
+        if (more) load_base(kt + 1, kt + 1 >= KT_full);
         compute(kt & 1, -1);
         if (more) store_stage((kt + 1) & 1);
         __syncthreads();
@@ -290,6 +300,8 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
             return launch_tile<E, 256, 128, 4, 2>(a, stream, timer);
         case kGemmTile256x256:
             return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
+        case kGemmTile256x256w4:
+            return launch_tile<E, 256, 256, 2, 2>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

@@ -97,10 +97,15 @@ enum GemmVariant {
     kGemmTile256x256 = 2,
     kGemmTile64x64 = 3,
     kGemmSkinny = 4,
+    kGemmTile256x256w4 = 5,  // 256x256 tile on 4 waves (128x128 per wave)
+    kGemmPipe256x256k32 = 6,  // direct-to-LDS pipeline, 4 stage buffers of 32 k (bf16)
+    kGemmPipe256x256k64 = 7,  // direct-to-LDS pipeline, 2 stage buffers of 64 k
+    kGemmPipe128x128k64 = 8,  // direct-to-LDS pipeline, 128x128 tile, 4 stage buffers of 64 k
     kGemmVariantCount
 };
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
+hipError_t launch_gemm_pipe(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer);
 
 // Geometry of the skinny kernel shared with the host (workspace sizing).

@@ -294,7 +294,7 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         c.nb = nb;
         return c;
     }
-    if (forced >= 0 && forced < kGemmSkinny) {
+    if (forced >= 0 && forced != kGemmSkinny) {
         c.variant = forced;
         return c;
     }
@@ -447,6 +447,8 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     const bool timed = next_timer(ctx, kProfGemm, &timer);
     if (c.variant == kGemmSkinny)
         LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
+    else if (c.variant >= kGemmPipe256x256k32)
+        LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
@@ -689,6 +691,18 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
             break;
         case kGemmTile256x256:
             snprintf(buf, sizeof buf, "tile_256x256");
+            break;
+        case kGemmTile256x256w4:
+            snprintf(buf, sizeof buf, "tile_256x256w4");
+            break;
+        case kGemmPipe256x256k32:
+            snprintf(buf, sizeof buf, "pipe_256x256_k32x4");
+            break;
+        case kGemmPipe256x256k64:
+            snprintf(buf, sizeof buf, "pipe_256x256_k64x2");
+            break;
+        case kGemmPipe128x128k64:
+            snprintf(buf, sizeof buf, "pipe_128x128_k64x4");
             break;
         default:
             snprintf(buf, sizeof buf, "unknown");
