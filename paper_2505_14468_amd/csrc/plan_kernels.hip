@@ -38,6 +38,66 @@ __device__ int block_exscan(int v, int &total, int *wave_sums) {
     return base + inc - v;
 }
 
+// For the 64 requests of one wave: rows of earlier lanes with the same key (off), and whether
+// this lane is the last one with its key.  Fully unrolled so that every cross-lane read is a
+// v_readlane with a constant lane index (a handful of cycles; a shuffle through the LDS crossbar
+// costs two orders of magnitude more latency and this loop is serial).
+__device__ __forceinline__ void rank_among_equal_keys(int key, int L, int lane, int &off, bool &last) {
+#pragma unroll
+    for (int l2 = 0; l2 < 64; ++l2) {
+        const int k2 = __builtin_amdgcn_readlane(key, l2);
+        const int L2 = __builtin_amdgcn_readlane(L, l2);
+        if (k2 == key) {
+            if (l2 < lane)
+                off += L2;
+            else if (l2 > lane)
+                last = false;
+        }
+    }
+}
+
+// Four exclusive scans at once (their cross-lane steps overlap instead of running back to back).
+__device__ void block_exscan4(int4 v, int4 &ex, int4 &total, int *wave_sums /* [4][kPlanWaves] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int4 inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int ox = __shfl_up(inc.x, d), oy = __shfl_up(inc.y, d), oz = __shfl_up(inc.z, d), ow = __shfl_up(inc.w, d);
+        if (lane >= d) {
+            inc.x += ox;
+            inc.y += oy;
+            inc.z += oz;
+            inc.w += ow;
+        }
+    }
+    __syncthreads();  // wave_sums may still be read from the previous call
+    if (lane == 63) {
+        wave_sums[0 * kPlanWaves + wave] = inc.x;
+        wave_sums[1 * kPlanWaves + wave] = inc.y;
+        wave_sums[2 * kPlanWaves + wave] = inc.z;
+        wave_sums[3 * kPlanWaves + wave] = inc.w;
+    }
+    __syncthreads();
+    int4 base = make_int4(0, 0, 0, 0), tot = make_int4(0, 0, 0, 0);
+#pragma unroll
+    for (int w = 0; w < kPlanWaves; ++w) {
+        const int a = wave_sums[0 * kPlanWaves + w], b = wave_sums[1 * kPlanWaves + w], c = wave_sums[2 * kPlanWaves + w],
+                  d = wave_sums[3 * kPlanWaves + w];
+        if (w < wave) {
+            base.x += a;
+            base.y += b;
+            base.z += c;
+            base.w += d;
+        }
+        tot.x += a;
+        tot.y += b;
+        tot.z += c;
+        tot.w += d;
+    }
+    total = tot;
+    ex = make_int4(base.x + inc.x - v.x, base.y + inc.y - v.y, base.z + inc.z - v.z, base.w + inc.w - v.w);
+}
+
 // perm / row_seg: one thread per original row.
 __device__ void fill_rows(const PlanBuildArgs &p, int start, int stride) {
     const int T = p.T, R = p.n_req;
@@ -196,11 +256,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
                 }
                 units = (h + kShrinkRows - 1) / kShrinkRows;
             }
-            int t_seg, t_row, t_ext, t_unit;
-            const int e_seg = block_exscan(flag, t_seg, wave_sums[0]);
-            const int e_row = block_exscan(h, t_row, wave_sums[1]);
-            const int e_ext = block_exscan(rk, t_ext, wave_sums[2]);
-            const int e_unit = block_exscan(units, t_unit, wave_sums[3]);
+            int4 ex4, tot4;
+            block_exscan4(make_int4(flag, h, rk, units), ex4, tot4, &wave_sums[0][0]);
+            const int e_seg = ex4.x, e_row = ex4.y, e_ext = ex4.z, e_unit = ex4.w;
+            const int t_seg = tot4.x, t_row = tot4.y, t_ext = tot4.z, t_unit = tot4.w;
             if (flag) {
                 const int s = c_seg + e_seg;
                 p.seg_adapter[s] = k < n_ad ? k : -1;
@@ -251,16 +310,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
             const int key = valid ? (a < 0 ? n_ad : a) : -2;
             int off = 0;
             bool last = true;
-            for (int l2 = 0; l2 < 64; ++l2) {
-                const int k2 = __shfl(key, l2);
-                const int L2 = __shfl(L, l2);
-                if (k2 == key) {
-                    if (l2 < lane)
-                        off += L2;
-                    else if (l2 > lane)
-                        last = false;
-                }
-            }
+            rank_among_equal_keys(key, L, lane, off, last);
             int b = 0;
             if (valid) {
                 b = cur[key];
@@ -280,6 +330,238 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
     }
 }
 
+// Small batches (the common case in serving: at most 2048 requests, 2047 adapter slots, 8192 rows):
+// the same algorithm with every intermediate array in LDS, so that the only global round trips
+// are the initial read of the request arrays and the final writes.  Latency, not bytes, is what
+// this kernel costs.
+constexpr int kSmallReq = 2048;
+constexpr int kSmallKeys = 2048;
+constexpr int kSmallRows = 8192;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs p) {
+    __shared__ int s_a[kSmallReq], s_L[kSmallReq + 64], s_key[kSmallReq + 64], s_tok[kSmallReq + 1], s_dst[kSmallReq];
+    __shared__ int s_hist[kSmallKeys], s_cur[kSmallKeys], s_kseg[kSmallKeys];
+    __shared__ int s_sad[kSmallKeys + 1], s_sip[kSmallKeys + 1], s_srk[kSmallKeys + 1], s_sex[kSmallKeys + 1], s_sun[kSmallKeys + 1];
+    __shared__ int wave_sums[4][kPlanWaves];
+    __shared__ int s_status;
+    __shared__ unsigned long long s_sum;
+    const int tid = threadIdx.x;
+    const int R = p.n_req, n_ad = p.n_adapters;
+
+    for (int i = tid; i < R + 64; i += kPlanThreads) {
+        const int a = i < R ? p.req_adapter[i] : -3;
+        if (i < R) s_a[i] = a;
+        s_L[i] = i < R ? p.req_ntok[i] : 0;
+        s_key[i] = a < -1 ? -3 : (a < 0 ? n_ad : a);  // key n_ad = "no adapter"; the tail matches nothing
+    }
+    for (int k = tid; k <= n_ad; k += kPlanThreads) s_hist[k] = 0;
+    if (tid == 0) {
+        s_status = 0;
+        s_sum = 0ull;
+    }
+    __syncthreads();
+
+    // 1. validate, histogram of rows per key
+    {
+        unsigned long long local = 0ull;
+        int st = 0;
+        for (int i = tid; i < R; i += kPlanThreads) {
+            const int a = s_a[i], L = s_L[i];
+            if (a < -1 || a >= n_ad) {
+                st = min(st, kErrBadAdapterId);
+            } else if (L < 0) {
+                st = min(st, kErrLengthMismatch);
+            } else if (L > 0) {
+                local += (unsigned long long)L;
+                atomicAdd(&s_hist[a < 0 ? n_ad : a], L);
+            }
+        }
+        if (st != 0) atomicMin(&s_status, st);
+        if (local != 0ull) atomicAdd(&s_sum, local);
+    }
+    __syncthreads();
+    if (tid == 0 && s_status == 0 && s_sum != (unsigned long long)(unsigned)p.T) s_status = kErrLengthMismatch;
+    __syncthreads();
+    if (s_status != 0) {
+        if (tid == 0) write_failed(p, s_status);
+        return;
+    }
+
+    // 2. first row of every request
+    {
+        int carry = 0;
+        for (int base = 0; base < R; base += kPlanThreads) {
+            const int i = base + tid;
+            const int v = i < R ? s_L[i] : 0;
+            int tot;
+            const int ex = block_exscan(v, tot, wave_sums[0]);
+            if (i < R) {
+                s_tok[i] = carry + ex;
+                p.tok_off[i] = carry + ex;
+            }
+            carry += tot;
+        }
+        if (tid == 0) {
+            s_tok[R] = carry;
+            p.tok_off[R] = carry;
+        }
+    }
+
+    // 3. segments
+    int c_seg = 0, c_row = 0, c_ext = 0, c_unit = 0;
+    {
+        int st = 0;
+        for (int base = 0; base <= n_ad; base += kPlanThreads) {
+            const int k = base + tid;
+            const int h = k <= n_ad ? s_hist[k] : 0;
+            const int flag = h > 0 ? 1 : 0;
+            int rk = 0, units = 0;
+            if (flag && k < n_ad) {
+                rk = p.rank[k];
+                if (rk <= 0) {
+                    st = min(st, kErrNotResident);
+                    rk = 0;
+                } else if (rk & 7) {
+                    st = min(st, kErrShape);
+                    rk = 0;
+                } else if (rk > p.r_max) {
+                    st = min(st, kErrRankTooLarge);
+                    rk = 0;
+                }
+                units = (h + kShrinkRows - 1) / kShrinkRows;
+            }
+            int4 ex4, tot4;
+            block_exscan4(make_int4(flag, h, rk, units), ex4, tot4, &wave_sums[0][0]);
+            const int e_seg = ex4.x, e_row = ex4.y, e_ext = ex4.z, e_unit = ex4.w;
+            const int t_seg = tot4.x, t_row = tot4.y, t_ext = tot4.z, t_unit = tot4.w;
+            if (flag) {
+                const int s = c_seg + e_seg;
+                s_sad[s] = k < n_ad ? k : -1;
+                s_sip[s] = c_row + e_row;
+                s_srk[s] = rk;
+                s_sex[s] = c_ext + e_ext;
+                s_sun[s] = c_unit + e_unit;
+                s_cur[k] = c_row + e_row;
+                s_kseg[k] = s;
+            } else if (k <= n_ad) {
+                s_kseg[k] = -1;
+            }
+            c_seg += t_seg;
+            c_row += t_row;
+            c_ext += t_ext;
+            c_unit += t_unit;
+        }
+        if (st != 0) atomicMin(&s_status, st);
+    }
+    __syncthreads();
+    if (s_status != 0) {
+        if (tid == 0) write_failed(p, s_status);
+        return;
+    }
+    if (tid == 0) {
+        s_sip[c_seg] = c_row;
+        s_sex[c_seg] = c_ext;
+        s_sun[c_seg] = c_unit;
+        p.scalars[kScNSeg] = c_seg;
+        p.scalars[kScStatus] = 0;
+        p.scalars[kScExtTotal] = c_ext;
+        p.scalars[kScNUnits] = c_unit;
+        p.scalars[kScT] = c_row;
+    }
+    __syncthreads();
+    for (int s = tid; s <= c_seg; s += kPlanThreads) {  // publish the segment arrays
+        if (s < c_seg) {
+            p.seg_adapter[s] = s_sad[s];
+            p.seg_rank[s] = s_srk[s];
+        }
+        p.seg_indptr[s] = s_sip[s];
+        p.seg_ext[s] = s_sex[s];
+        p.seg_unit[s] = s_sun[s];
+    }
+
+    // 4. stable destination of every request: one wave, 64 requests at a time.  Every lane compares its
+    //    key with the 64 keys of the chunk, which it reads from LDS (same address for all lanes: a
+    //    broadcast); the loads pipeline, and there is no cross-lane instruction on the serial path.
+    if (tid < 64) {
+        volatile int *cur = s_cur;
+        const int lane = tid;
+        for (int base = 0; base < R; base += 64) {
+            const int i = base + lane;
+            const bool valid = i < R;
+            const int key = valid ? s_key[i] : -2;
+            const int L = valid ? s_L[i] : 0;
+            int off = 0, later = 0;
+#pragma unroll 8
+            for (int l2 = 0; l2 < 64; ++l2) {
+                const bool same = s_key[base + l2] == key;  // entries past R hold -3
+                off += (same && l2 < lane) ? s_L[base + l2] : 0;
+                later |= (same && l2 > lane) ? 1 : 0;
+            }
+            int b = 0;
+            if (valid) {
+                b = cur[key];
+                s_dst[i] = b + off;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // all lanes have read before any lane writes
+            if (valid && !later) cur[key] = b + off + L;
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        }
+    }
+    __syncthreads();
+
+    // 5. per-row scatter
+    for (int t = tid; t < c_row; t += kPlanThreads) {
+        int lo = 0, hi = R;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_tok[mid + 1] > t)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int a = s_a[lo];
+        const int slot = s_dst[lo] + (t - s_tok[lo]);
+        p.perm[slot] = t;
+        p.row_seg[slot] = s_kseg[a < 0 ? n_ad : a];
+        p.row_adapter[t] = a;
+    }
+    // 6. one record per 8 ranks of the extension axis, one per shrink work unit
+    for (int q = tid; q < (c_ext >> 3); q += kPlanThreads) {
+        const int pel = q << 3;
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sex[mid + 1] > pel)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = (s_srk[lo] << 16) | (pel - s_sex[lo]);
+        rec.z = s_sip[lo];
+        rec.w = s_sip[lo + 1];
+        reinterpret_cast<int4 *>(p.ext_rec)[q] = rec;
+    }
+    for (int u = tid; u < c_unit; u += kPlanThreads) {
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sun[mid + 1] > u)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = s_srk[lo];
+        rec.z = slot0;
+        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
+    }
+}
+
 __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
     if (p.scalars[kScStatus] != 0) return;
     const int start = blockIdx.x * 256 + threadIdx.x;
@@ -292,6 +574,8 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
 }  // namespace
 
 hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream, const KernelTimer *timers) {
+    if (fuse_fill && a.n_req <= kSmallReq && a.n_adapters + 1 <= kSmallKeys && a.T <= kSmallRows)
+        return launch_kernel(plan_small_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
     hipError_t e = launch_kernel(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a,
                                  fuse_fill ? 1 : 0);
     if (e != hipSuccess) return e;

@@ -60,7 +60,8 @@ def test_plan_random(seed, device_plan):
     ranks = rng.choice([8, 16, 32, 64], size=n_ad)
     ids = rng.integers(-1, n_ad, size=R)
     L = rng.integers(0, 9, size=R)
-    _check_plan(ids, L, ranks, device_plan)
+    _check_plan(ids, L, ranks, device_plan)                 # LDS-resident small-batch kernel
+    _check_plan(ids, L, ranks, device_plan, fused_rows=0)   # general kernels (segments + grid-wide fill)
 
 
 @pytest.mark.parametrize("fused_rows", [0, 1 << 20])
