@@ -4,29 +4,38 @@
 //
 // (paper section 4.4: backbone result and adapter result are combined; here in the fp32
 // accumulators, before Y is rounded and stored, once.)  Same tiling, MFMA orientation, row
-// order and extension logic as gemm_tile_kernel.hip; what differs is how the base product is fed:
+// order and extension logic as gemm_tile_kernel.hip; what differs is how the base product is fed,
+// so that the matrix core never waits at a stage boundary:
 //
-//   * global -> LDS directly (global_load_lds_dwordx4): no staging registers, no ds_write, and the
-//     loads of several stages stay in flight while the matrix core works.  A wave-level load
-//     writes 64 consecutive 16-byte LDS slots, so the XOR swizzle that keeps the MFMA operand
-//     reads conflict-free is applied on the global side: the lane that fills slot (row, pos)
-//     fetches chunk pos ^ swz(row) of that row (still one contiguous row segment per row);
-//   * NBUF stage buffers in a ring, each its own LDS array, so that the compiler can tell that
-//     reading one buffer does not depend on the loads in flight into another; the waits for
-//     "my loads of stage kt have landed" are explicit vmcnt waits with the number of younger
-//     loads, followed by a bare s_barrier (all threads' loads landed / all waves are done
-//     with the buffer that is about to be refilled);
-//   * one barrier per stage, nothing else synchronises.
+//   * global -> LDS directly (buffer_load_dwordx4 ... lds): no staging registers, no ds_write, and the
+//     loads of two stages stay in flight while the matrix core works.  A wave-level load writes 64
+//     consecutive 16-byte LDS slots, so the XOR swizzle that keeps the MFMA operand reads
+//     conflict-free is applied on the global side: the lane that fills slot (row, pos) fetches
+//     chunk pos ^ swz(row) of that row (still one contiguous row segment per row);
+//   * a ring of four stage buffers (a stage = 4 chunks = 32 bf16 k per row); "my loads of stage
+//     s+1 have landed" is an explicit vmcnt wait with the number of younger loads, followed by a
+//     bare s_barrier;
+//   * that one barrier per stage sits in the MIDDLE of the stage: it certifies stage s+1 (all
+//     threads' loads landed) and frees the buffer of stage s-1 (all waves are past it), so the
+//     operand reads are software-pipelined straight across stage boundaries: while the MFMAs of one
+//     half-stage run, the LDS reads of the next half-stage (possibly of the next stage) are in
+//     flight.  A micro-benchmark of exactly this loop shape sustains ~1.9 PFLOP/s of the 2.5 peak
+//     with a barrier every 16 MFMAs, against ~1.0 when the reads start after the barrier;
+//   * the operand reads of that loop are issued as ds_read_b128 with explicit lgkmcnt waits: written
+//     as ordinary LDS array reads, the compiler cannot tell that a read of one buffer does not
+//     depend on the loads in flight into another and drains them all before every read.
 // A trailing partial K stage and the extension stages (masked V rows, B_a gathered through the
-// table) go through registers (load, mask, ds_write) into the same buffers.
+// table) go through registers (load, mask, ds_write) into the same buffers, with ordinary reads.
 #include <limits.h>
+
+#include <type_traits>
+#include <utility>
 
 #include "kernels.h"
 
 namespace lora {
 namespace {
 
-#define LORA_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define LORA_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 constexpr int kPipeTab = 256;  // extension chunk columns described per batch
@@ -38,6 +47,8 @@ struct PipeTable {
     int lo[kPipeTab];           // tile-relative rows [lo, hi) that belong to the adapter
     int hi[kPipeTab];
 };
+
+typedef unsigned raw4_t __attribute__((ext_vector_type(4)));  // a 16-byte chunk as the register quad an LDS read fills
 
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14])
 template <int N>
@@ -51,24 +62,49 @@ __device__ __forceinline__ int swz(int row) {
     return BKC == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 
-template <typename E, int BM, int BN, int WM, int WN, int BKC, int NBUF>
+// Issue one 16-byte LDS read at addr + OFF.  The destination is valid only after lds_settle() has
+// waited for it: until then nothing may touch the value.
+template <int OFF>
+__device__ __forceinline__ raw4_t lds_read_async(unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536, "ds_read immediate offset range");
+    raw4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+template <int OFF, int STRIDE, int... I>
+__device__ __forceinline__ void lds_read_async_seq(raw4_t *dst, unsigned addr, std::integer_sequence<int, I...>) {
+    ((dst[I] = lds_read_async<OFF + I * STRIDE>(addr)), ...);
+}
+// Wait until at most YOUNGER LDS reads are outstanding (they return in order), and make every later
+// use of the N values in v depend on that wait.
+template <int YOUNGER, int N>
+__device__ __forceinline__ void lds_settle(raw4_t (&v)[N]) {
+    static_assert(YOUNGER >= 0 && YOUNGER < 16, "lgkmcnt range");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(YOUNGER) : "memory");
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]));
+}
+
+template <typename E, int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int tiles_m, int tiles_n, int group_m) {
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass only needs the launch stub (and has no buffer-resource type)
     constexpr int CE = Elem<E>::CE;
+    constexpr int BKC = 4;  // chunks per row per stage
     constexpr int NT = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile: rows t, columns n
     constexpr int NBT = WTM / 32, NBN = WTN / 32;
     constexpr int ROWS = BN + BM;                 // W rows first, then X rows
+    constexpr int SLOTS = ROWS * BKC;             // chunks per stage buffer
+    constexpr int STAGE_BYTES = SLOTS * 16;
     constexpr int LPT = ROWS * BKC / NT;          // 16-byte loads per thread per stage
     constexpr int RPP = NT / BKC;                 // rows covered per load pass
     constexpr int SUB = BKC / 2;                  // MFMA substeps per stage
-    static_assert(NBUF == 2 || NBUF == 4, "ring of 2 or 4 stage buffers");
+    constexpr int NR = NBN + NBT;                 // LDS reads per half-stage
     static_assert(ROWS * BKC % NT == 0 && NBT >= 1 && NBN >= 1, "tile / workgroup mismatch");
 
-    __shared__ __attribute__((aligned(16))) chunk_t s0[ROWS * BKC];
-    __shared__ __attribute__((aligned(16))) chunk_t s1[ROWS * BKC];
-    __shared__ __attribute__((aligned(16))) chunk_t s2[NBUF == 4 ? ROWS * BKC : 1];
-    __shared__ __attribute__((aligned(16))) chunk_t s3[NBUF == 4 ? ROWS * BKC : 1];
+    __shared__ __attribute__((aligned(16))) chunk_t ring[4 * SLOTS];
     __shared__ PipeTable tab;
+    chunk_t *const s0 = ring, *const s1 = ring + SLOTS;
 
     if (p.plan.scalars[kScStatus] != 0) return;
 
@@ -86,7 +122,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
     const int m0 = pm * BM, n0 = pn * BN;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn0 = (wave % WN) * WTN, wm0 = (wave / WN) * WTM;
     const int l31 = lane & 31, lh = lane >> 5;
 
@@ -95,16 +131,21 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
     const E *V = static_cast<const E *>(p.V);
 
     // ---- per-thread load slots: LDS slot (row, pos) of pass i is filled with chunk pos ^ swz(row) ----
+    // Addressed as buffer loads: base in SGPRs, one 32-bit byte offset per lane, the stage's K offset
+    // in an SGPR, so a stage costs no address arithmetic.
+    static_assert(BN % RPP == 0, "a load pass must not straddle W rows and X rows");
     const int lpos = tid % BKC;
-    const E *src[LPT];   // row base in global memory (W0 row or gathered X row), plus the swizzled chunk offset
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(const_cast<E *>(W), 0, 0x7fffffff, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsX = __builtin_amdgcn_make_buffer_rsrc(const_cast<E *>(X), 0, 0x7fffffff, 0x00020000);
+    int voff[LPT];  // byte offset of (row, swizzled chunk) from the W0 / X base; the host checked that it fits 31 bits
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
         const int row = tid / BKC + i * RPP;
         const int c = lpos ^ swz<BKC>(row);
         if (row < BN)  // rows past N / T are clamped: they only feed outputs that are never stored
-            src[i] = W + (int64_t)min(n0 + row, p.N - 1) * p.ldw + c * CE;
+            voff[i] = (int)(((int64_t)min(n0 + row, p.N - 1) * p.ldw + c * CE) * (int64_t)sizeof(E));
         else
-            src[i] = X + (int64_t)p.plan.perm[min(m0 + row - BN, p.T - 1)] * p.ldx + c * CE;
+            voff[i] = (int)(((int64_t)p.plan.perm[min(m0 + row - BN, p.T - 1)] * p.ldx + c * CE) * (int64_t)sizeof(E));
     }
 
     // ---- extension range of this M-tile -----------------------------------------------------
@@ -131,92 +172,89 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
     for (int nb = 0; nb < NBN; ++nb) wpos[nb] = (wn0 + nb * 32 + l31) * BKC;
 #pragma unroll
     for (int tb = 0; tb < NBT; ++tb) xpos[tb] = (BN + wm0 + tb * 32 + l31) * BKC;
-    int wsw[NBN], xsw[NBT];
-#pragma unroll
-    for (int nb = 0; nb < NBN; ++nb) wsw[nb] = swz<BKC>(wn0 + nb * 32 + l31);
-#pragma unroll
-    for (int tb = 0; tb < NBT; ++tb) xsw[tb] = swz<BKC>(BN + wm0 + tb * 32 + l31);
-
-    // full MFMA work of one stage
-    auto compute = [&](const chunk_t *buf) {
-#pragma unroll
-        for (int kk = 0; kk < SUB; ++kk) {
-            const int cc = 2 * kk + lh;
-            chunk_t wf[NBN], xf[NBT];
-#pragma unroll
-            for (int nb = 0; nb < NBN; ++nb) wf[nb] = buf[wpos[nb] + (cc ^ wsw[nb])];
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb) xf[tb] = buf[xpos[tb] + (cc ^ xsw[tb])];
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb)
-#pragma unroll
-                for (int nb = 0; nb < NBN; ++nb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[tb]);
-        }
-    };
-    // asynchronous fill of a stage buffer with stage kt of the base product
-    auto dma = [&](chunk_t *buf, int kt) {
-#pragma unroll
-        for (int i = 0; i < LPT; ++i)
-            __builtin_amdgcn_global_load_lds(LORA_GPTR(src[i] + (int64_t)kt * (BKC * CE)), LORA_LPTR(buf + i * NT + wave * 64), 16, 0,
-                                             0);
-    };
+    const int lsw = swz<BKC>(l31);  // wave tiles start at multiples of 32 rows: the swizzle depends on the lane only
 
     // ---- base product over the stages that lie entirely inside K ----------------------------------
-    const int KT_full = p.K / (BKC * CE);
-    // One pipeline step: wait for my loads of stage kt, let everybody arrive (all loads of the stage
-    // landed, all waves done with the buffer read last step), refill that buffer, compute.
-    // Steady state: every step has NBUF-1 younger stages and no branch.
-#define LORA_PIPE_STEP(BUF, REFILL, KT_)          \
-    do {                                          \
-        wait_vmcnt<(NBUF - 2) * LPT>();           \
-        __builtin_amdgcn_s_barrier();             \
-        dma(REFILL, (KT_) + NBUF - 1);            \
-        compute(BUF);                             \
-    } while (0)
-    // Drain: the last stages, where younger stages may be missing (then wait for everything).
-#define LORA_PIPE_DRAIN(BUF, REFILL, KT_)                                   \
-    do {                                                                     \
-        const int kt_ = (KT_);                                               \
-        if (kt_ < KT_full) {                                                 \
-            if (kt_ + NBUF - 1 <= KT_full)                                   \
-                wait_vmcnt<(NBUF - 2) * LPT>();                              \
-            else                                                             \
-                wait_vmcnt<0>();                                             \
-            __builtin_amdgcn_s_barrier();                                    \
-            if (kt_ + NBUF - 1 < KT_full) dma(REFILL, kt_ + NBUF - 1);       \
-            compute(BUF);                                                    \
-        }                                                                    \
-    } while (0)
-
-    int kt = 0;
-    if (KT_full > 0) dma(s0, 0);
-    if constexpr (NBUF == 4) {
-        if (KT_full > 1) dma(s1, 1);
-        if (KT_full > 2) dma(s2, 2);
-        for (; kt + 2 * NBUF - 2 < KT_full; kt += 4) {
-            LORA_PIPE_STEP(s0, s3, kt);
-            LORA_PIPE_STEP(s1, s0, kt + 1);
-            LORA_PIPE_STEP(s2, s1, kt + 2);
-            LORA_PIPE_STEP(s3, s2, kt + 3);
-        }
-        for (; kt < KT_full; kt += 4) {
-            LORA_PIPE_DRAIN(s0, s3, kt);
-            LORA_PIPE_DRAIN(s1, s0, kt + 1);
-            LORA_PIPE_DRAIN(s2, s1, kt + 2);
-            LORA_PIPE_DRAIN(s3, s2, kt + 3);
-        }
-    } else {
-        for (; kt + 2 * NBUF - 2 < KT_full; kt += 2) {
-            LORA_PIPE_STEP(s0, s1, kt);
-            LORA_PIPE_STEP(s1, s0, kt + 1);
-        }
-        for (; kt < KT_full; kt += 2) {
-            LORA_PIPE_DRAIN(s0, s1, kt);
-            LORA_PIPE_DRAIN(s1, s0, kt + 1);
+    // operand fragments of one half-stage (two chunk columns = 16 bf16 k per lane pair)
+    struct Frag {
+        raw4_t w[NBN], x[NBT];
+    };
+    // LDS byte addresses of this lane's operand chunk in row block 0 of buffer 0, per half (the other
+    // half is the chunk position with bit 1 flipped); row blocks are immediate offsets, the buffer is added.
+    unsigned aW[2], aX[2];
+    {
+        const unsigned base = (unsigned)(size_t)LORA_LPTR(ring);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            aW[kk] = base + (unsigned)(wpos[0] + ((2 * kk + lh) ^ lsw)) * 16u;
+            aX[kk] = base + (unsigned)(xpos[0] + ((2 * kk + lh) ^ lsw)) * 16u;
         }
     }
-#undef LORA_PIPE_DRAIN
-#undef LORA_PIPE_STEP
+    auto read_half = [&](int buf, auto kk_, Frag &f) {
+        constexpr int KK = decltype(kk_)::value;
+        const unsigned off = (unsigned)buf * STAGE_BYTES;
+        lds_read_async_seq<0, 32 * BKC * 16>(f.w, aW[KK] + off, std::make_integer_sequence<int, NBN>{});
+        lds_read_async_seq<0, 32 * BKC * 16>(f.x, aX[KK] + off, std::make_integer_sequence<int, NBT>{});
+    };
+    auto settle = [&](auto younger_, Frag &f) {
+        constexpr int Y = decltype(younger_)::value;
+        lds_settle<Y>(f.w);
+        lds_settle<Y>(f.x);
+    };
+    auto mma_half = [&](const Frag &f) {
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb)
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb)
+                Elem<E>::mma32(acc[nb][tb], __builtin_bit_cast(chunk_t, f.w[nb]), __builtin_bit_cast(chunk_t, f.x[tb]));
+    };
+    // asynchronous fill of a stage buffer with stage kt of the base product
+    auto dma = [&](int buf, int kt) {
+        const int koff = kt * (BKC * CE * (int)sizeof(E));
+        chunk_t *dst = ring + buf * SLOTS + wave * 64;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(i * RPP < BN ? rsW : rsX, LORA_LPTR(dst + i * NT), 16, voff[i], koff, 0, 0);
+    };
+
+    const int KT_full = p.K / (BKC * CE);
+    if (KT_full > 0) {
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using INR = std::integral_constant<int, NR>;
+        const int last = KT_full - 1;
+        Frag fa, fb;  // fa: first half of the current stage, fb: second half
+        dma(0, 0);
+        dma(1, min(1, last));
+        dma(2, min(2, last));
+        wait_vmcnt<2 * LPT>();
+        __builtin_amdgcn_s_barrier();
+        read_half(0, I0(), fa);
+        // One stage per trip (stage s in buffer s % 4): the reads of half 2 fly during the MFMAs of
+        // half 1; then wait for my loads of stage s+1 (stage s+2 may stay in flight), barrier, refill
+        // the buffer that held stage s-1, and the reads of stage s+1's half 1 fly during half 2.
+        // Stages past the end are replaced by a reload of the last one, whose buffer is then never
+        // consumed: every trip has the same shape, and the wait counts hold up to the last trip.
+        // (the sched_barriers pin the order "issue the reads, then the MFMAs that hide them")
+#pragma unroll 1
+        for (int s = 0; s < KT_full; ++s) {
+            read_half(s & 3, I1(), fb);
+            settle(INR(), fa);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_half(fa);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmcnt<LPT>();
+            __builtin_amdgcn_s_barrier();
+            dma((s + 3) & 3, min(s + 3, last));
+            read_half((s + 1) & 3, I0(), fa);
+            settle(INR(), fb);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_half(fb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        settle(I0(), fa);  // the last trip's look-ahead reads: nothing may reuse their registers before they land
+        wait_vmcnt<0>();
+    }
     __syncthreads();  // every load has landed and every wave is done with the ring
 
     // ---- staged tail: a partial last K stage, then the extension stages --------------------------------
@@ -236,7 +274,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
         for (int i = 0; i < LPT; ++i) {
             const int c = lpos ^ swz<BKC>(srow[i]);
             const bool kv = (KT_full * BKC + c) * CE < p.K;
-            regs[i] = keep_if(kv, load_chunk(kv ? src[i] + (int64_t)KT_full * (BKC * CE) : src[i] - c * CE));
+            const E *rowp = xrowi[i] < 0 ? W + (int64_t)min(n0 + srow[i], p.N - 1) * p.ldw : X + (int64_t)xrowi[i] * p.ldx;
+            regs[i] = keep_if(kv, load_chunk(kv ? rowp + (int64_t)(KT_full * BKC + c) * CE : rowp));
         }
     };
     auto load_ext = [&](int se) {  // se = stage inside the current table batch
@@ -271,12 +310,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
             const int cc = 2 * kk + lh;
             chunk_t wf[NBN];
 #pragma unroll
-            for (int nb = 0; nb < NBN; ++nb) wf[nb] = buf[wpos[nb] + (cc ^ wsw[nb])];
+            for (int nb = 0; nb < NBN; ++nb) wf[nb] = buf[wpos[nb] + (cc ^ lsw)];
 #pragma unroll
             for (int tb = 0; tb < NBT; ++tb) {
                 const int t0 = wm0 + tb * 32;
                 if (lo < t0 + 32 && hi > t0) {
-                    const chunk_t xf = buf[xpos[tb] + (cc ^ xsw[tb])];
+                    const chunk_t xf = buf[xpos[tb] + (cc ^ lsw)];
 #pragma unroll
                     for (int nb = 0; nb < NBN; ++nb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf);
                 }
@@ -309,6 +348,22 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
         }
     };
 
+    // full MFMA work of one stage, not pipelined (partial K stage)
+    auto compute = [&](const chunk_t *buf) {
+#pragma unroll
+        for (int kk = 0; kk < SUB; ++kk) {
+            const int cc = 2 * kk + lh;
+            chunk_t wf[NBN], xf[NBT];
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb) wf[nb] = buf[wpos[nb] + (cc ^ lsw)];
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) xf[tb] = buf[xpos[tb] + (cc ^ lsw)];
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb)
+#pragma unroll
+                for (int nb = 0; nb < NBN; ++nb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[tb]);
+        }
+    };
     if (KT_full * BKC * CE < p.K) {
         load_partial();
         store_regs(s0);
@@ -360,14 +415,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_pipe_kernel(GemmArgs p, int 
             }
         }
     }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <typename E, int BM, int BN, int WM, int WN, int BKC, int NBUF>
+template <typename E, int BM, int BN, int WM, int WN>
 hipError_t launch_pipe(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
     const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
     const long total = (long)tiles_m * tiles_n;
     if (total <= 0) return hipSuccess;
-    auto kern = gemm_pipe_kernel<E, BM, BN, WM, WN, BKC, NBUF>;
+    auto kern = gemm_pipe_kernel<E, BM, BN, WM, WN>;
     const long grid = ((total + 7) / 8) * 8;
     const int group_m = 8;
     return launch_kernel(kern, dim3((unsigned)grid), dim3(WM * WN * 64), 0, stream, timer, a, tiles_m, tiles_n, group_m);
@@ -376,12 +432,12 @@ hipError_t launch_pipe(const GemmArgs &a, hipStream_t stream, const KernelTimer 
 template <typename E>
 hipError_t launch_pipe_variant(const GemmArgs &a, int variant, hipStream_t stream, const KernelTimer *timer) {
     switch (variant) {
-        case kGemmPipe256x256k32:
-            return launch_pipe<E, 256, 256, 4, 2, 4, 4>(a, stream, timer);
-        case kGemmPipe256x256k64:
-            return launch_pipe<E, 256, 256, 4, 2, 8, 2>(a, stream, timer);
-        case kGemmPipe128x128k64:
-            return launch_pipe<E, 128, 128, 2, 2, 8, 4>(a, stream, timer);
+        case kGemmPipe256x256w8:
+            return launch_pipe<E, 256, 256, 4, 2>(a, stream, timer);
+        case kGemmPipe256x256w4:
+            return launch_pipe<E, 256, 256, 2, 2>(a, stream, timer);
+        case kGemmPipe128x128w4:
+            return launch_pipe<E, 128, 128, 2, 2>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

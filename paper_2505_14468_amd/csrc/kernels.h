@@ -98,9 +98,9 @@ enum GemmVariant {
     kGemmTile64x64 = 3,
     kGemmSkinny = 4,
     kGemmTile256x256w4 = 5,  // 256x256 tile on 4 waves (128x128 per wave)
-    kGemmPipe256x256k32 = 6,  // direct-to-LDS pipeline, 4 stage buffers of 32 k (bf16)
-    kGemmPipe256x256k64 = 7,  // direct-to-LDS pipeline, 2 stage buffers of 64 k
-    kGemmPipe128x128k64 = 8,  // direct-to-LDS pipeline, 128x128 tile, 4 stage buffers of 64 k
+    kGemmPipe256x256w8 = 6,  // direct-to-LDS software pipeline, 256x256 tile on 8 waves
+    kGemmPipe256x256w4 = 7,  // same on 4 waves (128x128 per wave)
+    kGemmPipe128x128w4 = 8,  // 128x128 tile on 4 waves
     kGemmVariantCount
 };
 

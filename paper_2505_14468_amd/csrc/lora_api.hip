@@ -442,12 +442,16 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.T = (int32_t)plan->T;
     a.K = d->K;
     a.N = d->N;
-    const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
+    GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
+    if (c.variant >= kGemmPipe256x256w8) {  // these address W0 / X with 31-bit byte offsets
+        const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
+        if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
+    }
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
     if (c.variant == kGemmSkinny)
         LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
-    else if (c.variant >= kGemmPipe256x256k32)
+    else if (c.variant >= kGemmPipe256x256w8)
         LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
@@ -695,14 +699,14 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
         case kGemmTile256x256w4:
             snprintf(buf, sizeof buf, "tile_256x256w4");
             break;
-        case kGemmPipe256x256k32:
-            snprintf(buf, sizeof buf, "pipe_256x256_k32x4");
+        case kGemmPipe256x256w8:
+            snprintf(buf, sizeof buf, "pipe_256x256_w8");
             break;
-        case kGemmPipe256x256k64:
-            snprintf(buf, sizeof buf, "pipe_256x256_k64x2");
+        case kGemmPipe256x256w4:
+            snprintf(buf, sizeof buf, "pipe_256x256_w4");
             break;
-        case kGemmPipe128x128k64:
-            snprintf(buf, sizeof buf, "pipe_128x128_k64x4");
+        case kGemmPipe128x128w4:
+            snprintf(buf, sizeof buf, "pipe_128x128_w4");
             break;
         default:
             snprintf(buf, sizeof buf, "unknown");
