@@ -58,9 +58,8 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     chunk_t *wstage = reinterpret_cast<chunk_t *>(smem + (size_t)kSkWaves * TILE * sizeof(float));  // [kSkWaves][WBUF]
     SkTable *tab = reinterpret_cast<SkTable *>(wstage + kSkWaves * WBUF);
 
-    if (p.plan.scalars[kScStatus] != 0) return;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index as a scalar: K ranges, stage counters and stage offsets then live in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int n0 = blockIdx.x * (16 * NB);
 
@@ -71,11 +70,11 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     // W loads: lane -> (row lane/8 + 8*i of the 16-row block, chunk lane%8 of the 128-byte stage).
     // Rows past N are clamped to the last row: they only feed accumulator entries never stored.
     const int wr = lane >> 3, wc = lane & 7;
-    const E *wrow[NB][2];
+    const E *wrow[NB][2];  // row start + this lane's chunk of a stage; what changes per stage is a scalar
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) wrow[nb][i] = W + (int64_t)min(n0 + nb * 16 + wr + 8 * i, p.N - 1) * p.ldw;
+        for (int i = 0; i < 2; ++i) wrow[nb][i] = W + (int64_t)min(n0 + nb * 16 + wr + 8 * i, p.N - 1) * p.ldw + wc * CE;
     // swizzled positions inside the wave's staging buffer
     int wdst[NB][2];
 #pragma unroll
@@ -86,6 +85,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
             wdst[nb][i] = (nb * 16 + row) * 8 + (wc ^ ((row >> 1) & 7));
         }
     chunk_t *buf = wstage + wave * WBUF;  // one buffer is enough: a wave's LDS operations execute in order
+    const chunk_t *xlane = Xp + lane;
 
     f32x4_t acc[NB][TBLK];
 #pragma unroll
@@ -94,52 +94,57 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
         for (int tb = 0; tb < TBLK; ++tb) acc[nb][tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // ---- base product: this wave's share of the stages (64 k each) along K ---------------------------
+    // Whole stages are dealt to the waves and run without masks; a last partial stage (K not a
+    // multiple of 64) goes to the last wave.  Stages past a wave's range are skipped (a uniform
+    // branch), not loaded and dropped.
     const int kchunks = p.K / CE;
-    const int stages = (kchunks + 7) >> 3;
-    const int sg0 = (int)((int64_t)stages * wave / kSkWaves), sg1 = (int)((int64_t)stages * (wave + 1) / kSkWaves);
+    const int full = kchunks >> 3;
+    const int sg0 = (int)((int64_t)full * wave / kSkWaves), sg1 = (int)((int64_t)full * (wave + 1) / kSkWaves);
 
     chunk_t wa[SGB][NB][2], xa[SGB][2][TBLK], wb[SGB][NB][2], xb[SGB][2][TBLK];
     auto load_batch = [&](int g0, chunk_t (&wf)[SGB][NB][2], chunk_t (&xf)[SGB][2][TBLK]) {
 #pragma unroll
         for (int g = 0; g < SGB; ++g) {
             const int sg = g0 + g;
-            const int kc = sg * 8 + wc;
-            const bool ok = sg < sg1 && kc < kchunks;  // beyond the range: load chunk 0, drop it
-            const int koff = ok ? kc * CE : 0;
+            if (sg < sg1) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+                for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int i = 0; i < 2; ++i) wf[g][nb][i] = keep_if(ok, load_chunk(wrow[nb][i] + koff));
-            const int sgc = min(sg, stages - 1);  // X of a stage beyond the range meets zeroed weights
+                    for (int i = 0; i < 2; ++i) wf[g][nb][i] = load_chunk(wrow[nb][i] + sg * (8 * CE));
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int tb = 0; tb < TBLK; ++tb) xf[g][h][tb] = Xp[((int64_t)(sgc * 2 + h) * TBLK + tb) * 64 + lane];
+                    for (int tb = 0; tb < TBLK; ++tb) xf[g][h][tb] = xlane[((sg * 2 + h) * TBLK + tb) * 64];
+            }
         }
     };
-    auto mma_batch = [&](const chunk_t (&wf)[SGB][NB][2], const chunk_t (&xf)[SGB][2][TBLK]) {
+    auto mma_stage = [&](const chunk_t (&wf)[NB][2], const chunk_t (&xf)[2][TBLK]) {
 #pragma unroll
-        for (int g = 0; g < SGB; ++g) {
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+            for (int i = 0; i < 2; ++i) buf[wdst[nb][i]] = wf[nb][i];
+        // lanes exchange data through the wave's own buffer: LDS operations of one wave execute in
+        // order, the fences only keep the compiler from reordering across the exchange
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
 #pragma unroll
-                for (int i = 0; i < 2; ++i) buf[wdst[nb][i]] = wf[g][nb][i];
-            // lanes exchange data through the wave's own buffer: LDS operations of one wave execute in
-            // order, the fences only keep the compiler from reordering across the exchange
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int nb = 0; nb < NB; ++nb) {
+                const chunk_t w = buf[(nb * 16 + li) * 8 + ((h * 4 + lg) ^ ((li >> 1) & 7))];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const chunk_t w = buf[(nb * 16 + li) * 8 + ((h * 4 + lg) ^ ((li >> 1) & 7))];
+                for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], w, xf[h][tb]);
+            }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    };
+    auto mma_batch = [&](int g0, const chunk_t (&wf)[SGB][NB][2], const chunk_t (&xf)[SGB][2][TBLK]) {
 #pragma unroll
-                    for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], w, xf[g][h][tb]);
-                }
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        }
+        for (int g = 0; g < SGB; ++g)
+            if (g0 + g < sg1) mma_stage(wf[g], xf[g]);
     };
 
     load_batch(sg0, wa, xa);
+    // (the first loads do not depend on the plan: its status is looked at while they are in flight)
+    if (p.plan.scalars[kScStatus] != 0) return;
 
     // ---- extension table: one entry per 8 ranks of the batch's concatenated rank space ----------------
     const int ext_chunks = p.B != nullptr ? p.plan.scalars[kScExtTotal] / CE : 0;
@@ -180,9 +185,22 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 
     for (int g0 = sg0; g0 < sg1; g0 += 2 * SGB) {
         load_batch(g0 + SGB, wb, xb);
-        mma_batch(wa, xa);
+        mma_batch(g0, wa, xa);
         load_batch(g0 + 2 * SGB, wa, xa);
-        mma_batch(wb, xb);
+        mma_batch(g0 + SGB, wb, xb);
+    }
+    if ((kchunks & 7) != 0 && wave == kSkWaves - 1) {  // the partial stage: chunks past K are zeros (X's copy holds zeros there)
+        const bool ok = full * 8 + wc < kchunks;
+        chunk_t wf[NB][2], xf[2][TBLK];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) wf[nb][i] = keep_if(ok, load_chunk(ok ? wrow[nb][i] + full * (8 * CE) : wrow[nb][i] - wc * CE));
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int tb = 0; tb < TBLK; ++tb) xf[h][tb] = xlane[((full * 2 + h) * TBLK + tb) * 64];
+        mma_stage(wf, xf);
     }
 
     // ---- extension steps, dealt round-robin to the waves --------------------------------------------------

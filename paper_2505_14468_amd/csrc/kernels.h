@@ -65,8 +65,10 @@ struct ShrinkArgs {
     const float *scale;    // device table
     void *V;               // [T, r_max] of E
     int32_t r_max;
-    int32_t rank_groups;   // ceil(r_max / kShrinkRanks)
+    int32_t rank_block;    // ranks per workgroup: 16 (few units: spread them over the chip) or kShrinkRanks
+    int32_t rank_groups;   // ceil(r_max / rank_block)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
+    int32_t xlds_bytes;    // LDS for staging the X rows of small units: 0 or 64 KiB (decode-sized batches)
     // Fragment-major copy of X for the decode-sized GEMM (null = not needed): for MFMA step s
     // (32 k) and 16-row block tb, the 64 lanes' 16-byte operands are stored contiguously at
     // xpack[(s * pack_tblk + tb) * 64 + lane], lane = 16 * kgroup + row, zero past T and K.

@@ -56,6 +56,7 @@ struct lora_ctx {
     int opt_skinny_nb = -1;
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
+    int opt_shrink_rank_block = -1;
     // profiling mode: event pairs recorded tightly around each kernel
     bool prof_on = false;
     int prof_cap = 0;
@@ -409,11 +410,18 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.scale = ad ? d->tbl->scale : nullptr;
     a.V = ws + w.v_off;
     a.r_max = plan->r_max;
-    a.rank_groups = ad ? (plan->r_max + kShrinkRanks - 1) / kShrinkRanks : 1;
     // units <= sum over segments of ceil(rows/64) <= T/64 + number of adapter segments
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
     a.max_units = ad ? (int32_t)(plan->T / kShrinkRows + seg_bound2) : 0;
+    // With few units (decode-sized batches) a unit's ranks are dealt to several workgroups: every A_a
+    // is streamed once either way, and it takes most of the chip to stream them at HBM speed.
+    const int64_t wide_groups = (plan->r_max + kShrinkRanks - 1) / kShrinkRanks;
+    int rank_block = ad && a.max_units * wide_groups < 2 * (int64_t)ctx->num_cu ? 16 : kShrinkRanks;
+    if (ctx->opt_shrink_rank_block > 0) rank_block = ctx->opt_shrink_rank_block;
+    a.rank_block = rank_block;
+    a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
+    a.xlds_bytes = ad && plan->T <= 256 ? 64 * 1024 : 0;  // small batches: units of a few rows, one workgroup per CU is plenty
     a.xpack = pack ? ws + w.xpack_off : nullptr;
     a.pack_tblk = pack ? skinny_tblk(plan->T) : 0;
     a.pack_wgs = pack ? (int32_t)((w.xpack_bytes / 16 + 2047) / 2048) : 0;  // 4 chunks per thread
@@ -519,6 +527,9 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
         ctx->opt_skinny_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
         ctx->opt_plan_fused_rows = value;
+    } else if (!strcmp(name, "shrink_rank_block")) {
+        if (value > 0 && value != 8 && value != 16 && value != 32 && value != 64) return LORA_ERR_INVALID_ARG;
+        ctx->opt_shrink_rank_block = value;
     } else {
         return LORA_ERR_INVALID_ARG;
     }
