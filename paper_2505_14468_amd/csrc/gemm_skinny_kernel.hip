@@ -48,8 +48,10 @@ template <int TBLK, int NB>
 __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     typedef __bf16 E;
     constexpr int CE = 8;
-    constexpr int LPG = 2 * NB + 2 * TBLK;             // 16-byte loads per lane per stage (2 MFMA steps = 64 k)
-    constexpr int SGB = (20 / LPG) > 0 ? 20 / LPG : 1;  // stages per load batch; two batches in flight
+    constexpr int WS = 8 / NB;  // stages of W0 requested ahead (a stage = 2 MFMA steps = 64 k; 2 * NB loads per lane)
+    constexpr int XB0 = 4 / TBLK < WS / 2 ? 4 / TBLK : WS / 2;
+    constexpr int XB = XB0 > 0 ? XB0 : 1;  // stages per batch of X loads (2 * TBLK loads per lane each); two batches in flight
+    static_assert(WS % (2 * XB) == 0, "a W0 window is a whole number of X batch pairs");
     constexpr int TILE = NB * TBLK * 256;              // floats of one wave's partial tile
     constexpr int WBUF = NB * 16 * 8;                  // chunks of one W staging buffer (16*NB rows x 128 B)
 
@@ -62,6 +64,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int n0 = blockIdx.x * (16 * NB);
+    LORA_TS(p.trace, 0);
 
     const E *V = static_cast<const E *>(p.V);
     const E *W = static_cast<const E *>(p.W);
@@ -101,16 +104,26 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     const int full = kchunks >> 3;
     const int sg0 = (int)((int64_t)full * wave / kSkWaves), sg1 = (int)((int64_t)full * (wave + 1) / kSkWaves);
 
-    chunk_t wa[SGB][NB][2], xa[SGB][2][TBLK], wb[SGB][NB][2], xb[SGB][2][TBLK];
-    auto load_batch = [&](int g0, chunk_t (&wf)[SGB][NB][2], chunk_t (&xf)[SGB][2][TBLK]) {
+    // W0 comes from HBM, X from L2, and loads return in order: a wait for X would also wait for every W0
+    // load issued before it.  So the two streams are decoupled: the W0 loads of a whole window of stages
+    // (all of a wave's share at K = 4096) go out first and have the X traffic to hide behind, then X
+    // flows in small batches.
+    chunk_t wq[WS][NB][2], xa[XB][2][TBLK], xb[XB][2][TBLK];
+    auto load_w = [&](int S) {
 #pragma unroll
-        for (int g = 0; g < SGB; ++g) {
-            const int sg = g0 + g;
-            if (sg < sg1) {
+        for (int q = 0; q < WS; ++q)
+            if (S + q < sg1) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) wf[g][nb][i] = load_chunk(wrow[nb][i] + sg * (8 * CE));
+                    for (int i = 0; i < 2; ++i) wq[q][nb][i] = load_chunk(wrow[nb][i] + (S + q) * (8 * CE));
+            }
+    };
+    auto load_x = [&](int g0, chunk_t (&xf)[XB][2][TBLK]) {
+#pragma unroll
+        for (int g = 0; g < XB; ++g) {
+            const int sg = g0 + g;
+            if (sg < sg1) {
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -136,59 +149,114 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
             }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     };
-    auto mma_batch = [&](int g0, const chunk_t (&wf)[SGB][NB][2], const chunk_t (&xf)[SGB][2][TBLK]) {
-#pragma unroll
-        for (int g = 0; g < SGB; ++g)
-            if (g0 + g < sg1) mma_stage(wf[g], xf[g]);
-    };
-
-    load_batch(sg0, wa, xa);
-    // (the first loads do not depend on the plan: its status is looked at while they are in flight)
-    if (p.plan.scalars[kScStatus] != 0) return;
-
     // ---- extension table: one entry per 8 ranks of the batch's concatenated rank space ----------------
+    // An entry takes two dependent loads (the plan's record, then the adapter table's pointer).  Loads
+    // return in order, so each of the two is issued just BEFORE a batch of the base product's loads:
+    // waiting for it then waits for nothing younger, and the round trips are hidden behind the batches.
+    static_assert(kSkTab == kSkThreads, "one table entry per thread");
     const int ext_chunks = p.B != nullptr ? p.plan.scalars[kScExtTotal] / CE : 0;
-    auto build_table = [&](int chunk0) {
-        for (int idx = tid; idx < kSkTab; idx += kSkThreads) {
-            const int ch = chunk0 + idx;
-            const void *ptr = nullptr;
-            int r = 0, j = 0, a = -2;
-            if (ch < ext_chunks) {
-                const int4 rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[ch];
-                const E *b = rec.x >= 0 ? static_cast<const E *>(p.B[rec.x]) : nullptr;
-                if (b != nullptr) {
-                    r = rec.y >> 16;
-                    j = rec.y & 0xffff;
-                    a = rec.x;
-                    ptr = b + j;
-                } else {
-                    atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
-                }
-            }
-            tab->ptr[idx] = ptr;
-            tab->r[idx] = r;
-            tab->j[idx] = j;
-            tab->a[idx] = a;
-        }
+    const int status = p.plan.scalars[kScStatus];
+    struct Entry {
+        const void *ptr;
+        int r, j, a;
     };
+    auto fetch_rec = [&](int ch) {  // record of extension chunk ch (unused: adapter -2)
+        int4 rec = make_int4(-2, 0, 0, 0);
+        if (ch < ext_chunks) rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[ch];
+        return rec;
+    };
+    auto fetch_ptr = [&](const int4 &rec) { return rec.x >= 0 ? p.B[rec.x] : nullptr; };
+    auto publish = [&](int idx, const int4 &rec, const void *b) {
+        Entry e{nullptr, 0, 0, -2};
+        if (b != nullptr) {
+            e.r = rec.y >> 16;
+            e.j = rec.y & 0xffff;
+            e.a = rec.x;
+            e.ptr = static_cast<const E *>(b) + e.j;
+        } else if (rec.x != -2) {
+            atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+        }
+        tab->ptr[idx] = e.ptr;
+        tab->r[idx] = e.r;
+        tab->j[idx] = e.j;
+        tab->a[idx] = e.a;
+    };
+
+    const int4 rec0 = fetch_rec(tid);
+    load_w(sg0);
+    load_x(sg0, xa);
+    if (status != 0) return;
+    const void *bptr0 = fetch_ptr(rec0);
     int row_ad[TBLK];
 #pragma unroll
-    for (int tb = 0; tb < TBLK; ++tb) row_ad[tb] = -1;
+    for (int tb = 0; tb < TBLK; ++tb) {
+        const int t = tb * 16 + li;
+        row_ad[tb] = (ext_chunks > 0 && t < p.T) ? p.plan.row_adapter[t] : -1;
+    }
+    load_x(sg0 + XB, xb);
+    LORA_TS(p.trace, 1);  // first window of W0 and two batches of X issued
     if (ext_chunks > 0) {
-#pragma unroll
-        for (int tb = 0; tb < TBLK; ++tb) {
-            const int t = tb * 16 + li;
-            row_ad[tb] = t < p.T ? p.plan.row_adapter[t] : -1;
-        }
-        build_table(0);
+        publish(tid, rec0, bptr0);
+        __syncthreads();
     }
+    LORA_TS(p.trace, 2);  // table published
 
-    for (int g0 = sg0; g0 < sg1; g0 += 2 * SGB) {
-        load_batch(g0 + SGB, wb, xb);
-        mma_batch(g0, wa, xa);
-        load_batch(g0 + 2 * SGB, wa, xa);
-        mma_batch(g0 + SGB, wb, xb);
+    // ---- extension steps, dealt round-robin to the waves; a trip = two steps, their loads overlap ---------
+    auto ext_load = [&](int s, int nst, chunk_t (&wf)[2][NB], chunk_t (&xf)[2][TBLK]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = min(s + u * kSkWaves, kSkTab / 4 - 1) * 4 + lg;
+            const bool live = s + u * kSkWaves < nst;
+            const E *bp = static_cast<const E *>(tab->ptr[idx]);
+            const int r = tab->r[idx], j = tab->j[idx], a = tab->a[idx];
+            const bool wok = live && bp != nullptr;
+            const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int n = min(n0 + nb * 16 + li, p.N - 1);
+                wf[u][nb] = keep_if(wok, load_chunk(bsrc + (wok ? (int64_t)n * r : 0)));
+            }
+#pragma unroll
+            for (int tb = 0; tb < TBLK; ++tb) {
+                const int t = min(tb * 16 + li, p.T - 1);
+                const bool xok = live && row_ad[tb] == a;  // rows of other adapters contribute nothing
+                xf[u][tb] = keep_if(xok, load_chunk(V + (xok ? (int64_t)t * p.r_max + j : 0)));
+            }
+        }
+    };
+    auto ext_mma = [&](const chunk_t (&wf)[2][NB], const chunk_t (&xf)[2][TBLK]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], wf[u][nb], xf[u][tb]);
+    };
+    const int nst0 = (min(ext_chunks, kSkTab) + 3) >> 2;  // steps of the first table
+    const bool ext_first = wave < nst0;                  // this wave has a first trip
+    chunk_t ewf[2][NB], exf[2][TBLK];
+
+    // ---- the K loop; the operands of the wave's first extension trip are fetched under its last pass ----
+    bool ext_loaded = false;
+    for (int S = sg0; S < sg1; S += WS) {
+        if (TBLK <= 4 && ext_first && S + WS >= sg1) {  // the last window hides the first extension trip's loads (registers permitting)
+            ext_load(wave, nst0, ewf, exf);
+            ext_loaded = true;
+        }
+#pragma unroll
+        for (int q = 0; q < WS; q += 2 * XB) {
+#pragma unroll
+            for (int g = 0; g < XB; ++g)
+                if (S + q + g < sg1) mma_stage(wq[q + g], xa[g]);
+            load_x(S + q + 2 * XB, xa);
+#pragma unroll
+            for (int g = 0; g < XB; ++g)
+                if (S + q + XB + g < sg1) mma_stage(wq[q + XB + g], xb[g]);
+            load_x(S + q + 3 * XB, xb);
+        }
+        load_w(S + WS);  // K beyond one window: its latency shows once per window
     }
+    LORA_TS(p.trace, 3);  // K loop issued (MFMAs may still run)
     if ((kchunks & 7) != 0 && wave == kSkWaves - 1) {  // the partial stage: chunks past K are zeros (X's copy holds zeros there)
         const bool ok = full * 8 + wc < kchunks;
         chunk_t wf[NB][2], xf[2][TBLK];
@@ -202,46 +270,27 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
             for (int tb = 0; tb < TBLK; ++tb) xf[h][tb] = xlane[((full * 2 + h) * TBLK + tb) * 64];
         mma_stage(wf, xf);
     }
-
-    // ---- extension steps, dealt round-robin to the waves --------------------------------------------------
-    for (int chunk0 = 0; chunk0 < ext_chunks; chunk0 += kSkTab) {
-        if (chunk0 > 0) {
-            __syncthreads();
-            build_table(chunk0);
+    if (ext_first) {
+        if (!ext_loaded) ext_load(wave, nst0, ewf, exf);  // a wave without a share of K
+        ext_mma(ewf, exf);
+        for (int s = wave + 2 * kSkWaves; s < nst0; s += 2 * kSkWaves) {
+            ext_load(s, nst0, ewf, exf);
+            ext_mma(ewf, exf);
         }
+    }
+    for (int chunk0 = kSkTab; chunk0 < ext_chunks; chunk0 += kSkTab) {  // more than one table's worth
+        __syncthreads();  // every wave is done with the previous table
+        const int4 rec = fetch_rec(chunk0 + tid);
+        publish(tid, rec, fetch_ptr(rec));
         __syncthreads();
         const int nst = (min(ext_chunks - chunk0, kSkTab) + 3) >> 2;
-        for (int s = wave; s < nst; s += 2 * kSkWaves) {  // two steps per trip: their loads overlap
-            chunk_t wf[2][NB], xf[2][TBLK];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int idx = min(s + u * kSkWaves, kSkTab / 4 - 1) * 4 + lg;
-                const bool live = s + u * kSkWaves < nst;
-                const E *bp = static_cast<const E *>(tab->ptr[idx]);
-                const int r = tab->r[idx], j = tab->j[idx], a = tab->a[idx];
-                const bool wok = live && bp != nullptr;
-                const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int n = min(n0 + nb * 16 + li, p.N - 1);
-                    wf[u][nb] = keep_if(wok, load_chunk(bsrc + (wok ? (int64_t)n * r : 0)));
-                }
-#pragma unroll
-                for (int tb = 0; tb < TBLK; ++tb) {
-                    const int t = min(tb * 16 + li, p.T - 1);
-                    const bool xok = live && row_ad[tb] == a;  // rows of other adapters contribute nothing
-                    xf[u][tb] = keep_if(xok, load_chunk(V + (xok ? (int64_t)t * p.r_max + j : 0)));
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], wf[u][nb], xf[u][tb]);
+        for (int s = wave; s < nst; s += 2 * kSkWaves) {
+            ext_load(s, nst, ewf, exf);
+            ext_mma(ewf, exf);
         }
     }
 
+    LORA_TS(p.trace, 4);  // extension issued
     // ---- sum the 8 partial tiles in wave order, store Y once ------------------------------------------------
     // acc[nb][tb][e] = D[n = n0 + nb*16 + lg*4 + e][t = tb*16 + li]
     float4 *mine = reinterpret_cast<float4 *>(red + (size_t)wave * TILE);
@@ -251,6 +300,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
         for (int tb = 0; tb < TBLK; ++tb)
             mine[(nb * TBLK + tb) * 64 + lane] = make_float4(acc[nb][tb][0], acc[nb][tb][1], acc[nb][tb][2], acc[nb][tb][3]);
     __syncthreads();
+    LORA_TS(p.trace, 5);  // partial tiles parked
     E *Y = static_cast<E *>(p.Y);
     for (int idx = tid; idx < NB * TBLK * 64; idx += kSkThreads) {
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -277,6 +327,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
                 if (n + e < p.N) store1(yrow + n + e, v[e]);
         }
     }
+    LORA_TS(p.trace, 6);
 }
 
 template <int TBLK, int NB>
@@ -292,7 +343,15 @@ hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *t
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+#ifdef LORA_TRACE
+    return trace_launch("gemm_skinny", n_tiles, [&](long long *buf) {
+        GemmArgs b = a;
+        b.trace = buf;
+        return launch_kernel(kern, dim3((unsigned)n_tiles), dim3(kSkThreads), smem, stream, timer, b);
+    });
+#else
     return launch_kernel(kern, dim3((unsigned)n_tiles), dim3(kSkThreads), smem, stream, timer, a);
+#endif
 }
 
 }  // namespace

@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
 #include "common.hiph"
 
 namespace lora {
@@ -40,6 +44,50 @@ struct KernelTimer {
     hipEvent_t start, stop;
 };
 
+// ---- optional phase trace: builds with -DLORA_TRACE only (a development aid) -------------------------------
+// Thread 0 of every workgroup stamps the constant 100 MHz clock into trace[blockIdx.x * 8 + slot]; with the
+// environment variable LORA_TRACE set to a kernel's name, that kernel's 30th launch prints the stamps in
+// microseconds relative to the earliest one (the launches are synchronous then).
+#ifdef LORA_TRACE
+#define LORA_TS(buf, i)                                                                     \
+    do {                                                                                    \
+        if ((buf) != nullptr && threadIdx.x == 0) (buf)[blockIdx.x * 8 + (i)] = wall_clock64(); \
+    } while (0)
+template <typename Launch>
+inline hipError_t trace_launch(const char *name, long grid, Launch launch) {
+    const char *want = getenv("LORA_TRACE");
+    if (want == nullptr || strcmp(want, name) != 0) return launch(nullptr);
+    constexpr long kMaxWgs = 8192;
+    static long long *dbuf = nullptr;
+    static int calls = 0;
+    if (dbuf == nullptr && hipMalloc(&dbuf, 8 * 8 * kMaxWgs) != hipSuccess) return hipErrorOutOfMemory;
+    (void)hipMemset(dbuf, 0, 8 * 8 * kMaxWgs);
+    (void)hipDeviceSynchronize();
+    hipError_t e = grid <= kMaxWgs ? launch(dbuf) : launch(nullptr);
+    (void)hipDeviceSynchronize();
+    if (++calls == 30 && grid <= kMaxWgs) {
+        static long long h[8 * kMaxWgs];
+        (void)hipMemcpy(h, dbuf, sizeof(long long) * 8 * grid, hipMemcpyDeviceToHost);
+        long long t0 = -1;
+        for (long g = 0; g < grid; ++g)
+            if (h[g * 8] && (t0 < 0 || h[g * 8] < t0)) t0 = h[g * 8];
+        const long stride = grid > 48 ? grid / 24 : 1;
+        for (long g = 0; g < grid; g += stride) {
+            if (!h[g * 8]) continue;
+            printf("trace %s wg %ld:", name, g);
+            for (int i = 0; i < 8; ++i) printf(" %6.2f", h[g * 8 + i] ? (h[g * 8 + i] - t0) * 0.01 : -1.0);
+            printf("\n");
+        }
+        fflush(stdout);
+    }
+    return e;
+}
+#else
+#define LORA_TS(buf, i) \
+    do {                \
+    } while (0)
+#endif
+
 // Launch with or without a timer.
 template <typename F, typename... Args>
 inline hipError_t launch_kernel(F kernel, dim3 grid, dim3 block, size_t smem, hipStream_t stream, const KernelTimer *timer,
@@ -74,6 +122,7 @@ struct ShrinkArgs {
     // xpack[(s * pack_tblk + tb) * 64 + lane], lane = 16 * kgroup + row, zero past T and K.
     void *xpack;
     int32_t pack_tblk;
+    long long *trace = nullptr;  // phase stamps (trace builds only)
     int32_t pack_wgs;      // extra workgroups in front of the shrink units that write the copy
 };
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
@@ -91,6 +140,7 @@ struct GemmArgs {
     const void *const *B;  // device table (null when no adapters)
     int32_t r_max;
     int32_t T, K, N;
+    long long *trace = nullptr;  // phase stamps (trace builds only)
 };
 
 enum GemmVariant {

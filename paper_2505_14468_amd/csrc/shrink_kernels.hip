@@ -113,7 +113,9 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
             }
         }
     };
+    LORA_TS(p.trace, 2);  // row map, adapter pointer, scale read
     load_batch(st0, xa, aa);  // first: nothing below depends on it, and it is the long pole
+    LORA_TS(p.trace, 3);  // first batch issued
     if (xlds) {
         for (int t = 0; t < nrows; ++t) {  // nrows and the row are uniform: one row per trip, one chunk per thread
             const E *src = static_cast<const E *>(p.X) + (int64_t)p.plan.perm[slot0 + t] * p.ldx;
@@ -121,6 +123,7 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
         }
     }
     if (xlds) __syncthreads();  // the staged rows are complete (uniform over the workgroup)
+    LORA_TS(p.trace, 4);  // rows staged
     for (int s0 = st0; s0 < st1; s0 += 2 * SB) {
         load_batch(s0 + SB, xb, ab);
         mma_batch(s0, xa, aa);
@@ -145,6 +148,7 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
         }
     }
 
+    LORA_TS(p.trace, 5);  // K loop issued
     // Sum the per-wave partial tiles in wave order (fixed order -> deterministic), scale, store.
     // acc[tb][jb][e] holds D[j = jb*16 + lg*4 + e][t = tb*16 + li].
     E *V = static_cast<E *>(p.V);
@@ -223,6 +227,7 @@ template <typename E>
 __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
+    LORA_TS(p.trace, 0);
 
     if ((int)blockIdx.x < p.pack_wgs) {
         if (p.plan.scalars[kScStatus] != 0) return;
@@ -239,6 +244,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
     const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
     if (status != 0 || unit >= n_units) return;
+    LORA_TS(p.trace, 1);  // work-list record read
 
     // the plan's work list names the unit: adapter, rank, first slot, rows (one load, no search)
     const int a = rec.x, r = rec.y, slot0 = rec.z, nrows = rec.w;
@@ -283,6 +289,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
         else
             shrink_unit<E, 4, 4>(p, Aa, scale, slot0, nrows, j0, nj, prow, smem);
     }
+    LORA_TS(p.trace, 6);
 }
 
 }  // namespace
@@ -302,8 +309,17 @@ hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+#ifdef LORA_TRACE
+    return trace_launch("shrink", grid, [&](long long *buf) {
+        ShrinkArgs b = a;
+        b.trace = buf;
+        if (dtype == 1) return launch_kernel(shrink_kernel<__bf16>, dim3((unsigned)grid), dim3(kShWaves * 64), smem, stream, timer, b);
+        return launch_kernel(shrink_kernel<float>, dim3((unsigned)grid), dim3(kShWaves * 64), smem, stream, timer, b);
+    });
+#else
     if (dtype == 1) return launch_kernel(shrink_kernel<__bf16>, dim3((unsigned)grid), dim3(kShWaves * 64), smem, stream, timer, a);
     return launch_kernel(shrink_kernel<float>, dim3((unsigned)grid), dim3(kShWaves * 64), smem, stream, timer, a);
+#endif
 }
 
 }  // namespace lora
