@@ -144,7 +144,8 @@ int lora_ctx_create(lora_ctx **out, int device_ordinal);
 int lora_ctx_destroy(lora_ctx *ctx);
 
 /* Tuning overrides for experiments ("gemm_variant", "skinny_nb",
- * "skinny_max_rows", "plan_fused_rows", "shrink_rank_block" = 16 / 32 / 64);
+ * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
+ * decode-sized plan kernel, "shrink_rank_block" = 8 / 16 / 32 / 64);
  * value < 0 restores the built-in heuristic.  Results never depend on them
  * beyond fp32 summation order.  Errors: INVALID_ARG for an unknown name or a
  * value the option does not take. */

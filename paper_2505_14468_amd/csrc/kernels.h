@@ -100,8 +100,9 @@ inline hipError_t launch_kernel(F kernel, dim3 grid, dim3 block, size_t smem, hi
 }
 
 // Enqueues the segment builder (one or two kernels).  `fuse_fill`: the single
-// workgroup of the first kernel also fills the T-sized arrays.  timers: [0] segments, [1] fill.
-hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream, const KernelTimer *timers);
+// workgroup of the first kernel also fills the T-sized arrays.  `variant`: 0 = pick by size, 1 = never the
+// decode-sized (one lane per request) kernel.  timers: [0] segments, [1] fill.
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, int variant, hipStream_t stream, const KernelTimer *timers);
 
 struct ShrinkArgs {
     PlanView plan;
@@ -113,7 +114,7 @@ struct ShrinkArgs {
     const float *scale;    // device table
     void *V;               // [T, r_max] of E
     int32_t r_max;
-    int32_t rank_block;    // ranks per workgroup: 16 (few units: spread them over the chip) or kShrinkRanks
+    int32_t rank_block;    // ranks per workgroup: 8 or 16 (few units: spread them over the chip) or kShrinkRanks
     int32_t rank_groups;   // ceil(r_max / rank_block)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
     int32_t xlds_bytes;    // LDS for staging the X rows of small units: 0 or 64 KiB (decode-sized batches)

@@ -57,6 +57,7 @@ struct lora_ctx {
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
     int opt_shrink_rank_block = -1;
+    int opt_plan_variant = -1;
     // profiling mode: event pairs recorded tightly around each kernel
     bool prof_on = false;
     int prof_cap = 0;
@@ -233,7 +234,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     const bool fuse = T <= fused_rows && L.ext_cap <= 8192;
     KernelTimer timers[2];
     const bool timed = next_timer(ctx, kProfPlanSegments, &timers[0]) && (fuse || next_timer(ctx, kProfPlanFill, &timers[1]));
-    LORA_HIP(launch_plan_build(a, fuse, stream, timed ? timers : nullptr));
+    LORA_HIP(launch_plan_build(a, fuse, ctx->opt_plan_variant > 0 ? ctx->opt_plan_variant : 0, stream, timed ? timers : nullptr));
 
     out->T = T;
     out->n_req = n_req;
@@ -417,7 +418,11 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     // With few units (decode-sized batches) a unit's ranks are dealt to several workgroups: every A_a
     // is streamed once either way, and it takes most of the chip to stream them at HBM speed.
     const int64_t wide_groups = (plan->r_max + kShrinkRanks - 1) / kShrinkRanks;
-    int rank_block = ad && a.max_units * wide_groups < 2 * (int64_t)ctx->num_cu ? 16 : kShrinkRanks;
+    const int64_t mid_groups = (plan->r_max + 15) / 16;
+    int rank_block = !ad                                                  ? kShrinkRanks
+                     : a.max_units * mid_groups < 2 * (int64_t)ctx->num_cu  ? 8
+                     : a.max_units * wide_groups < 2 * (int64_t)ctx->num_cu ? 16
+                                                                            : kShrinkRanks;
     if (ctx->opt_shrink_rank_block > 0) rank_block = ctx->opt_shrink_rank_block;
     a.rank_block = rank_block;
     a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
@@ -527,6 +532,9 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
         ctx->opt_skinny_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
         ctx->opt_plan_fused_rows = value;
+    } else if (!strcmp(name, "plan_variant")) {
+        if (value > 1) return LORA_ERR_INVALID_ARG;
+        ctx->opt_plan_variant = value;
     } else if (!strcmp(name, "shrink_rank_block")) {
         if (value > 0 && value != 8 && value != 16 && value != 32 && value != 64) return LORA_ERR_INVALID_ARG;
         ctx->opt_shrink_rank_block = value;

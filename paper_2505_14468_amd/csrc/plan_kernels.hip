@@ -7,6 +7,8 @@
 // shrink work list and one record per 8 ranks of the concatenated rank space).
 //
 // All arithmetic is integer, so integer atomics keep the result deterministic.
+#include <limits.h>
+
 #include "kernels.h"
 
 namespace lora {
@@ -562,6 +564,242 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
     }
 }
 
+// Decode-sized batches (at most 64 requests, any number of adapter slots): one lane per request.
+// Every request-level quantity is a sum over the other requests -- rows of requests with a smaller
+// key (first slot of the segment), rows of earlier requests with the same key (stable order inside
+// it), rows of the key (its shrink units), whether an earlier request has the key (first of its
+// segment) -- so it is accumulated lane-parallel while the other requests' (key, rows) are
+// broadcast one at a time from a scalar register (v_readlane: no LDS round trip, no scan, no
+// histogram over the adapter slots).  Four waves take a quarter of the broadcasts each; a second
+// pass over the first requests of the segments yields segment index and rank / unit prefixes.
+constexpr int kTinyReq = 64;
+constexpr int kTinyWaves = 4;
+
+__global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p) {
+    __shared__ int s_p1[kTinyWaves][5][64];  // pass 1 partials: less, equal-before, rows of key, rows before, earlier-same flag
+    __shared__ int s_p2[kTinyWaves][3][64];  // pass 2 partials: segments, ranks, units of smaller keys
+    __shared__ unsigned long long s_rows[kTinyWaves];
+    __shared__ int s_tot[kTinyWaves][2];     // ranks, units of all segments (per wave's share)
+    __shared__ int s_tok[kTinyReq + 1], s_dst[kTinyReq], s_rseg[kTinyReq], s_a[kTinyReq];
+    __shared__ int s_sad[kTinyReq + 1], s_sip[kTinyReq + 1], s_srk[kTinyReq + 1], s_sex[kTinyReq + 1], s_sun[kTinyReq + 1];
+    __shared__ int s_hdr[4];  // status, segments, total ranks, total units
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int R = p.n_req, n_ad = p.n_adapters;
+
+    // request state, kept by each of the four working waves
+    int a = -1, L = 0, key = INT_MAX, rows = 0, rk = 0;
+    bool bad = false, neg = false, active = false;
+    if (wave < kTinyWaves) {
+        const bool valid = lane < R;
+        a = valid ? p.req_adapter[lane] : -1;
+        L = valid ? p.req_ntok[lane] : 0;
+        bad = valid && (a < -1 || a >= n_ad);
+        neg = valid && !bad && L < 0;
+        active = valid && !bad && !neg && L > 0;
+        key = active ? (a < 0 ? n_ad : a) : INT_MAX;  // key n_ad = "no adapter"; idle lanes match nothing that counts
+        rows = active ? L : 0;
+        rk = (active && a >= 0) ? p.rank[a] : 0;  // wanted in pass 2 only: in flight during pass 1
+
+        // ---- pass 1: this wave's quarter of the requests, broadcast one by one ----
+        int less = 0, eqb = 0, h = 0, before = 0, earlier = 0;
+        unsigned long long total = 0ull;
+#pragma unroll
+        for (int jj = 0; jj < 64 / kTinyWaves; ++jj) {
+            const int j = wave * (64 / kTinyWaves) + jj;
+            if (j < R) {
+                const int kj = __builtin_amdgcn_readlane(key, j);
+                const int Lj = __builtin_amdgcn_readlane(rows, j);
+                const bool same = kj == key, prior = j < lane;
+                less += kj < key ? Lj : 0;
+                h += same ? Lj : 0;
+                eqb += (same && prior) ? Lj : 0;
+                before += prior ? Lj : 0;
+                earlier |= (same && prior) ? 1 : 0;
+                total += (unsigned long long)(unsigned)Lj;
+            }
+        }
+        s_p1[wave][0][lane] = less;
+        s_p1[wave][1][lane] = eqb;
+        s_p1[wave][2][lane] = h;
+        s_p1[wave][3][lane] = before;
+        s_p1[wave][4][lane] = earlier;
+        if (lane == 0) s_rows[wave] = total;
+    }
+    __syncthreads();
+
+    int less = 0, eqb = 0, h = 0, before = 0, rkf = 0, units = 0, st = 0;
+    bool first = false;
+    if (wave < kTinyWaves) {
+        int earlier = 0;
+#pragma unroll
+        for (int w = 0; w < kTinyWaves; ++w) {
+            less += s_p1[w][0][lane];
+            eqb += s_p1[w][1][lane];
+            h += s_p1[w][2][lane];
+            before += s_p1[w][3][lane];
+            earlier |= s_p1[w][4][lane];
+        }
+        first = active && earlier == 0;
+        // status, in the order and with the precedence of the general kernel (the smallest code wins)
+        if (__builtin_amdgcn_ballot_w64(bad) != 0ull) st = min(st, kErrBadAdapterId);
+        if (__builtin_amdgcn_ballot_w64(neg) != 0ull) st = min(st, kErrLengthMismatch);
+        if (st == 0) {
+            unsigned long long total = 0ull;
+#pragma unroll
+            for (int w = 0; w < kTinyWaves; ++w) total += s_rows[w];
+            if (total != (unsigned long long)(unsigned)p.T) st = kErrLengthMismatch;
+        }
+        if (st == 0) {
+            const bool seg_ad = first && a >= 0;
+            const bool not_res = seg_ad && rk <= 0;
+            const bool shape = seg_ad && rk > 0 && (rk & 7) != 0;
+            const bool large = seg_ad && rk > 0 && (rk & 7) == 0 && rk > p.r_max;
+            if (__builtin_amdgcn_ballot_w64(not_res) != 0ull) st = min(st, kErrNotResident);
+            if (__builtin_amdgcn_ballot_w64(large) != 0ull) st = min(st, kErrRankTooLarge);
+            if (__builtin_amdgcn_ballot_w64(shape) != 0ull) st = min(st, kErrShape);
+            rkf = (seg_ad && !not_res && !shape && !large) ? rk : 0;
+            units = seg_ad ? (h + kShrinkRows - 1) / kShrinkRows : 0;
+        }
+
+        // ---- pass 2: the first requests of the segments (this wave's quarter), broadcast one by one ----
+        const unsigned long long fmask = __builtin_amdgcn_ballot_w64(first);
+        int seg = 0, ext = 0, un = 0, tot_ext = 0, tot_un = 0;
+        if (st == 0) {
+#pragma unroll
+            for (int jj = 0; jj < 64 / kTinyWaves; ++jj) {
+                const int j = wave * (64 / kTinyWaves) + jj;
+                if ((fmask >> j) & 1ull) {
+                    const int kj = __builtin_amdgcn_readlane(key, j);
+                    const int rj = __builtin_amdgcn_readlane(rkf, j);
+                    const int uj = __builtin_amdgcn_readlane(units, j);
+                    const bool lt = kj < key;
+                    seg += lt ? 1 : 0;
+                    ext += lt ? rj : 0;
+                    un += lt ? uj : 0;
+                    tot_ext += rj;
+                    tot_un += uj;
+                }
+            }
+        }
+        s_p2[wave][0][lane] = seg;
+        s_p2[wave][1][lane] = ext;
+        s_p2[wave][2][lane] = un;
+        if (lane == 0) {
+            s_tot[wave][0] = tot_ext;
+            s_tot[wave][1] = tot_un;
+        }
+        if (wave == 0 && lane == 0) s_hdr[0] = st;  // every working wave computed the same status
+    }
+    __syncthreads();
+    if (s_hdr[0] != 0) {
+        if (tid == 0) write_failed(p, s_hdr[0]);
+        return;
+    }
+
+    if (wave == 0) {  // publish: request arrays and segment arrays, to LDS for the fill below and to the plan
+        int seg = 0, ext = 0, un = 0, c_ext = 0, c_unit = 0;
+#pragma unroll
+        for (int w = 0; w < kTinyWaves; ++w) {
+            seg += s_p2[w][0][lane];
+            ext += s_p2[w][1][lane];
+            un += s_p2[w][2][lane];
+            c_ext += s_tot[w][0];
+            c_unit += s_tot[w][1];
+        }
+        const unsigned long long fmask = __builtin_amdgcn_ballot_w64(first);
+        const int c_seg = __builtin_popcountll(fmask);
+        if (lane < R) {
+            s_tok[lane] = before;
+            s_dst[lane] = less + eqb;
+            s_rseg[lane] = seg;
+            s_a[lane] = a;
+            p.tok_off[lane] = before;
+        }
+        if (first) {
+            s_sad[seg] = a >= 0 ? a : -1;
+            s_sip[seg] = less;
+            s_srk[seg] = rkf;
+            s_sex[seg] = ext;
+            s_sun[seg] = un;
+            p.seg_adapter[seg] = a >= 0 ? a : -1;
+            p.seg_indptr[seg] = less;
+            p.seg_rank[seg] = rkf;
+            p.seg_ext[seg] = ext;
+            p.seg_unit[seg] = un;
+        }
+        if (lane == 0) {
+            s_tok[R] = p.T;
+            p.tok_off[R] = p.T;
+            s_sip[c_seg] = p.T;
+            s_sex[c_seg] = c_ext;
+            s_sun[c_seg] = c_unit;
+            p.seg_indptr[c_seg] = p.T;
+            p.seg_ext[c_seg] = c_ext;
+            p.seg_unit[c_seg] = c_unit;
+            p.scalars[kScNSeg] = c_seg;
+            p.scalars[kScStatus] = 0;
+            p.scalars[kScExtTotal] = c_ext;
+            p.scalars[kScNUnits] = c_unit;
+            p.scalars[kScT] = p.T;
+            s_hdr[1] = c_seg;
+            s_hdr[2] = c_ext;
+            s_hdr[3] = c_unit;
+        }
+    }
+    __syncthreads();
+    const int c_seg = s_hdr[1], c_ext = s_hdr[2], c_unit = s_hdr[3];
+
+    // per-row scatter, extension records, shrink work list: as in the small-batch kernel
+    for (int t = tid; t < p.T; t += kPlanThreads) {
+        int lo = 0, hi = R;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_tok[mid + 1] > t)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int slot = s_dst[lo] + (t - s_tok[lo]);
+        p.perm[slot] = t;
+        p.row_seg[slot] = s_rseg[lo];
+        p.row_adapter[t] = s_a[lo];
+    }
+    for (int q = tid; q < (c_ext >> 3); q += kPlanThreads) {
+        const int pel = q << 3;
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sex[mid + 1] > pel)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = (s_srk[lo] << 16) | (pel - s_sex[lo]);
+        rec.z = s_sip[lo];
+        rec.w = s_sip[lo + 1];
+        reinterpret_cast<int4 *>(p.ext_rec)[q] = rec;
+    }
+    for (int u = tid; u < c_unit; u += kPlanThreads) {
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sun[mid + 1] > u)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = s_srk[lo];
+        rec.z = slot0;
+        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
+    }
+}
+
 __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
     if (p.scalars[kScStatus] != 0) return;
     const int start = blockIdx.x * 256 + threadIdx.x;
@@ -573,7 +811,9 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
 
 }  // namespace
 
-hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, hipStream_t stream, const KernelTimer *timers) {
+hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, int variant, hipStream_t stream, const KernelTimer *timers) {
+    if (fuse_fill && variant != 1 && a.n_req <= kTinyReq && a.T <= kSmallRows)
+        return launch_kernel(plan_tiny_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
     if (fuse_fill && a.n_req <= kSmallReq && a.n_adapters + 1 <= kSmallKeys && a.T <= kSmallRows)
         return launch_kernel(plan_small_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
     hipError_t e = launch_kernel(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a,

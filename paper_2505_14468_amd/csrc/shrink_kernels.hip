@@ -25,6 +25,8 @@ constexpr int kRedBytes = kShrinkRows * kRS * 4;  // serial reduction buffer (la
 constexpr int kPartBytes = kShWaves * 4 * 1024;   // per-wave partial tiles (units of at most 4 MFMA tiles)
 constexpr int kXldsBytes = 64 * 1024;             // rows of X staged in LDS (units of a few rows)
 constexpr int kXldsPad = 4;                       // chunks of padding per staged row: rows fall into different banks
+constexpr int kXldsRows = 4;                      // at most this many rows are staged ...
+constexpr int kXldsChunks = 2;                    // ... of at most this many chunks per thread (K <= 8192 in bf16)
 
 // Dynamic LDS of the kernel: [reduction area][X staging area (only when launched with it)].
 constexpr int kShSmemBase = kRedBytes > kPartBytes ? kRedBytes : kPartBytes;
@@ -45,7 +47,8 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
     // A unit of a few rows (decode) keeps its rows of X in LDS: as MFMA operand, a row is wanted by
     // every lane group, and a global load costs the address unit the same whether its lanes read 16
     // distinct rows or the same one 16 times -- it would spend as long on X as on A_a.
-    const bool xlds = TB == 1 && p.xlds_bytes > 0 && (int64_t)nrows * (kchunks + kXldsPad) * 16 <= p.xlds_bytes;
+    const bool xlds = TB == 1 && p.xlds_bytes > 0 && nrows <= kXldsRows && kchunks <= kXldsChunks * kShWaves * 64 &&
+                      (int64_t)nrows * (kchunks + kXldsPad) * 16 <= p.xlds_bytes;
     chunk_t *xs = reinterpret_cast<chunk_t *>(smem + kShSmemBase);
     const int xstride = kchunks + kXldsPad;
     // Per-lane byte offsets into A_a / X: row (ranks and rows past the end of the unit are clamped to the
@@ -114,21 +117,45 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
         }
     };
     LORA_TS(p.trace, 2);  // row map, adapter pointer, scale read
-    load_batch(st0, xa, aa);  // first: nothing below depends on it, and it is the long pole
-    LORA_TS(p.trace, 3);  // first batch issued
+    // Everything that can be requested now is requested now, oldest first in the order it is needed
+    // (loads return in order): the unit's rows of X (a few KB, from L2), then both batches of A_a --
+    // at K = 4096 that is a wave's whole share.
+    chunk_t xr[kXldsRows][kXldsChunks];
     if (xlds) {
-        for (int t = 0; t < nrows; ++t) {  // nrows and the row are uniform: one row per trip, one chunk per thread
-            const E *src = static_cast<const E *>(p.X) + (int64_t)p.plan.perm[slot0 + t] * p.ldx;
-            for (int c = tid; c < kchunks; c += kShWaves * 64) xs[t * xstride + c] = load_chunk(src + (int64_t)c * CE);
-        }
+#pragma unroll
+        for (int t = 0; t < kXldsRows; ++t)
+            if (t < nrows) {
+                // lane t of the first lane group holds the row map entry of row t
+                const int row = __builtin_amdgcn_readlane(prow[0], t);
+                const E *src = static_cast<const E *>(p.X) + (int64_t)row * p.ldx;
+#pragma unroll
+                for (int u = 0; u < kXldsChunks; ++u) {
+                    const int c = tid + u * (kShWaves * 64);
+                    if (c < kchunks) xr[t][u] = load_chunk(src + (int64_t)c * CE);
+                }
+            }
     }
-    if (xlds) __syncthreads();  // the staged rows are complete (uniform over the workgroup)
+    load_batch(st0, xa, aa);
+    load_batch(st0 + SB, xb, ab);
+    LORA_TS(p.trace, 3);  // loads issued
+    if (xlds) {
+#pragma unroll
+        for (int t = 0; t < kXldsRows; ++t)
+            if (t < nrows) {
+#pragma unroll
+                for (int u = 0; u < kXldsChunks; ++u) {
+                    const int c = tid + u * (kShWaves * 64);
+                    if (c < kchunks) xs[t * xstride + c] = xr[t][u];
+                }
+            }
+        __syncthreads();  // the staged rows are complete (uniform over the workgroup)
+    }
     LORA_TS(p.trace, 4);  // rows staged
     for (int s0 = st0; s0 < st1; s0 += 2 * SB) {
-        load_batch(s0 + SB, xb, ab);
         mma_batch(s0, xa, aa);
         load_batch(s0 + 2 * SB, xa, aa);
         mma_batch(s0 + SB, xb, ab);
+        load_batch(s0 + 3 * SB, xb, ab);
     }
     if ((kchunks & 7) != 0 && wave == kShWaves - 1) {  // the partial pair: chunks past K are zeros
 #pragma unroll

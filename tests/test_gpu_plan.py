@@ -6,11 +6,12 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 
-def _check_plan(ids, L, ranks, device_plan, fused_rows=-1):
+def _check_plan(ids, L, ranks, device_plan, fused_rows=-1, plan_variant=-1):
     import torch
     from gpu_common import ctx, rt, plan_reference
     c = ctx()
     c.set_option("plan_fused_rows", fused_rows)
+    c.set_option("plan_variant", plan_variant)
     ids, L, ranks = np.asarray(ids, np.int32), np.asarray(L, np.int32), np.asarray(ranks, np.int32)
     r_max = int(ranks.max()) if ranks.size else 0
     if device_plan:
@@ -21,6 +22,7 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1):
         pl = rt.plan(c, ids, L, ranks, r_max)
     got = pl.to_host(c)
     c.set_option("plan_fused_rows", -1)
+    c.set_option("plan_variant", -1)
     assert got["status"] == 0
     ref = plan_reference(ids, L, ranks)
     assert got["n_seg"] == ref["n_seg"]
@@ -64,6 +66,23 @@ def test_plan_random(seed, device_plan):
     _check_plan(ids, L, ranks, device_plan, fused_rows=0)   # general kernels (segments + grid-wide fill)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_plan_decode_sized_batches(seed):
+    """At most 64 requests: the one-lane-per-request kernel, against the reference and with the same
+    batch through the other kernels (plan_variant=1)."""
+    rng = np.random.default_rng(300 + seed)
+    n_ad = int(rng.choice([1, 3, 32, 200, 5000]))
+    R = int(rng.choice([1, 2, 17, 63, 64]))
+    ranks = rng.choice([8, 16, 24, 64], size=n_ad)
+    ids = rng.integers(-1, n_ad, size=R)
+    if seed % 2 == 0:
+        ids[rng.integers(0, R, size=R // 2)] = ids[0]  # repeated keys: several requests per segment
+    L = rng.integers(0, 3, size=R) if seed < 3 else rng.integers(0, 60, size=R)  # decode-like / short prefills
+    for variant in (-1, 1):
+        _check_plan(ids, L, ranks, True, plan_variant=variant)
+        _check_plan(ids, L, ranks, False, plan_variant=variant)
+
+
 @pytest.mark.parametrize("fused_rows", [0, 1 << 20])
 def test_plan_both_fill_paths_and_many_requests(fused_rows):
     rng = np.random.default_rng(5)
@@ -102,10 +121,14 @@ def test_plan_device_reports_errors_in_status_word():
         (([0, 1], [1, 1], [8, 16], 8, 2), B.LORA_ERR_RANK_TOO_LARGE),
         (([0, 1], [1, 1], [8, 12], 16, 2), B.LORA_ERR_SHAPE),
     ]
+    cases.append((([0, 5, 1], [1, 1, -1], [8, 8], 8, 1), B.LORA_ERR_LENGTH_MISMATCH))  # two faults: the smaller code
     for (ids, L, ranks, r_max, T), want in cases:
-        pl = rt.plan_device(c, t(ids), t(L), t(ranks), r_max, T)
-        status, n_seg = pl.status(c)
-        assert status == want and n_seg == 0, (ids, L, ranks, status)
+        for variant in (1, -1):  # other kernels, then the decode-sized one
+            c.set_option("plan_variant", variant)
+            pl = rt.plan_device(c, t(ids), t(L), t(ranks), r_max, T)
+            status, n_seg = pl.status(c)
+            assert status == want and n_seg == 0, (ids, L, ranks, status, variant)
+        c.set_option("plan_variant", -1)
         # a failed plan makes the layer a no-op: Y keeps its contents, nothing faults
         X = torch.zeros((T, 64), dtype=torch.bfloat16, device=dev)
         W0 = torch.zeros((32, 64), dtype=torch.bfloat16, device=dev)
