@@ -145,7 +145,9 @@ int lora_ctx_destroy(lora_ctx *ctx);
 
 /* Tuning overrides for experiments ("gemm_variant", "skinny_nb",
  * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
- * decode-sized plan kernel, "shrink_rank_block" = 8 / 16 / 32 / 64);
+ * decode-sized plan kernel, "expand_split" = 0 / 1: adapter term always
+ * computed inside the GEMM / by the separate expand kernel whenever the
+ * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64);
  * value < 0 restores the built-in heuristic.  Results never depend on them
  * beyond fp32 summation order.  Errors: INVALID_ARG for an unknown name or a
  * value the option does not take. */
@@ -204,6 +206,15 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
  * shapes as long as it is big enough for each and the calls do not overlap in
  * time.  Returns 0 for invalid arguments. */
 size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
+
+/* The workspace size that lets every batch take its fastest path: the size
+ * above plus, for batches of more than 128 rows, room for the adapter term
+ * in fp32 ([T, N]).  Batches of many small segments then compute that term
+ * in a weight-streaming kernel of its own and the GEMM adds it before its
+ * single rounding of Y; with a smaller workspace the term is computed inside
+ * the GEMM (same result within fp32 summation order).  Returns 0 for invalid
+ * arguments. */
+size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
 
 /* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an
  * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).

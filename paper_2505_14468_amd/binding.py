@@ -34,7 +34,7 @@ LORA_ERR_PLAN = -10
 EXPORTS = [
     "lora_ctx_create", "lora_ctx_destroy", "lora_ctx_set_option",
     "lora_plan_validate", "lora_plan_bytes", "lora_plan", "lora_plan_device", "lora_plan_status",
-    "lora_linear_workspace_bytes", "lora_shrink", "lora_gemm_expand", "lora_linear",
+    "lora_linear_workspace_bytes", "lora_linear_workspace_bytes_preferred", "lora_shrink", "lora_gemm_expand", "lora_linear",
     "lora_profile_begin", "lora_profile_end",
     "lora_gemm_kernel_name", "lora_strerror", "lora_last_hip_error",
 ]
@@ -95,6 +95,8 @@ def lib():
         L.lora_plan_status.argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.c_void_p, i32p]
         L.lora_linear_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.lora_linear_workspace_bytes.restype = C.c_size_t
+        L.lora_linear_workspace_bytes_preferred.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.lora_linear_workspace_bytes_preferred.restype = C.c_size_t
         for name in ("lora_shrink", "lora_gemm_expand", "lora_linear"):
             getattr(L, name).argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(lora_linear_desc), C.c_void_p]
         L.lora_profile_begin.argtypes = [C.c_void_p, C.c_int]
@@ -195,6 +197,10 @@ def lora_plan_status(ctx, plan: lora_plan_t, stream: int):
 # ---- the layer ------------------------------------------------------------------
 def lora_linear_workspace_bytes(T: int, K: int, N: int, r_max: int, dtype: int) -> int:
     return int(lib().lora_linear_workspace_bytes(int(T), int(K), int(N), int(r_max), int(dtype)))
+
+
+def lora_linear_workspace_bytes_preferred(T: int, K: int, N: int, r_max: int, dtype: int) -> int:
+    return int(lib().lora_linear_workspace_bytes_preferred(int(T), int(K), int(N), int(r_max), int(dtype)))
 
 
 def make_adapter_table(n_adapters: int, A_ptrs: int, B_ptrs: int, scale_ptr: int) -> lora_adapter_table_t:

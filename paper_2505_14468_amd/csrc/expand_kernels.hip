@@ -1,0 +1,201 @@
+// Segmented LoRA expand as a kernel of its own, for batches of many small segments:
+//
+//     D[row, n] = sum_j V[row, j] * B_a[n, j]        for the rows of every adapter segment, in fp32
+//
+// (second half of the adapter product of paper section 4.4; the base GEMM that runs next adds D to
+// its fp32 accumulators before it rounds and stores Y, once).  When an M tile of the fused GEMM holds dozens of adapters, every
+// extension stage there serves a handful of rows, and the adapters' B matrices -- together larger
+// than W0 in such a batch -- arrive through a two-deep, latency-bound pipeline.  Here the same work
+// is a weight-streaming problem laid out like the shrink:
+//
+//   * a workgroup = one work unit of the plan's list (<= 64 rows of one segment) x 1024 output columns
+//     (long enough a stream of B_a to pay for the unit's set-up: work list, row map, V);
+//   * the unit's rows of V (<= 64 x r, a few KB) are staged in LDS once; as MFMA operand they are
+//     read from there, so global loads carry B_a only;
+//   * each of the 8 waves walks 16-column blocks; MFMA 16x16x32 with the 16 output columns as M
+//     (operand rows = rows of B_a, contiguous along the rank) and 16 token rows as N; the loads of
+//     the next group of MFMA steps are in flight while the current one is multiplied, across block
+//     boundaries;
+//   * steps come in pairs that share one 128-byte piece of every B_a row (step 2m takes the even
+//     16-byte chunks, step 2m+1 the odd ones), so a load instruction covers whole cache lines;
+//   * every (row, column) with an adapter belongs to exactly one unit, so D is stored, not accumulated;
+//     rows without an adapter are never written and never read.  D costs 8 bytes of traffic per output
+//     element with an adapter, against the B_a bytes streamed at HBM speed instead of through a
+//     latency-bound pipeline; the host picks this path for batches of many small segments only.
+#include "kernels.h"
+
+namespace lora {
+namespace {
+
+constexpr int kExWaves = 8;
+constexpr int kExBlocksPerWave = 8;                               // 16-column blocks per wave
+constexpr int kExCols = kExWaves * kExBlocksPerWave * 16;         // output columns per workgroup
+constexpr int kExGroup = 4;                                       // MFMA steps per load group
+constexpr int kExPad = 1;                                         // chunks of padding per staged row of V
+
+template <typename E, int TB>
+__device__ __forceinline__ void expand_unit(const ExpandArgs &p, const E *Ba, int r, int slot0, int nrows, int nwg0,
+                                            unsigned char *smem) {
+    constexpr int CE = Elem<E>::CE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int rchunks = r / CE;
+    const int vstride = rchunks + kExPad;
+    chunk_t *vs = reinterpret_cast<chunk_t *>(smem);
+    const E *V = static_cast<const E *>(p.V);
+
+    // rows of D this lane stores (rows past the unit: never stored)
+    int64_t drow[TB];
+    bool rok[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int t = tb * 16 + li;
+        rok[tb] = t < nrows;
+        drow[tb] = (int64_t)p.plan.perm[slot0 + min(t, nrows - 1)] * p.ldd;
+    }
+    const chunk_t *vrow[TB];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) vrow[tb] = vs + min(tb * 16 + li, nrows - 1) * vstride;
+
+    // MFMA steps over the rank: pairs of steps, lane group g takes chunks 2g (even step) and 2g+1 (odd step)
+    // of each 8-chunk piece; chunks past the rank contribute zeros (the V operand is zeroed).
+    const int steps = 2 * ((rchunks + 7) >> 3);
+    const int groups = (steps + kExGroup - 1) / kExGroup;
+    auto chunk_of = [&](int st) { return (st >> 1) * 8 + 2 * lg + (st & 1); };
+
+    // this wave's column blocks: nwg0 + (wave + 8 * b) * 16, b = 0 .. kExBlocksPerWave-1 (those below N)
+    auto block_n0 = [&](int b) { return nwg0 + (wave + kExWaves * b) * 16; };
+    int nblk = 0;
+#pragma unroll
+    for (int b = 0; b < kExBlocksPerWave; ++b) nblk += block_n0(b) < p.N ? 1 : 0;
+    const int total = nblk * groups;  // (block, group) pairs, walked in order
+
+    chunk_t wa[kExGroup], wb[kExGroup];
+    auto load_group = [&](int q, chunk_t (&wf)[kExGroup]) {
+        if (q < total) {
+            const int b = q / groups, g = q - b * groups;
+            const E *brow = Ba + (int64_t)min(block_n0(b) + li, p.N - 1) * r;  // columns past N: clamped, never stored
+#pragma unroll
+            for (int s = 0; s < kExGroup; ++s) {
+                const int st = g * kExGroup + s;
+                const int kc = chunk_of(st);
+                wf[s] = load_chunk(brow + (int64_t)((st < steps && kc < rchunks) ? kc : 0) * CE);
+            }
+        }
+    };
+    f32x4_t acc[TB];
+    auto mma_group = [&](int q, const chunk_t (&wf)[kExGroup]) {
+        const int g = q % groups;
+#pragma unroll
+        for (int s = 0; s < kExGroup; ++s) {
+            const int st = g * kExGroup + s;
+            if (st < steps) {
+                const int kc = chunk_of(st);
+                const bool ok = kc < rchunks;
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) {
+                    const chunk_t v = keep_if(ok, vrow[tb][ok ? kc : 0]);
+                    Elem<E>::mma16(acc[tb], wf[s], v);
+                }
+            }
+        }
+    };
+    // acc[tb][e] = D[n = n0 + lg*4 + e][t = tb*16 + li]: a lane stores 4 consecutive columns of one row
+    auto flush_block = [&](int b) {
+        const int n = block_n0(b) + lg * 4;
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) {
+            if (!rok[tb]) continue;
+            float *dst = p.D + drow[tb] + n;
+            if (n + 3 < p.N) {
+                store4(dst, acc[tb][0], acc[tb][1], acc[tb][2], acc[tb][3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < p.N) dst[e] = acc[tb][e];
+            }
+        }
+    };
+
+    // the first two groups of B_a go out before V is staged: nothing they need depends on it
+    load_group(0, wa);
+    load_group(1, wb);
+    // ---- stage the unit's rows of V (original row order in memory: gather through the row map) ----
+    for (int e = tid; e < nrows * rchunks; e += kExWaves * 64) {
+        const int t = e / rchunks, c = e - t * rchunks;
+        vs[t * vstride + c] = load_chunk(V + (int64_t)p.plan.perm[slot0 + t] * p.r_max + (int64_t)c * CE);
+    }
+    __syncthreads();
+    for (int q = 0; q < total; q += 2) {
+        if (q > 0) load_group(q + 1, wb);
+        if (q % groups == 0) {
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        mma_group(q, wa);
+        if ((q + 1) % groups == 0) flush_block(q / groups);
+        load_group(q + 2, wa);
+        if (q + 1 < total) {
+            if ((q + 1) % groups == 0) {
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            }
+            mma_group(q + 1, wb);
+            if ((q + 2) % groups == 0) flush_block((q + 1) / groups);
+        }
+    }
+}
+
+template <typename E>
+__global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int unit = blockIdx.x / p.col_groups;
+    const int cg = blockIdx.x - unit * p.col_groups;
+    // the grid is an upper bound of the unit count and the work list is that long
+    const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
+    const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
+    if (status != 0 || unit >= n_units) return;
+    const int a = rec.x, r = rec.y, slot0 = rec.z, nrows = rec.w;
+    if (a < 0 || r <= 0 || nrows <= 0) return;
+    const E *Ba = static_cast<const E *>(p.B[a]);
+    if (Ba == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
+        if (threadIdx.x == 0) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+        const int n_lo = cg * kExCols, n_hi = min(n_lo + kExCols, p.N);
+        for (int e = threadIdx.x; e < nrows * (n_hi - n_lo); e += kExWaves * 64) {
+            const int t = e / (n_hi - n_lo), n = n_lo + e - t * (n_hi - n_lo);
+            p.D[(int64_t)p.plan.perm[slot0 + t] * p.ldd + n] = 0.f;
+        }
+        return;
+    }
+    if (nrows <= 16)
+        expand_unit<E, 1>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+    else
+        expand_unit<E, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+}
+
+}  // namespace
+
+size_t expand_smem_bytes(int r_max, int dtype) {
+    const int ce = dtype == 1 ? 8 : 4;
+    return (size_t)kShrinkRows * (size_t)(r_max / ce + kExPad) * 16;
+}
+
+hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, const KernelTimer *timer) {
+    if (a0.max_units <= 0 || a0.N <= 0) return hipSuccess;
+    ExpandArgs a = a0;
+    a.col_groups = (a.N + kExCols - 1) / kExCols;
+    const long grid = (long)a.max_units * a.col_groups;
+    const size_t smem = expand_smem_bytes(a.r_max, dtype);
+    static size_t attr_bytes[2] = {0, 0};  // more than the default 64 KB of dynamic LDS (ranks above ~480)
+    if (smem > 64 * 1024 && smem > attr_bytes[dtype == 1]) {
+        const void *fn = dtype == 1 ? reinterpret_cast<const void *>(expand_kernel<__bf16>)
+                                    : reinterpret_cast<const void *>(expand_kernel<float>);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_bytes[dtype == 1] = smem;
+    }
+    if (dtype == 1) return launch_kernel(expand_kernel<__bf16>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
+    return launch_kernel(expand_kernel<float>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
+}
+
+}  // namespace lora

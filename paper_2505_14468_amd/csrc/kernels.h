@@ -138,11 +138,27 @@ struct GemmArgs {
     int64_t ldy;
     const void *V;         // [T, r_max] of E, original row order (null when no adapters)
     const void *Xpack;     // fragment-major copy of X (decode-sized kernel only)
-    const void *const *B;  // device table (null when no adapters)
+    const void *const *B;  // device table (null when no adapters, or when the adapter term comes in D)
+    const float *D;        // adapter term in fp32, [T, ldd], original row order, rows with an adapter only (null = none)
+    int64_t ldd;
     int32_t r_max;
     int32_t T, K, N;
     long long *trace = nullptr;  // phase stamps (trace builds only)
 };
+
+// Separate expand kernel (many small segments): D[row, :] = V[row, :] B_a^T per shrink work unit, in fp32.
+struct ExpandArgs {
+    PlanView plan;
+    const void *V;         // [T, r_max] of E, original row order
+    const void *const *B;  // device table
+    float *D;              // [T, ldd] fp32, original row order; rows without an adapter are not written
+    int64_t ldd;
+    int32_t r_max;
+    int32_t N;
+    int32_t max_units;     // upper bound of work units (grid = max_units * col_groups)
+    int32_t col_groups;    // set by the launcher: ceil(N / columns per workgroup)
+};
+hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 
 enum GemmVariant {
     kGemmTile128x128 = 0,

@@ -58,6 +58,7 @@ struct lora_ctx {
     int opt_plan_fused_rows = -1;
     int opt_shrink_rank_block = -1;
     int opt_plan_variant = -1;
+    int opt_expand_split = -1;
     // profiling mode: event pairs recorded tightly around each kernel
     bool prof_on = false;
     int prof_cap = 0;
@@ -325,7 +326,8 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 }
 
 struct WorkspaceLayout {
-    size_t v_off, xpack_off, xpack_bytes, total;
+    size_t v_off, xpack_off, xpack_bytes, total;  // total: what every call needs
+    size_t d_off, d_bytes, ldd, total_preferred;  // fp32 adapter term of the separate expand kernel (optional)
 };
 
 // Bytes of the fragment-major copy of X the decode-sized GEMM reads (whole 64-k stages, 16-row blocks).
@@ -344,6 +346,10 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     w.xpack_bytes = (dtype == LORA_DTYPE_BF16 && T > 0 && T <= kSkinnyMaxRows) ? xpack_bytes_for(T, K) : 0;
     off = align_up(off + w.xpack_bytes, 256);
     w.total = off < 256 ? 256 : off;
+    w.ldd = align_up((size_t)N, 4);
+    w.d_off = w.total;
+    w.d_bytes = T > kSkinnyMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
+    w.total_preferred = align_up(w.d_off + w.d_bytes, 256);
     return w;
 }
 
@@ -460,14 +466,49 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
         if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
     }
+    // Batches of many small segments (an M tile of the fused kernel would hold dozens of adapters, a few
+    // rows each): a weight-streaming kernel computes the adapter term per segment into the workspace (fp32)
+    // and the GEMM adds it to its accumulators -- if the caller's workspace has the room.
+    bool split = false;
+    if (ad && c.variant != kGemmSkinny && w.d_bytes > 0 && d->workspace_bytes >= w.total_preferred) {
+        const int64_t segs = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;  // upper bound
+        split = segs > 0 && plan->T / segs < 64;
+        if (ctx->opt_expand_split >= 0) split = ctx->opt_expand_split == 1;
+    }
+    a.D = nullptr;
+    a.ldd = 0;
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
+    // (in split mode one event pair brackets both kernels: start with the first, stop with the second)
+    KernelTimer first = timer, second = timer;
+    first.stop = nullptr;
+    second.start = nullptr;
+    if (split) {
+        ExpandArgs e;
+        e.plan = view_of(plan);
+        e.V = ws + w.v_off;
+        e.B = d->tbl->B;
+        e.D = reinterpret_cast<float *>(ws + w.d_off);
+        e.ldd = (int64_t)w.ldd;
+        e.r_max = plan->r_max;
+        e.N = d->N;
+        const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
+        const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
+        e.max_units = (int32_t)(plan->T / kShrinkRows + seg_bound2);  // as for the shrink grid
+        e.col_groups = 0;
+        LORA_HIP(launch_expand(e, d->dtype, stream, timed ? &first : nullptr));
+        a.B = nullptr;
+        a.V = nullptr;
+        a.D = e.D;
+        a.ldd = e.ldd;
+    }
+    const KernelTimer *tg = !timed ? nullptr : (split ? &second : &timer);
     if (c.variant == kGemmSkinny)
-        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
+        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, tg));
     else if (c.variant >= kGemmPipe256x256w8)
-        LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
+        LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, tg));
     else
-        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
+        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
     return LORA_OK;
 }
 
@@ -532,6 +573,9 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
         ctx->opt_skinny_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
         ctx->opt_plan_fused_rows = value;
+    } else if (!strcmp(name, "expand_split")) {
+        if (value > 1) return LORA_ERR_INVALID_ARG;
+        ctx->opt_expand_split = value;
     } else if (!strcmp(name, "plan_variant")) {
         if (value > 1) return LORA_ERR_INVALID_ARG;
         ctx->opt_plan_variant = value;
@@ -619,6 +663,11 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
     if (T < 0 || K <= 0 || N <= 0 || r_max < 0 || (dtype != LORA_DTYPE_BF16 && dtype != LORA_DTYPE_F32)) return 0;
     return workspace_layout(T, K, N, r_max, dtype).total;
+}
+
+size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
+    if (T < 0 || K <= 0 || N <= 0 || r_max < 0 || (dtype != LORA_DTYPE_BF16 && dtype != LORA_DTYPE_F32)) return 0;
+    return workspace_layout(T, K, N, r_max, dtype).total_preferred;
 }
 
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {

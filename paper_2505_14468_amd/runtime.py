@@ -174,8 +174,10 @@ def plan_device(ctx: Context, req_adapter: torch.Tensor, req_ntok: torch.Tensor,
     return Plan(st, buf, keep=(req_adapter, req_ntok, adapter_rank))
 
 
-def workspace(T: int, K: int, N: int, r_max: int, dtype: torch.dtype, device) -> torch.Tensor:
-    nbytes = B.lora_linear_workspace_bytes(T, K, N, r_max, dtype_code(dtype))
+def workspace(T: int, K: int, N: int, r_max: int, dtype: torch.dtype, device, minimal: bool = False) -> torch.Tensor:
+    """Workspace of the preferred size (every batch can take its fastest path), or of the minimal one."""
+    fn = B.lora_linear_workspace_bytes if minimal else B.lora_linear_workspace_bytes_preferred
+    nbytes = fn(T, K, N, r_max, dtype_code(dtype))
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 

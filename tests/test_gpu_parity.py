@@ -49,6 +49,30 @@ def test_tile_kernels_ragged_multi_tile(variant, dtype):
     reset_options()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_separate_expand_kernel_ragged(dtype):
+    """The adapter term added by the expand kernel of its own (many small segments) instead of inside the
+    GEMM: ragged N, ranks that are not multiples of 32, segments of more than 16 and more than 64 rows,
+    rows without an adapter, zero-length requests; both results against the oracle and against each other."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, TOL
+    ids, L = _mixed_batch(11, R=60, n_ad=7, max_len=30)
+    ids[:6] = 3  # one adapter with a long segment
+    L[:6] = 29
+    wl = make_custom(seed=77, dtype=dtype, K=264, N=1100, ranks=(8, 16, 64, 40, 8, 24, 128), scales=(2.0, 0.5, 1.0, 0.25, 1.5, 1.0, 0.75),
+                     req_adapter=ids, req_ntok=L, name=f"expand_split_{dtype}")
+    assert wl.T > 256
+    out = {}
+    for split in (0, 1):
+        ctx().set_option("expand_split", split)
+        for device_plan in (False, True):
+            out[split] = gpu_linear(wl, device_plan=device_plan)
+            e = check_against_oracle(wl, out[split])
+        print(f"{wl.name} split={split}: T={wl.T} err/rms {e:.2e}", flush=True)
+    rms = float(np.sqrt((out[0] ** 2).mean()))
+    assert float(np.abs(out[0] - out[1]).max()) <= TOL[dtype] * rms
+    reset_options()
+
+
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
 def test_skinny_kernel_row_counts(T):
     """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""
