@@ -92,6 +92,24 @@ def test_skinny_kernel_row_counts(T):
     reset_options()
 
 
+@pytest.mark.parametrize("T", [3, 70])
+def test_decode_kernels_long_contraction_axis(T):
+    """K of a down projection (11016 = 172 stages of 64 + one chunk): more than one W0 window per wave in the
+    decode GEMM, many load batches per wave in the shrink, rows of X too long to be staged in LDS; ranks up
+    to 128 (several rank blocks per unit)."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
+    rng = np.random.default_rng(900 + T)
+    ranks = (8, 128, 64, 16)
+    ids = rng.integers(-1, len(ranks), size=T)
+    wl = make_custom(seed=500 + T, dtype="bf16", K=11016, N=40, ranks=ranks, scales=(1.0, 0.5, 2.0, 1.0),
+                     req_adapter=ids, req_ntok=np.ones(T, int), name=f"long_k_T{T}")
+    for rb in (-1, 64):
+        ctx().set_option("shrink_rank_block", rb)
+        e = check_against_oracle(wl, gpu_linear(wl, device_plan=True))
+    print(f"{wl.name}: err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
 def test_skinny_equals_tile_path_within_tolerance_and_tile_handles_small_T():
     from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
     ids, L = _mixed_batch(8, R=20, n_ad=5, max_len=6)
