@@ -35,14 +35,6 @@ namespace {
 
 constexpr int kSkWaves = 8;
 constexpr int kSkThreads = kSkWaves * 64;
-constexpr int kSkTab = 512;  // extension chunks described per batch (128 MFMA steps)
-
-struct SkTable {
-    const void *ptr[kSkTab];  // B_a + j
-    int r[kSkTab];            // row stride of B_a
-    int j[kSkTab];            // column inside V / B_a
-    int a[kSkTab];            // adapter id (-2 = unused column)
-};
 
 template <int TBLK, int NB>
 __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
@@ -58,7 +50,6 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *red = reinterpret_cast<float *>(smem);  // [kSkWaves][TILE]
     chunk_t *wstage = reinterpret_cast<chunk_t *>(smem + (size_t)kSkWaves * TILE * sizeof(float));  // [kSkWaves][WBUF]
-    SkTable *tab = reinterpret_cast<SkTable *>(wstage + kSkWaves * WBUF);
 
     // the wave index as a scalar: K ranges, stage counters and stage offsets then live in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -149,68 +140,35 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
             }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     };
-    // ---- extension table: one entry per 8 ranks of the batch's concatenated rank space ----------------
-    // An entry takes two dependent loads (the plan's record, then the adapter table's pointer).  Loads
-    // return in order, so each of the two is issued just BEFORE a batch of the base product's loads:
-    // waiting for it then waits for nothing younger, and the round trips are hidden behind the batches.
-    static_assert(kSkTab == kSkThreads, "one table entry per thread");
+    // ---- extension: MFMA steps over the batch's concatenated rank space, dealt round-robin to the waves ----
+    // A step is 4 chunks of 8 ranks; lane group g works on chunk 4 s + g, described by one record of the plan
+    // (adapter, its rank, the chunk's offset inside it).  Every lane fetches the record and then the
+    // adapter's B pointer for its own chunk -- two dependent loads, no table in LDS, no barrier.  Loads return
+    // in order, so each of the two is issued just BEFORE a batch of the base product's loads: waiting for it
+    // then waits for nothing younger, and the round trips hide behind the batches.  A trip is two steps.
     const int ext_chunks = p.B != nullptr ? p.plan.scalars[kScExtTotal] / CE : 0;
     const int status = p.plan.scalars[kScStatus];
-    struct Entry {
-        const void *ptr;
-        int r, j, a;
-    };
-    auto fetch_rec = [&](int ch) {  // record of extension chunk ch (unused: adapter -2)
-        int4 rec = make_int4(-2, 0, 0, 0);
-        if (ch < ext_chunks) rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[ch];
-        return rec;
-    };
-    auto fetch_ptr = [&](const int4 &rec) { return rec.x >= 0 ? p.B[rec.x] : nullptr; };
-    auto publish = [&](int idx, const int4 &rec, const void *b) {
-        Entry e{nullptr, 0, 0, -2};
-        if (b != nullptr) {
-            e.r = rec.y >> 16;
-            e.j = rec.y & 0xffff;
-            e.a = rec.x;
-            e.ptr = static_cast<const E *>(b) + e.j;
-        } else if (rec.x != -2) {
-            atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
-        }
-        tab->ptr[idx] = e.ptr;
-        tab->r[idx] = e.r;
-        tab->j[idx] = e.j;
-        tab->a[idx] = e.a;
-    };
-
-    const int4 rec0 = fetch_rec(tid);
-    load_w(sg0);
-    load_x(sg0, xa);
-    if (status != 0) return;
-    const void *bptr0 = fetch_ptr(rec0);
-    int row_ad[TBLK];
-#pragma unroll
-    for (int tb = 0; tb < TBLK; ++tb) {
-        const int t = tb * 16 + li;
-        row_ad[tb] = (ext_chunks > 0 && t < p.T) ? p.plan.row_adapter[t] : -1;
-    }
-    load_x(sg0 + XB, xb);
-    LORA_TS(p.trace, 1);  // first window of W0 and two batches of X issued
-    if (ext_chunks > 0) {
-        publish(tid, rec0, bptr0);
-        __syncthreads();
-    }
-    LORA_TS(p.trace, 2);  // table published
-
-    // ---- extension steps, dealt round-robin to the waves; a trip = two steps, their loads overlap ---------
-    auto ext_load = [&](int s, int nst, chunk_t (&wf)[2][NB], chunk_t (&xf)[2][TBLK]) {
+    const int nst = (ext_chunks + 3) >> 2;
+    int row_ad[TBLK];  // adapter of this lane's token rows (set below)
+    auto fetch_rec = [&](int s, int4 (&rec)[2]) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const int idx = min(s + u * kSkWaves, kSkTab / 4 - 1) * 4 + lg;
-            const bool live = s + u * kSkWaves < nst;
-            const E *bp = static_cast<const E *>(tab->ptr[idx]);
-            const int r = tab->r[idx], j = tab->j[idx], a = tab->a[idx];
-            const bool wok = live && bp != nullptr;
-            const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
+            const int ch = (s + u * kSkWaves) * 4 + lg;
+            rec[u] = make_int4(-2, 0, 0, 0);  // unused chunk
+            if (ch < ext_chunks) rec[u] = reinterpret_cast<const int4 *>(p.plan.ext_rec)[ch];
+        }
+    };
+    auto fetch_ptr = [&](const int4 (&rec)[2], const void *(&bp)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) bp[u] = rec[u].x >= 0 ? p.B[rec[u].x] : nullptr;
+    };
+    auto ext_load = [&](const int4 (&rec)[2], const void *(&bp)[2], chunk_t (&wf)[2][NB], chunk_t (&xf)[2][TBLK]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int a = rec[u].x, r = rec[u].y >> 16, j = rec[u].y & 0xffff;
+            const bool wok = bp[u] != nullptr;
+            if (a >= 0 && !wok) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);  // slot emptied after the plan
+            const E *bsrc = wok ? static_cast<const E *>(bp[u]) + j : W;  // W: some in-bounds address for the dropped loads
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int n = min(n0 + nb * 16 + li, p.N - 1);
@@ -219,7 +177,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 #pragma unroll
             for (int tb = 0; tb < TBLK; ++tb) {
                 const int t = min(tb * 16 + li, p.T - 1);
-                const bool xok = live && row_ad[tb] == a;  // rows of other adapters contribute nothing
+                const bool xok = wok && row_ad[tb] == a;  // rows of other adapters contribute nothing
                 xf[u][tb] = keep_if(xok, load_chunk(V + (xok ? (int64_t)t * p.r_max + j : 0)));
             }
         }
@@ -232,15 +190,30 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 #pragma unroll
                 for (int tb = 0; tb < TBLK; ++tb) Elem<E>::mma16(acc[nb][tb], wf[u][nb], xf[u][tb]);
     };
-    const int nst0 = (min(ext_chunks, kSkTab) + 3) >> 2;  // steps of the first table
-    const bool ext_first = wave < nst0;                  // this wave has a first trip
+
+    const bool ext_first = wave < nst;  // this wave has a first trip (steps wave and wave + 8)
+    constexpr bool kEarly = TBLK * NB <= 4;  // registers to spare for the early fetch (else: after the K loop)
+    int4 rec0[2];
+    const void *bptr0[2];
+    if (kEarly) fetch_rec(wave, rec0);
+    load_w(sg0);
+    load_x(sg0, xa);
+    if (status != 0) return;
+    if (kEarly) fetch_ptr(rec0, bptr0);
+#pragma unroll
+    for (int tb = 0; tb < TBLK; ++tb) {
+        const int t = tb * 16 + li;
+        row_ad[tb] = (ext_chunks > 0 && t < p.T) ? p.plan.row_adapter[t] : -1;
+    }
+    load_x(sg0 + XB, xb);
+    LORA_TS(p.trace, 1);  // first window of W0 and two batches of X issued
     chunk_t ewf[2][NB], exf[2][TBLK];
 
     // ---- the K loop; the operands of the wave's first extension trip are fetched under its last pass ----
     bool ext_loaded = false;
     for (int S = sg0; S < sg1; S += WS) {
-        if (TBLK <= 4 && ext_first && S + WS >= sg1) {  // the last window hides the first extension trip's loads (registers permitting)
-            ext_load(wave, nst0, ewf, exf);
+        if (kEarly && ext_first && S + WS >= sg1) {  // the last window hides the first extension trip's loads
+            ext_load(rec0, bptr0, ewf, exf);
             ext_loaded = true;
         }
 #pragma unroll
@@ -271,25 +244,21 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
         mma_stage(wf, xf);
     }
     if (ext_first) {
-        if (!ext_loaded) ext_load(wave, nst0, ewf, exf);  // a wave without a share of K
+        if (!kEarly) {
+            fetch_rec(wave, rec0);
+            fetch_ptr(rec0, bptr0);
+        }
+        if (!ext_loaded) ext_load(rec0, bptr0, ewf, exf);  // a wave without a share of K, or no registers to spare
         ext_mma(ewf, exf);
-        for (int s = wave + 2 * kSkWaves; s < nst0; s += 2 * kSkWaves) {
-            ext_load(s, nst0, ewf, exf);
+        for (int s = wave + 2 * kSkWaves; s < nst; s += 2 * kSkWaves) {  // more than 64 chunks of ranks in the batch
+            int4 rec[2];
+            const void *bp[2];
+            fetch_rec(s, rec);
+            fetch_ptr(rec, bp);
+            ext_load(rec, bp, ewf, exf);
             ext_mma(ewf, exf);
         }
     }
-    for (int chunk0 = kSkTab; chunk0 < ext_chunks; chunk0 += kSkTab) {  // more than one table's worth
-        __syncthreads();  // every wave is done with the previous table
-        const int4 rec = fetch_rec(chunk0 + tid);
-        publish(tid, rec, fetch_ptr(rec));
-        __syncthreads();
-        const int nst = (min(ext_chunks - chunk0, kSkTab) + 3) >> 2;
-        for (int s = wave; s < nst; s += 2 * kSkWaves) {
-            ext_load(s, nst, ewf, exf);
-            ext_mma(ewf, exf);
-        }
-    }
-
     LORA_TS(p.trace, 4);  // extension issued
     // ---- sum the 8 partial tiles in wave order, store Y once ------------------------------------------------
     // acc[nb][tb][e] = D[n = n0 + nb*16 + lg*4 + e][t = tb*16 + li]
@@ -333,8 +302,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 template <int TBLK, int NB>
 hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
     const int n_tiles = (a.N + 16 * NB - 1) / (16 * NB);
-    const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t) +
-                        sizeof(SkTable);
+    const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t);
     auto kern = gemm_skinny_kernel<TBLK, NB>;
     static bool attr_set = false;
     if (!attr_set) {
