@@ -342,7 +342,7 @@ constexpr int kSmallRows = 8192;
 
 __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs p) {
     __shared__ int s_a[kSmallReq], s_L[kSmallReq + 64], s_key[kSmallReq + 64], s_tok[kSmallReq + 1], s_dst[kSmallReq];
-    __shared__ int s_hist[kSmallKeys], s_cur[kSmallKeys], s_kseg[kSmallKeys];
+    __shared__ int s_hist[kSmallKeys], s_cur[kSmallKeys], s_kseg[kSmallKeys], s_ofl[kSmallReq];
     __shared__ int s_sad[kSmallKeys + 1], s_sip[kSmallKeys + 1], s_srk[kSmallKeys + 1], s_sex[kSmallKeys + 1], s_sun[kSmallKeys + 1];
     __shared__ int wave_sums[4][kPlanWaves];
     __shared__ int s_status;
@@ -481,31 +481,49 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         p.seg_unit[s] = s_sun[s];
     }
 
-    // 4. stable destination of every request: one wave, 64 requests at a time.  Every lane compares its
-    //    key with the 64 keys of the chunk, which it reads from LDS (same address for all lanes: a
-    //    broadcast); the loads pipeline, and there is no cross-lane instruction on the serial path.
+    // 4. stable destination of every request, 64 requests (one wave) at a time.
+    //    4a, all waves, a chunk of 64 requests each: rows of earlier requests of the chunk with the same key,
+    //        and whether a later request of the chunk has the key -- the other requests' (key, rows) are
+    //        broadcast one by one from scalar registers.
+    //    4b, one wave, chunk after chunk (the only serial part: two LDS accesses per chunk): running slot of
+    //        the key + offset inside the chunk; the last request of a key in the chunk advances the slot.
+    {
+        const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        for (int base = wave * 64; base < R; base += kPlanThreads) {
+            const int i = base + lane;
+            const bool valid = i < R;
+            const int key = valid ? s_key[i] : -2;
+            const int L = valid ? s_L[i] : 0;
+            int off = 0, later = 0;
+#pragma unroll 16
+            for (int l2 = 0; l2 < 64; ++l2) {
+                const int k2 = __builtin_amdgcn_readlane(key, l2);
+                const int L2 = __builtin_amdgcn_readlane(L, l2);
+                const bool same = k2 == key;
+                off += (same && l2 < lane) ? L2 : 0;
+                later |= (same && l2 > lane) ? 1 : 0;
+            }
+            if (valid) s_ofl[i] = (off << 1) | (later ? 0 : 1);
+        }
+    }
+    __syncthreads();
     if (tid < 64) {
         volatile int *cur = s_cur;
         const int lane = tid;
         for (int base = 0; base < R; base += 64) {
             const int i = base + lane;
             const bool valid = i < R;
-            const int key = valid ? s_key[i] : -2;
-            const int L = valid ? s_L[i] : 0;
-            int off = 0, later = 0;
-#pragma unroll 8
-            for (int l2 = 0; l2 < 64; ++l2) {
-                const bool same = s_key[base + l2] == key;  // entries past R hold -3
-                off += (same && l2 < lane) ? s_L[base + l2] : 0;
-                later |= (same && l2 > lane) ? 1 : 0;
-            }
-            int b = 0;
+            int b = 0, off = 0, last = 0, key = 0;
             if (valid) {
+                key = s_key[i];
+                const int ofl = s_ofl[i];
+                off = ofl >> 1;
+                last = ofl & 1;
                 b = cur[key];
                 s_dst[i] = b + off;
             }
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // all lanes have read before any lane writes
-            if (valid && !later) cur[key] = b + off + L;
+            if (valid && last) cur[key] = b + off + s_L[i];
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         }
     }
