@@ -13,9 +13,8 @@
 //   * the unit's rows of V (<= 64 x r, a few KB) are staged in LDS once; as MFMA operand they are
 //     read from there, so global loads carry B_a only;
 //   * each of the 8 waves walks 16-column blocks; MFMA 16x16x32 with the 16 output columns as M
-//     (operand rows = rows of B_a, contiguous along the rank) and 16 token rows as N; the loads of
-//     the next group of MFMA steps are in flight while the current one is multiplied, across block
-//     boundaries;
+//     (operand rows = rows of B_a, contiguous along the rank) and 16 token rows as N; four groups
+//     of loads (16 KB per wave) are in flight while one is multiplied, across block boundaries;
 //   * steps come in pairs that share one 128-byte piece of every B_a row (step 2m takes the even
 //     16-byte chunks, step 2m+1 the odd ones), so a load instruction covers whole cache lines;
 //   * every (row, column) with an adapter belongs to exactly one unit, so D is stored, not accumulated;
@@ -31,6 +30,7 @@ constexpr int kExWaves = 8;
 constexpr int kExBlocksPerWave = 8;                               // 16-column blocks per wave
 constexpr int kExCols = kExWaves * kExBlocksPerWave * 16;         // output columns per workgroup
 constexpr int kExGroup = 4;                                       // MFMA steps per load group
+constexpr int kExRing = 4;                                        // load groups in flight per wave
 constexpr int kExPad = 1;                                         // chunks of padding per staged row of V
 
 template <typename E, int TB>
@@ -63,14 +63,14 @@ __device__ __forceinline__ void expand_unit(const ExpandArgs &p, const E *Ba, in
     const int groups = (steps + kExGroup - 1) / kExGroup;
     auto chunk_of = [&](int st) { return (st >> 1) * 8 + 2 * lg + (st & 1); };
 
-    // this wave's column blocks: nwg0 + (wave + 8 * b) * 16, b = 0 .. kExBlocksPerWave-1 (those below N)
-    auto block_n0 = [&](int b) { return nwg0 + (wave + kExWaves * b) * 16; };
+    // this wave's column blocks, b = 0 .. kExBlocksPerWave-1 (those below N): pairs of adjacent blocks (32 columns:
+    // a row's two stores fall into one 128-byte line), pair p of wave w at column 32 * (w + 8 p)
+    auto block_n0 = [&](int b) { return nwg0 + (2 * wave + (b & 1) + 2 * kExWaves * (b >> 1)) * 16; };
     int nblk = 0;
 #pragma unroll
     for (int b = 0; b < kExBlocksPerWave; ++b) nblk += block_n0(b) < p.N ? 1 : 0;
     const int total = nblk * groups;  // (block, group) pairs, walked in order
 
-    chunk_t wa[kExGroup], wb[kExGroup];
     auto load_group = [&](int q, chunk_t (&wf)[kExGroup]) {
         if (q < total) {
             const int b = q / groups, g = q - b * groups;
@@ -117,31 +117,32 @@ __device__ __forceinline__ void expand_unit(const ExpandArgs &p, const E *Ba, in
         }
     };
 
-    // the first two groups of B_a go out before V is staged: nothing they need depends on it
-    load_group(0, wa);
-    load_group(1, wb);
     // ---- stage the unit's rows of V (original row order in memory: gather through the row map) ----
+    // V first: it comes from L2 and loads return in order -- behind B_a's loads from HBM it would arrive last.
+    LORA_TS(p.trace, 2);  // row map read
     for (int e = tid; e < nrows * rchunks; e += kExWaves * 64) {
         const int t = e / rchunks, c = e - t * rchunks;
         vs[t * vstride + c] = load_chunk(V + (int64_t)p.plan.perm[slot0 + t] * p.r_max + (int64_t)c * CE);
     }
+    // ---- a ring of kExRing groups of B_a loads in flight per wave ----
+    chunk_t ring[kExRing][kExGroup];
+#pragma unroll
+    for (int i = 0; i < kExRing; ++i) load_group(i, ring[i]);
     __syncthreads();
-    for (int q = 0; q < total; q += 2) {
-        if (q > 0) load_group(q + 1, wb);
-        if (q % groups == 0) {
+    LORA_TS(p.trace, 3);  // V staged
+    for (int q0 = 0; q0 < total; q0 += kExRing) {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        }
-        mma_group(q, wa);
-        if ((q + 1) % groups == 0) flush_block(q / groups);
-        load_group(q + 2, wa);
-        if (q + 1 < total) {
-            if ((q + 1) % groups == 0) {
+        for (int i = 0; i < kExRing; ++i) {
+            const int q = q0 + i;
+            if (q < total) {
+                if (q % groups == 0) {
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    for (int tb = 0; tb < TB; ++tb) acc[tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
+                mma_group(q, ring[i]);
+                if ((q + 1) % groups == 0) flush_block(q / groups);
+                load_group(q + kExRing, ring[i]);
             }
-            mma_group(q + 1, wb);
-            if ((q + 2) % groups == 0) flush_block((q + 1) / groups);
         }
     }
 }
@@ -149,6 +150,7 @@ __device__ __forceinline__ void expand_unit(const ExpandArgs &p, const E *Ba, in
 template <typename E>
 __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    LORA_TS(p.trace, 0);
     const int unit = blockIdx.x / p.col_groups;
     const int cg = blockIdx.x - unit * p.col_groups;
     // the grid is an upper bound of the unit count and the work list is that long
@@ -158,6 +160,7 @@ __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
     const int a = rec.x, r = rec.y, slot0 = rec.z, nrows = rec.w;
     if (a < 0 || r <= 0 || nrows <= 0) return;
     const E *Ba = static_cast<const E *>(p.B[a]);
+    LORA_TS(p.trace, 1);  // work-list record read
     if (Ba == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
         if (threadIdx.x == 0) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
         const int n_lo = cg * kExCols, n_hi = min(n_lo + kExCols, p.N);
@@ -171,6 +174,7 @@ __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
         expand_unit<E, 1>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
     else
         expand_unit<E, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+    LORA_TS(p.trace, 5);
 }
 
 }  // namespace
@@ -194,8 +198,17 @@ hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, co
         if (e != hipSuccess) return e;
         attr_bytes[dtype == 1] = smem;
     }
+#ifdef LORA_TRACE
+    return trace_launch("expand", grid, [&](long long *buf) {
+        ExpandArgs b = a;
+        b.trace = buf;
+        if (dtype == 1) return launch_kernel(expand_kernel<__bf16>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, b);
+        return launch_kernel(expand_kernel<float>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, b);
+    });
+#else
     if (dtype == 1) return launch_kernel(expand_kernel<__bf16>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
     return launch_kernel(expand_kernel<float>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
+#endif
 }
 
 }  // namespace lora

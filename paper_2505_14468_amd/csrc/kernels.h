@@ -157,6 +157,7 @@ struct ExpandArgs {
     int32_t N;
     int32_t max_units;     // upper bound of work units (grid = max_units * col_groups)
     int32_t col_groups;    // set by the launcher: ceil(N / columns per workgroup)
+    long long *trace = nullptr;  // phase stamps (trace builds only)
 };
 hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 
