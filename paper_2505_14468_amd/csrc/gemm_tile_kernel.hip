@@ -250,29 +250,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 #pragma unroll
     for (int tb = 0; tb < NBT; ++tb) {
         const int t = m0 + wm0 + tb * 32 + l31;
-        if (t >= p.T) continue;
-        const int row = p.plan.perm[t];
+        const bool row_ok = t < p.T;
+        const int row = p.plan.perm[min(t, p.T - 1)];
         E *yrow = Y + (int64_t)row * p.ldy;
-        // the adapter term, when a kernel of its own has computed it (rows with an adapter only): added in
-        // fp32, before the one rounding
+        // the adapter term, when a kernel of its own has computed it (rows with an adapter only)
         const float *drow = (p.D != nullptr && p.plan.row_adapter[row] >= 0) ? p.D + (int64_t)row * p.ldd : nullptr;
 #pragma unroll
-        for (int nb = 0; nb < NBN; ++nb) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn0 + nb * 32 + g * 8 + lh * 4;
-                const f32x16_t &c = acc[nb][tb];
-                if (n + 3 < p.N) {
-                    float d[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (drow != nullptr) load4(drow + n, d);
-                    store4(yrow + n, c[g * 4 + 0] + d[0], c[g * 4 + 1] + d[1], c[g * 4 + 2] + d[2], c[g * 4 + 3] + d[3]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < p.N) store1(yrow + n + e, c[g * 4 + e] + (drow != nullptr ? drow[n + e] : 0.f));
-                }
-            }
-        }
+        for (int nb = 0; nb < NBN; ++nb) store_acc_tile<E>(acc[nb][tb], yrow, drow, n0 + wn0 + nb * 32, lh, p.N, row_ok);
     }
 }
 
