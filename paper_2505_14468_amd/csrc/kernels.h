@@ -71,7 +71,7 @@ inline hipError_t trace_launch(const char *name, long grid, Launch launch) {
         long long t0 = -1;
         for (long g = 0; g < grid; ++g)
             if (h[g * 8] && (t0 < 0 || h[g * 8] < t0)) t0 = h[g * 8];
-        const long stride = grid > 48 ? grid / 24 : 1;
+        const long stride = getenv("LORA_TRACE_ALL") ? 1 : (grid > 48 ? grid / 24 : 1);  // a sample of the workgroups, or all
         for (long g = 0; g < grid; g += stride) {
             if (!h[g * 8]) continue;
             printf("trace %s wg %ld:", name, g);

@@ -26,7 +26,7 @@ def _sample_rows(wl, n, seed=0):
     return np.array(sorted(rows))[: n + 16]
 
 
-def _run_full(idx, p=0, n_rows=12):
+def _run_full(idx, p=0, n_rows=12, minimal_workspace=False):
     import torch
     from gpu_common import ctx, rt, check_against_oracle, reset_options, B
     from workloads import to_f64
@@ -44,7 +44,10 @@ def _run_full(idx, p=0, n_rows=12):
     rn = torch.from_numpy(np.ascontiguousarray(wl.req_ntok)).to(dev)
     rk = torch.from_numpy(np.ascontiguousarray(wl.ranks)).to(dev)
     pl = rt.plan_device(c, ra, rn, rk, wl.r_max, wl.T)
-    Y = rt.linear(c, pl, X, W0, table)
+    pr = wl.projections[p]
+    # minimal workspace: no room for the separate expand kernel's term, the adapter term is computed inside the GEMM
+    ws = rt.workspace(wl.T, pr.K, pr.N, wl.r_max, X.dtype, dev, minimal=minimal_workspace)
+    Y = rt.linear(c, pl, X, W0, table, ws=ws)
     torch.cuda.synchronize()
     status, _ = pl.status(c)
     assert status == 0
@@ -53,11 +56,10 @@ def _run_full(idx, p=0, n_rows=12):
     full = np.zeros((wl.T, Yh.shape[1]))
     full[rows] = Yh
     e = check_against_oracle(wl, full, p=p, rows=rows)
-    pr = wl.projections[p]
     name = B.lora_gemm_kernel_name(c.handle, wl.T, pr.K, pr.N, rt.dtype_code(X.dtype))
     print(f"config {idx} {pr.name}: T={wl.T} kernel={name} rows checked={rows.size} err/rms={e:.2e}", flush=True)
     # determinism at full size (bitwise)
-    Y2 = rt.linear(c, pl, X, W0, table)
+    Y2 = rt.linear(c, pl, X, W0, table, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(Y.view(torch.int16) if Y.dtype == torch.bfloat16 else Y, Y2.view(torch.int16) if Y2.dtype == torch.bfloat16 else Y2)
     wl.drop_cache()
@@ -89,6 +91,11 @@ def test_config3_sampled_rows(p):
 
 def test_config4_sampled_rows():
     _run_full(4, n_rows=8)
+
+
+def test_config3_minimal_workspace_fused_expand():
+    """The same batch of many small segments with the adapter term inside the GEMM (workspace of the minimal size)."""
+    _run_full(3, p=0, minimal_workspace=True)
 
 
 @pytest.mark.parametrize("batch", [1, 10, 20, 32, 73])
