@@ -231,7 +231,10 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.unit_rec = base + L.unit_rec;
     a.ext_rec = base + L.ext_rec;
     a.scalars = base + L.scalars;
-    const int fused_rows = ctx->opt_plan_fused_rows >= 0 ? ctx->opt_plan_fused_rows : 4096;
+    // One workgroup builds the whole plan (per-row arrays included) up to 4096 rows, up to 8192 for batches of at
+    // most 64 requests (the one-lane-per-request kernel leaves its workgroup more time for the rows); beyond that
+    // the per-row arrays are filled by a second, grid-wide kernel.
+    const int fused_rows = ctx->opt_plan_fused_rows >= 0 ? ctx->opt_plan_fused_rows : (n_req <= 64 ? 8192 : 4096);
     const bool fuse = T <= fused_rows && L.ext_cap <= 8192;
     KernelTimer timers[2];
     const bool timed = next_timer(ctx, kProfPlanSegments, &timers[0]) && (fuse || next_timer(ctx, kProfPlanFill, &timers[1]));
