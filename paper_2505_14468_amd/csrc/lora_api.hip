@@ -430,7 +430,8 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     const int64_t mid_groups = (plan->r_max + 15) / 16;
     // (every rank block of a unit reads the unit's rows of X again: only worth it while X is small)
     const bool small_x = plan->T <= 256;
-    int rank_block = !ad || !small_x                                      ? kShrinkRanks
+    int rank_block = !ad                                                  ? kShrinkRanks
+                     : !small_x ? (a.max_units * wide_groups < (int64_t)ctx->num_cu && plan->r_max > 32 ? 32 : kShrinkRanks)
                      : a.max_units * mid_groups < 2 * (int64_t)ctx->num_cu  ? 8
                      : a.max_units * wide_groups < 2 * (int64_t)ctx->num_cu ? 16
                                                                             : kShrinkRanks;
