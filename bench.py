@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=1, help="workload: index into BASELINE.json configs (default 1)")
     ap.add_argument("--proj", type=int, default=0, help="projection of a multi-projection workload (config 3)")
+    ap.add_argument("--same-adapter", type=int, default=0, metavar="ROWS",
+                    help="instead of --config: ROWS single-token requests on ONE adapter at config 1's shape "
+                         "(one function's own batch, the regime of the paper's section 6)")
     ap.add_argument("--weight-sets", type=int, default=0, help="rotating weight sets (0 = sized to exceed the caches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true", help="skip the sampled parity check against the oracle")
@@ -71,9 +74,9 @@ def main():
         return
     from paper_2505_14468_amd import binding as B
     from paper_2505_14468_amd import runtime as rt
-    from workloads import make_workload, to_f64
+    from workloads import make_workload, same_adapter_decode, to_f64
 
-    wl = make_workload(args.config)
+    wl = same_adapter_decode(args.same_adapter) if args.same_adapter > 0 else make_workload(args.config)
     p = args.proj
     pr = wl.projections[p]
     K, N, T = pr.K, pr.N, wl.T
@@ -155,7 +158,7 @@ def main():
     v_bytes = es * int(sum(int(wl.ranks[a]) * int(n) for a, n in zip(*np.unique(wl.row_adapter()[wl.row_adapter() >= 0], return_counts=True))))
     gemm_bytes = es * (T * K + K * N + T * N + r_used * N) + v_bytes
     gemm_flops = 2 * T * K * N + 2 * N * v_bytes // es
-    hbm_bound = HBM_BOUND.get(args.config, T <= 256)
+    hbm_bound = T <= 256 if args.same_adapter > 0 else HBM_BOUND.get(args.config, T <= 256)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):

@@ -53,6 +53,11 @@ struct KernelTimer {
     do {                                                                                    \
         if ((buf) != nullptr && threadIdx.x == 0) (buf)[blockIdx.x * 8 + (i)] = wall_clock64(); \
     } while (0)
+// the same from the first thread of wave `w` (how far apart the waves of a workgroup finish a phase)
+#define LORA_TS_WAVE(buf, i, w)                                                                              \
+    do {                                                                                                     \
+        if ((buf) != nullptr && (int)threadIdx.x == (w) * 64) (buf)[blockIdx.x * 8 + (i)] = wall_clock64(); \
+    } while (0)
 template <typename Launch>
 inline hipError_t trace_launch(const char *name, long grid, Launch launch) {
     const char *want = getenv("LORA_TRACE");
@@ -85,6 +90,9 @@ inline hipError_t trace_launch(const char *name, long grid, Launch launch) {
 #else
 #define LORA_TS(buf, i) \
     do {                \
+    } while (0)
+#define LORA_TS_WAVE(buf, i, w) \
+    do {                        \
     } while (0)
 #endif
 

@@ -14,6 +14,8 @@
 // units spend their registers on loads in flight rather than on empty tiles.
 // The per-wave partial tiles are summed through LDS in wave order, so the result is
 // deterministic, scaled by s_a in fp32 and stored once (bf16 or fp32), in original row order.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace lora {
@@ -23,46 +25,64 @@ constexpr int kShWaves = 8;
 constexpr int kRS = kShrinkRanks + 1;             // padded row stride of the serial reduction buffer
 constexpr int kRedBytes = kShrinkRows * kRS * 4;  // serial reduction buffer (large units)
 constexpr int kPartBytes = kShWaves * 4 * 1024;   // per-wave partial tiles (units of at most 4 MFMA tiles)
+constexpr int kStageBytes = kShWaves * 2048;       // per-wave buffers that turn loaded lines into MFMA operands
 constexpr int kXldsBytes = 64 * 1024;             // rows of X staged in LDS (units of a few rows)
 constexpr int kXldsPad = 4;                       // chunks of padding per staged row: rows fall into different banks
 constexpr int kXldsRows = 4;                      // at most this many rows are staged ...
 constexpr int kXldsChunks = 2;                    // ... of at most this many chunks per thread (K <= 8192 in bf16)
 
-// Dynamic LDS of the kernel: [reduction area][X staging area (only when launched with it)].
+// Dynamic LDS of the kernel: [reduction area][operand buffers][X staging area (only when launched with it)].
 constexpr int kShSmemBase = kRedBytes > kPartBytes ? kRedBytes : kPartBytes;
 
 template <typename E, int TB, int JB>
 __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, float scale, int slot0, int nrows, int j0,
-                                            int nj, const int (&prow)[4], unsigned char *smem) {
+                                            int nj, const int (&prow)[4][2], unsigned char *smem) {
     constexpr int CE = Elem<E>::CE;
     constexpr int LPS = TB + JB;
-    constexpr int SB = (TB * JB >= 8 ? 12 : 16) / LPS;  // MFMA steps per load batch (2 batches in flight)
-    // The wave index as a scalar: the K ranges, step counters and step offsets below then live in scalar
+    // Stages (128 bytes of every row: two MFMA steps) of operand loads in flight per wave, held in a ring of
+    // registers; a 16-row block is requested again for the stage RS later as soon as it has been consumed.
+    constexpr int RS = LPS >= 8 ? 1 : 16 / LPS;
+    // The wave index as a scalar: the K ranges, stage counters and stage offsets below then live in scalar
     // registers and cost the vector pipeline nothing.  (Units of a few rows are short serial instruction
     // streams; every dependent vector instruction is ~10 cycles of their run time.)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int kchunks = p.K / CE;
 
-    // A unit of a few rows (decode) keeps its rows of X in LDS: as MFMA operand, a row is wanted by
-    // every lane group, and a global load costs the address unit the same whether its lanes read 16
-    // distinct rows or the same one 16 times -- it would spend as long on X as on A_a.
+    // A unit of a few rows (decode) keeps its rows of X in LDS, shared by the waves: as MFMA operand a row
+    // is wanted by every lane group of every wave.
     const bool xlds = TB == 1 && p.xlds_bytes > 0 && nrows <= kXldsRows && kchunks <= kXldsChunks * kShWaves * 64 &&
                       (int64_t)nrows * (kchunks + kXldsPad) * 16 <= p.xlds_bytes;
-    chunk_t *xs = reinterpret_cast<chunk_t *>(smem + kShSmemBase);
+    chunk_t *xs = reinterpret_cast<chunk_t *>(smem + kShSmemBase + kStageBytes);
     const int xstride = kchunks + kXldsPad;
-    // Per-lane byte offsets into A_a / X: row (ranks and rows past the end of the unit are clamped to the
-    // last one) and this lane group's first chunk of a 128-byte piece; what changes per step is a scalar.
+
+    // Operand loads.  An MFMA operand wants "row lane % 16, 16 bytes of k" per lane; read like that from a
+    // row-major matrix an instruction touches 16 cache lines for 64 bytes each, and the vector cache then
+    // delivers a third of what it does for whole lines (measured per CU: ~30 against ~80 GB/s).  So a stage
+    // (128 bytes of every row: two MFMA steps) of a 16-row block is loaded as two instructions of 8 rows x
+    // 128 bytes -- lane -> (row lane / 8 + 8 i, chunk lane % 8) -- and turned into operand layout through
+    // a 2 KB wave-private, XOR-swizzled LDS buffer (no barrier: LDS operations of one wave execute in
+    // order).  Step h of a stage takes chunks 4 h .. 4 h + 3, lane group g chunk 4 h + g, for both operands.
+    // Ranks and rows past the end of the unit are clamped to the last one.
+    const int wr = lane >> 3, wc = lane & 7;
     const char *Ab = reinterpret_cast<const char *>(Aa);
-    unsigned aoff[JB];
+    unsigned aoff[JB][2];
+    const char *xrow[TB][2];
+    int wdst[2];
 #pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-        aoff[jb] = (unsigned)(((int64_t)(j0 + min(jb * 16 + li, nj - 1)) * p.K + 2 * lg * CE) * (int64_t)sizeof(E));
-    const char *xrow[TB];
+    for (int i = 0; i < 2; ++i) {
+        const int row = wr + 8 * i;
+        wdst[i] = row * 8 + (wc ^ ((row >> 1) & 7));
 #pragma unroll
-    for (int tb = 0; tb < TB; ++tb)
-        xrow[tb] = reinterpret_cast<const char *>(p.X) + ((int64_t)prow[tb] * p.ldx + 2 * lg * CE) * (int64_t)sizeof(E);
-    const chunk_t *xsrow = xs + min(li, nrows - 1) * xstride + 2 * lg;
+        for (int jb = 0; jb < JB; ++jb)
+            aoff[jb][i] = (unsigned)(((int64_t)(j0 + min(jb * 16 + row, nj - 1)) * p.K + wc * CE) * (int64_t)sizeof(E));
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+            xrow[tb][i] = reinterpret_cast<const char *>(p.X) + ((int64_t)prow[tb][i] * p.ldx + wc * CE) * (int64_t)sizeof(E);
+    }
+    chunk_t *buf = reinterpret_cast<chunk_t *>(smem + kShSmemBase) + wave * 128;
+    const int rsrc = li * 8, rswz = (li >> 1) & 7;
+    const chunk_t *xsrow = xs + min(li, nrows - 1) * xstride + lg;
 
     f32x4_t acc[TB][JB];
 #pragma unroll
@@ -70,63 +90,80 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) acc[tb][jb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    // This wave's share of the MFMA steps along K (one step = 4 chunks).  Steps come in pairs that
-    // share one 128-byte piece of every row: step 2m takes its even chunks, step 2m+1 the odd ones
-    // (lane group g: chunks 2g and 2g+1), so that both loads of a lane fall into the same line;
-    // the order of the k terms inside a pair is free as long as A_a and X use the same one.
-    // Whole pairs are dealt to the waves; a last partial pair (K not a multiple of 64) goes to the
-    // last wave, masked.
-    const int pairs = kchunks >> 3;
-    const int st0 = 2 * (int)((int64_t)pairs * wave / kShWaves), st1 = 2 * (int)((int64_t)pairs * (wave + 1) / kShWaves);
-    auto step_chunk = [&](int st) { return (st >> 1) * 8 + (st & 1); };  // without the lane group's 2g
+    // This wave's share of the stages along K.  Whole stages are dealt to the waves; a last partial one
+    // (K not a multiple of the 128-byte piece) goes to the last wave, masked.
+    const int full = kchunks >> 3;
+    const int sg0 = (int)((int64_t)full * wave / kShWaves), sg1 = (int)((int64_t)full * (wave + 1) / kShWaves);
 
-    // Steps past the wave's range are skipped (a uniform branch), not loaded and dropped: the address
+    // Stages past the wave's range are skipped (a uniform branch), not loaded and dropped: the address
     // unit's time is what this kernel runs out of.
-    chunk_t xa[SB][TB], aa[SB][JB], xb[SB][TB], ab[SB][JB];
-    auto load_batch = [&](int s0, chunk_t (&xf)[SB][TB], chunk_t (&af)[SB][JB]) {
+    struct StageRegs {
+        chunk_t x[TB][2], a[JB][2];
+    };
+    StageRegs ring[RS];
+    // (the caller guarantees sg < sg1, or skips the call under a uniform branch)
+    auto load_x = [&](int sg, int tb, StageRegs &f) {
+        if (!xlds) {
 #pragma unroll
-        for (int s = 0; s < SB; ++s) {
-            const int st = s0 + s;
-            if (st < st1) {
-                const unsigned sb = (unsigned)step_chunk(st) * 16u;  // scalar byte offset of the step
-                if (!xlds) {
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb) xf[s][tb] = load_chunk(xrow[tb] + sb);
-                }
-#pragma unroll
-                for (int jb = 0; jb < JB; ++jb) af[s][jb] = load_chunk(Ab + sb + aoff[jb]);
-            }
+            for (int i = 0; i < 2; ++i) f.x[tb][i] = load_chunk(xrow[tb][i] + (unsigned)sg * 128u);  // scalar stage offset
         }
     };
-    auto mma_batch = [&](int s0, const chunk_t (&xf)[SB][TB], const chunk_t (&af)[SB][JB]) {
+    auto load_a = [&](int sg, int jb, StageRegs &f) {
 #pragma unroll
-        for (int s = 0; s < SB; ++s) {
-            const int st = s0 + s;
-            if (st < st1) {
-                if (xlds) {
-                    const chunk_t x = xsrow[step_chunk(st)];
+        for (int i = 0; i < 2; ++i) f.a[jb][i] = load_chunk(Ab + (unsigned)sg * 128u + aoff[jb][i]);
+    };
+    // one 16-row block of one stage: through the wave's buffer into the two steps' operands
+    auto to_operands = [&](const chunk_t (&in)[2], chunk_t (&out)[2]) {
+        buf[wdst[0]] = in[0];
+        buf[wdst[1]] = in[1];
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // keeps the compiler from reordering across the exchange
+        out[0] = buf[rsrc + (lg ^ rswz)];
+        out[1] = buf[rsrc + ((4 + lg) ^ rswz)];
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    };
+    // One stage: X blocks to operands, then rank block by rank block.  REFILL: every consumed block is
+    // requested again for stage `next`, unconditionally -- loads behind a branch would make the compiler wait
+    // for ALL loads in flight at every use, because it can no longer count the younger ones.
+    auto mma_stage = [&](int sg, StageRegs &f, int next, auto refill, bool partial) {
+        constexpr int REFILL = decltype(refill)::value;  // 0 never, 1 always, 2 if next < sg1
+        const bool again = REFILL == 1 || (REFILL == 2 && next < sg1);
+        chunk_t x[TB][2];
+        if (xlds) {
 #pragma unroll
-                    for (int jb = 0; jb < JB; ++jb) Elem<E>::mma16(acc[0][jb], af[s][jb], x);
-                } else {
-#pragma unroll
-                    for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-                        for (int jb = 0; jb < JB; ++jb) Elem<E>::mma16(acc[tb][jb], af[s][jb], xf[s][tb]);
-                }
+            for (int h = 0; h < 2; ++h) {
+                const int kc = sg * 8 + h * 4;  // + lg is in xsrow
+                x[0][h] = xsrow[kc];
+                if (partial) x[0][h] = keep_if(kc + lg < kchunks, x[0][h]);  // the staged rows end at K
             }
+        } else {
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                to_operands(f.x[tb], x[tb]);
+                if (again) load_x(next, tb, f);
+            }
+        }
+#pragma unroll
+        for (int jb = 0; jb < JB; ++jb) {
+            chunk_t a[2];
+            to_operands(f.a[jb], a);
+            if (again) load_a(next, jb, f);
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int tb = 0; tb < TB; ++tb) Elem<E>::mma16(acc[tb][jb], a[h], x[tb][h]);
         }
     };
     LORA_TS(p.trace, 2);  // row map, adapter pointer, scale read
     // Everything that can be requested now is requested now, oldest first in the order it is needed
-    // (loads return in order): the unit's rows of X (a few KB, from L2), then both batches of A_a --
-    // at K = 4096 that is a wave's whole share.
+    // (loads return in order): the unit's rows of X (a few KB, from L2), then the ring of operand
+    // stages -- for a unit of one block each at K = 4096 that is a wave's whole share.
     chunk_t xr[kXldsRows][kXldsChunks];
     if (xlds) {
 #pragma unroll
         for (int t = 0; t < kXldsRows; ++t)
             if (t < nrows) {
-                // lane t of the first lane group holds the row map entry of row t
-                const int row = __builtin_amdgcn_readlane(prow[0], t);
+                // lane 8 t holds the row map entry of row t
+                const int row = __builtin_amdgcn_readlane(prow[0][0], 8 * t);
                 const E *src = static_cast<const E *>(p.X) + (int64_t)row * p.ldx;
 #pragma unroll
                 for (int u = 0; u < kXldsChunks; ++u) {
@@ -135,8 +172,16 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
                 }
             }
     }
-    load_batch(st0, xa, aa);
-    load_batch(st0 + SB, xb, ab);
+    if (sg0 < sg1) {  // (a wave with fewer than RS stages requests its last one more than once)
+#pragma unroll
+        for (int q = 0; q < RS; ++q) {
+            const int sg = min(sg0 + q, sg1 - 1);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) load_x(sg, tb, ring[q]);
+#pragma unroll
+            for (int jb = 0; jb < JB; ++jb) load_a(sg, jb, ring[q]);
+        }
+    }
     LORA_TS(p.trace, 3);  // loads issued
     if (xlds) {
 #pragma unroll
@@ -151,31 +196,37 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
         __syncthreads();  // the staged rows are complete (uniform over the workgroup)
     }
     LORA_TS(p.trace, 4);  // rows staged
-    for (int s0 = st0; s0 < st1; s0 += 2 * SB) {
-        mma_batch(s0, xa, aa);
-        load_batch(s0 + 2 * SB, xa, aa);
-        mma_batch(s0 + SB, xb, ab);
-        load_batch(s0 + 3 * SB, xb, ab);
+    int g0 = sg0;
+    for (; g0 + 2 * RS <= sg1; g0 += RS) {  // every stage here has its refill stage inside the wave's range
+#pragma unroll
+        for (int q = 0; q < RS; ++q) mma_stage(g0 + q, ring[q], g0 + q + RS, std::integral_constant<int, 1>{}, false);
     }
-    if ((kchunks & 7) != 0 && wave == kShWaves - 1) {  // the partial pair: chunks past K are zeros
+    if (g0 + RS < sg1) {  // the last ring-ful with refills: some of them
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int kc = pairs * 8 + 2 * lg + h;
-            const bool ok = kc < kchunks;
-            const int sb = ok ? (pairs * 8 + h) * 16 : -(2 * lg * 16);  // dropped loads read the start of the row
-            chunk_t x[TB], a[JB];
+        for (int q = 0; q < RS; ++q) mma_stage(g0 + q, ring[q], g0 + q + RS, std::integral_constant<int, 2>{}, false);
+        g0 += RS;
+    }
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) x[tb] = keep_if(ok, load_chunk(xrow[tb] + sb));
+    for (int q = 0; q < RS; ++q)
+        if (g0 + q < sg1) mma_stage(g0 + q, ring[q], 0, std::integral_constant<int, 0>{}, false);
+    if ((kchunks & 7) != 0 && wave == kShWaves - 1) {  // the partial stage: chunks past K are zeros
+        const bool ok = full * 8 + wc < kchunks;
+        const int sb = ok ? full * 128 : -(wc * 16);  // dropped loads read the start of the row
+        StageRegs f;
 #pragma unroll
-            for (int jb = 0; jb < JB; ++jb) a[jb] = keep_if(ok, load_chunk(Ab + ((int64_t)aoff[jb] + sb)));
+        for (int i = 0; i < 2; ++i) {
+            if (!xlds) {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb)
+                for (int tb = 0; tb < TB; ++tb) f.x[tb][i] = keep_if(ok, load_chunk(xrow[tb][i] + sb));
+            }
 #pragma unroll
-                for (int jb = 0; jb < JB; ++jb) Elem<E>::mma16(acc[tb][jb], a[jb], x[tb]);
+            for (int jb = 0; jb < JB; ++jb) f.a[jb][i] = keep_if(ok, load_chunk(Ab + ((int64_t)aoff[jb][i] + sb)));
         }
+        mma_stage(full, f, 0, std::integral_constant<int, 0>{}, true);
     }
 
-    LORA_TS(p.trace, 5);  // K loop issued
+    LORA_TS(p.trace, 5);  // K loop done (first wave)
+    LORA_TS_WAVE(p.trace, 7, kShWaves - 1);  // (last wave)
     // Sum the per-wave partial tiles in wave order (fixed order -> deterministic), scale, store.
     // acc[tb][jb][e] holds D[j = jb*16 + lg*4 + e][t = tb*16 + li].
     E *V = static_cast<E *>(p.V);
@@ -280,12 +331,13 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     const int nj = min(p.rank_block, r - j0);
     // Rows past the end of the unit are clamped to its last one: they only feed accumulator
     // entries that are never stored.
-    int prow[4];
-    {
-        const int li = tid & 15;
-        prow[0] = p.plan.perm[slot0 + min(li, nrows - 1)];
+    int prow[4][2];  // lane -> row lane / 8 + 8 i of each 16-row block (the operand loads' mapping)
 #pragma unroll
-        for (int tb = 1; tb < 4; ++tb) prow[tb] = nrows > 16 ? p.plan.perm[slot0 + min(tb * 16 + li, nrows - 1)] : prow[0];
+    for (int i = 0; i < 2; ++i) {
+        const int row = ((tid & 63) >> 3) + 8 * i;
+        prow[0][i] = p.plan.perm[slot0 + min(row, nrows - 1)];
+#pragma unroll
+        for (int tb = 1; tb < 4; ++tb) prow[tb][i] = nrows > 16 ? p.plan.perm[slot0 + min(tb * 16 + row, nrows - 1)] : prow[0][i];
     }
     const E *Aa = static_cast<const E *>(p.A[a]);
     const float scale = p.scale[a];
@@ -325,14 +377,14 @@ hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, con
     const long grid = (long)a.max_units * a.rank_groups + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
-    const size_t smem = (size_t)kShSmemBase + (size_t)a.xlds_bytes;
+    const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;
     static bool attr_set = false;  // more than the default 64 KB of dynamic LDS
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<__bf16>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kShSmemBase + kXldsBytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kShSmemBase + kStageBytes + kXldsBytes);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<float>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kShSmemBase + kXldsBytes);
+                                    kShSmemBase + kStageBytes + kXldsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
