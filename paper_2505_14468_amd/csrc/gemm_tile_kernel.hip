@@ -84,16 +84,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 
     // ---- per-thread load slots ------------------------------------------------------------
     const int lrow = tid >> 3, lc = tid & 7;
-    const E *xsrc[XL];
+    // 32-bit offsets in 16-byte chunks (row start + this thread's chunk of a stage): half the registers of
+    // pointers, and one 64-bit shift-add per load (rows are 16-byte aligned, so ldx and ldw are whole chunks)
+    const chunk_t *Xc = static_cast<const chunk_t *>(p.X), *Wc = static_cast<const chunk_t *>(p.W);
+    unsigned xoff[XL], woff[WL];
     int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
     for (int i = 0; i < XL; ++i) {  // rows past T / N are clamped: they only feed outputs that are never stored
         xrowi[i] = p.plan.perm[min(m0 + lrow + i * RPP, p.T - 1)];
-        xsrc[i] = X + (int64_t)xrowi[i] * p.ldx;
+        xoff[i] = (unsigned)((int64_t)xrowi[i] * (p.ldx / CE) + lc);
     }
-    const E *wsrc[WL];
 #pragma unroll
-    for (int i = 0; i < WL; ++i) wsrc[i] = W + (int64_t)min(n0 + lrow + i * RPP, p.N - 1) * p.ldw;
+    for (int i = 0; i < WL; ++i) woff[i] = (unsigned)((int64_t)min(n0 + lrow + i * RPP, p.N - 1) * (p.ldw / CE) + lc);
 
     // ---- extension range of this M-tile -----------------------------------------------------
     int pbeg = 0, pend = 0;
@@ -145,19 +147,18 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // Loads are branch-free so that all of a stage's loads are in flight together.  Full stages need
     // no mask at all; the last, partial stage of K loads chunk 0 instead and drops it.
     auto load_base = [&](int kt, bool partial) {
-        const int kc = kt * 8 + lc;
         if (!partial) {
 #pragma unroll
-            for (int i = 0; i < XL; ++i) xr[i] = load_chunk(xsrc[i] + kc * CE);
+            for (int i = 0; i < XL; ++i) xr[i] = load_chunk(Xc + ((size_t)xoff[i] + kt * 8));
 #pragma unroll
-            for (int i = 0; i < WL; ++i) wr[i] = load_chunk(wsrc[i] + kc * CE);
+            for (int i = 0; i < WL; ++i) wr[i] = load_chunk(Wc + ((size_t)woff[i] + kt * 8));
         } else {
-            const bool kv = kc * CE < p.K;
-            const int off = kv ? kc * CE : 0;
+            const bool kv = (kt * 8 + lc) * CE < p.K;
+            const int off = kv ? kt * 8 : -lc;
 #pragma unroll
-            for (int i = 0; i < XL; ++i) xr[i] = keep_if(kv, load_chunk(xsrc[i] + off));
+            for (int i = 0; i < XL; ++i) xr[i] = keep_if(kv, load_chunk(Xc + ((int64_t)xoff[i] + off)));
 #pragma unroll
-            for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, load_chunk(wsrc[i] + off));
+            for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, load_chunk(Wc + ((int64_t)woff[i] + off)));
         }
     };
     auto load_ext = [&](int se) {  // se = stage inside the current table batch
@@ -213,18 +214,77 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     };
 
     // ---- base product: sum over K ---------------------------------------------------------------
+    // One barrier per stage, and the matrix cores have work queued on both sides of it: operands are
+    // read from LDS one use ahead, in place -- a W operand is requested for the next k-step as soon
+    // as its two MFMAs of this one are issued, the two X operands alternate between two register
+    // sets.  The last k-step of a stage is split: half of its MFMAs go out before the stage's stores
+    // and barrier, the other half after the barrier, behind the first operand reads of the next
+    // stage, whose latency they cover.  Global loads for the stage after next are issued right
+    // behind the barrier and have a whole stage to arrive.
     const int KT = (p.K + 8 * CE - 1) / (8 * CE);
     const int KT_full = p.K / (8 * CE);  // stages that lie entirely inside K
+    auto read_w = [&](int buf, int kk, int nb) { return sW[buf * BN * 8 + swz(wn0 + nb * 32 + l31, 2 * kk + lh)]; };
+    auto read_x = [&](int buf, int kk, int tb) { return sX[buf * BM * 8 + swz(wm0 + tb * 32 + l31, 2 * kk + lh)]; };
     load_base(0, KT_full < 1);
     store_stage(0);
+    if (KT > 1) load_base(1, 1 >= KT_full);
     __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) load_base(kt + 1, kt + 1 >= KT_full);
-        compute(kt & 1, -1);
-        if (more) store_stage((kt + 1) & 1);
+    chunk_t wf[NBN], xf[2][NBT];
+#pragma unroll
+    for (int tb = 0; tb < NBT; ++tb) xf[0][tb] = read_x(0, 0, tb);
+#pragma unroll
+    for (int nb = 0; nb < NBN; ++nb) wf[nb] = read_w(0, 0, nb);
+    // (more: a next stage exists; load2: so does the one after it, partial2: which is the partial one)
+    // The waves of a SIMD take turns at the address unit: a stage's loads of all waves at once keep every
+    // wave waiting at its load instructions (the unit takes one every ~16 cycles) with its MFMAs queued up
+    // behind them.  The first half of the waves requests stage kt + 2 right behind the barrier, the second
+    // half one k-step later -- while one wave of a SIMD waits to issue loads, the other issues MFMAs.
+    const bool late = __builtin_amdgcn_readfirstlane(wave) >= (WM * WN) / 2;
+    auto stage = [&](int kt, bool more, bool load2, bool partial2, bool load1, bool partial1) {
+        const int buf = kt & 1;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            const int cur = kk & 1;
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) xf[cur ^ 1][tb] = read_x(buf, kk + 1, tb);
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb) {
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[cur][tb]);
+                wf[nb] = read_w(buf, kk + 1, nb);
+            }
+            if (kk == 0 && late && load1) load_base(kt + 1, partial1);
+        }
+        // k-step 3 (operands in xf[1], wf): first half, stores of the next stage, barrier, second half
+        constexpr int H = NBN > 1 ? NBN / 2 : 1;
+#pragma unroll
+        for (int nb = 0; nb < H; ++nb)
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
+        if (more) store_stage(buf ^ 1);
         __syncthreads();
+        if (!late && load2) load_base(kt + 2, partial2);
+        if (more) {
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) xf[0][tb] = read_x(buf ^ 1, 0, tb);
+#pragma unroll
+            for (int nb = 0; nb < H; ++nb) wf[nb] = read_w(buf ^ 1, 0, nb);
+        }
+#pragma unroll
+        for (int nb = H; nb < NBN; ++nb) {
+#pragma unroll
+            for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
+            if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
+        }
+    };
+    // (stage 1 was requested by every wave before the loop)
+    int kt = 0;
+    if (KT_full > 2) {
+        stage(0, true, true, false, false, false);
+        for (kt = 1; kt + 2 < KT_full; ++kt) stage(kt, true, true, false, true, false);  // the steady state
     }
+    for (; kt < KT; ++kt) stage(kt, kt + 1 < KT, kt + 2 < KT, kt + 2 >= KT_full, kt >= 1 && kt + 1 < KT, kt + 1 >= KT_full);
+    __syncthreads();  // (NBN == 1: the second half above is empty and reads of the last buffer end after its barrier)
 
     // ---- extension: sum over the concatenated ranks of this tile's adapters -----------------------
     for (int chunk0 = 0; chunk0 < ext_chunks; chunk0 += kTabCap) {

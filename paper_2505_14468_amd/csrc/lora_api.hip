@@ -366,6 +366,8 @@ int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
     if (d->K <= 0 || d->N <= 0 || (d->K & 7) != 0) return LORA_ERR_SHAPE;
     if (d->ldx < d->K || d->ldw < d->K || d->ldy < d->N) return LORA_ERR_SHAPE;
     if (d->ldx % ce || d->ldw % ce || d->ldy % ce) return LORA_ERR_ALIGNMENT;
+    // the kernels address X and W0 with 32-bit offsets in 16-byte units: 64 GiB each
+    if (plan->T * (d->ldx / ce) >= (1ll << 32) || (int64_t)d->N * (d->ldw / ce) >= (1ll << 32)) return LORA_ERR_SHAPE;
     if (plan->T > 0) {
         if (!d->X || !d->W0 || !d->Y) return LORA_ERR_INVALID_ARG;
         if (((uintptr_t)d->X | (uintptr_t)d->W0 | (uintptr_t)d->Y) & 15u) return LORA_ERR_ALIGNMENT;
