@@ -125,9 +125,9 @@ typedef struct lora_linear_desc {
     int32_t N;              /* d_out: > 0                                                   */
     int32_t flags;          /* must be 0                                                    */
     const void *X;          /* device [T, ldx]                                              */
-    int64_t ldx;            /* >= K, multiple of 8 (bf16) or 4 (fp32); T * ldx below 64 GiB */
+    int64_t ldx;            /* >= K, multiple of 8 (bf16) or 4 (fp32); X smaller than 4 GiB*/
     const void *W0;         /* device [N, ldw], const, externally owned                     */
-    int64_t ldw;            /* >= K, multiple of 8 (bf16) or 4 (fp32); N * ldw below 64 GiB */
+    int64_t ldw;            /* >= K, multiple of 8 (bf16) or 4 (fp32); < 4 Mi elements     */
     void *Y;                /* device [T, ldy]; must not alias X, W0 or the adapters        */
     int64_t ldy;            /* >= N, multiple of 8 (bf16) or 4 (fp32)                       */
     const lora_adapter_table_t *tbl; /* host pointer; NULL = backbone product only         */

@@ -52,6 +52,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     constexpr int XL = BM * 8 / NT, WL = BN * 8 / NT;  // 16-byte loads per thread per stage
     constexpr int RPP = NT / 8;                        // rows covered per load pass
     static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
+    // The largest tile on 4 waves (512 registers each) runs the base product as a deeper software pipeline, with
+    // two register sets of staged operands; on 8 waves the second set does not fit.
+    constexpr bool DEEP = XL % 4 == 0 && WL % 4 == 0 && BM * BN >= 256 * 256 && WM * WN <= 4;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     chunk_t *sW = reinterpret_cast<chunk_t *>(smem);                 // [2][BN*8]
@@ -84,18 +87,21 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 
     // ---- per-thread load slots ------------------------------------------------------------
     const int lrow = tid >> 3, lc = tid & 7;
-    // 32-bit offsets in 16-byte chunks (row start + this thread's chunk of a stage): half the registers of
-    // pointers, and one 64-bit shift-add per load (rows are 16-byte aligned, so ldx and ldw are whole chunks)
-    const chunk_t *Xc = static_cast<const chunk_t *>(p.X), *Wc = static_cast<const chunk_t *>(p.W);
+    // 32-bit byte offsets (row start + this thread's chunk of a stage) against a scalar base that moves along K:
+    // a load then needs no vector address arithmetic at all, and one register of address.  X is
+    // addressed from its start (the host checks that it is smaller than 4 GiB), W0 from the tile's first row.
+    const BufferDesc Xd = make_buffer_desc(p.X);
+    const BufferDesc Wd = make_buffer_desc(static_cast<const char *>(p.W) + (int64_t)n0 * p.ldw * (int64_t)sizeof(E));
     unsigned xoff[XL], woff[WL];
     int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
     for (int i = 0; i < XL; ++i) {  // rows past T / N are clamped: they only feed outputs that are never stored
         xrowi[i] = p.plan.perm[min(m0 + lrow + i * RPP, p.T - 1)];
-        xoff[i] = (unsigned)((int64_t)xrowi[i] * (p.ldx / CE) + lc);
+        xoff[i] = (unsigned)(((int64_t)xrowi[i] * p.ldx + lc * CE) * (int64_t)sizeof(E));
     }
 #pragma unroll
-    for (int i = 0; i < WL; ++i) woff[i] = (unsigned)((int64_t)min(n0 + lrow + i * RPP, p.N - 1) * (p.ldw / CE) + lc);
+    for (int i = 0; i < WL; ++i)
+        woff[i] = (unsigned)(((int64_t)(min(n0 + lrow + i * RPP, p.N - 1) - n0) * p.ldw + lc * CE) * (int64_t)sizeof(E));
 
     // ---- extension range of this M-tile -----------------------------------------------------
     int pbeg = 0, pend = 0;
@@ -149,16 +155,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     auto load_base = [&](int kt, bool partial) {
         if (!partial) {
 #pragma unroll
-            for (int i = 0; i < XL; ++i) xr[i] = load_chunk(Xc + ((size_t)xoff[i] + kt * 8));
+            for (int i = 0; i < XL; ++i) xr[i] = buffer_load_chunk(Xd, xoff[i], kt * 128);
 #pragma unroll
-            for (int i = 0; i < WL; ++i) wr[i] = load_chunk(Wc + ((size_t)woff[i] + kt * 8));
+            for (int i = 0; i < WL; ++i) wr[i] = buffer_load_chunk(Wd, woff[i], kt * 128);
         } else {
             const bool kv = (kt * 8 + lc) * CE < p.K;
-            const int off = kv ? kt * 8 : -lc;
+            // dropped loads read the start of the row (all of it in the per-lane offset: the scalar one must be uniform)
+            const unsigned adj = kv ? (unsigned)kt * 128u : 0u - (unsigned)lc * 16u;
 #pragma unroll
-            for (int i = 0; i < XL; ++i) xr[i] = keep_if(kv, load_chunk(Xc + ((int64_t)xoff[i] + off)));
+            for (int i = 0; i < XL; ++i) xr[i] = keep_if(kv, buffer_load_chunk(Xd, xoff[i] + adj, 0));
 #pragma unroll
-            for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, load_chunk(Wc + ((int64_t)woff[i] + off)));
+            for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, buffer_load_chunk(Wd, woff[i] + adj, 0));
         }
     };
     auto load_ext = [&](int se) {  // se = stage inside the current table batch
@@ -279,7 +286,87 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     };
     // (stage 1 was requested by every wave before the loop)
     int kt = 0;
-    if (KT_full > 2) {
+    if constexpr (DEEP) {
+        // Two register sets of staged operands: while stage kt is multiplied, the loads of stage kt + 2 go out
+        // into one set and the other set, which holds stage kt + 1, is written to the LDS buffer that stage
+        // kt - 1 was read from -- a quarter of each per k-step, so neither the address unit nor LDS sees a
+        // burst and a load has a whole stage to arrive.  The barrier waits for LDS traffic only, never for
+        // the loads in flight across it.
+        chunk_t xr2[XL], wr2[WL];
+        constexpr int XQ = XL / 4, WQ = WL / 4;
+        auto gload_q = [&](chunk_t (&xs)[XL], chunk_t (&ws)[WL], int kq, int q, bool partial) {
+            if (!partial) {
+#pragma unroll
+                for (int i = q * XQ; i < (q + 1) * XQ; ++i) xs[i] = buffer_load_chunk(Xd, xoff[i], kq * 128);
+#pragma unroll
+                for (int i = q * WQ; i < (q + 1) * WQ; ++i) ws[i] = buffer_load_chunk(Wd, woff[i], kq * 128);
+            } else {
+                const bool kv = (kq * 8 + lc) * CE < p.K;
+                const unsigned adj = kv ? (unsigned)kq * 128u : 0u - (unsigned)lc * 16u;
+#pragma unroll
+                for (int i = q * XQ; i < (q + 1) * XQ; ++i) xs[i] = keep_if(kv, buffer_load_chunk(Xd, xoff[i] + adj, 0));
+#pragma unroll
+                for (int i = q * WQ; i < (q + 1) * WQ; ++i) ws[i] = keep_if(kv, buffer_load_chunk(Wd, woff[i] + adj, 0));
+            }
+        };
+        auto lstore_q = [&](const chunk_t (&xs)[XL], const chunk_t (&ws)[WL], int buf, int q) {
+#pragma unroll
+            for (int i = q * XQ; i < (q + 1) * XQ; ++i) sX[buf * BM * 8 + swz(lrow + i * RPP, lc)] = xs[i];
+#pragma unroll
+            for (int i = q * WQ; i < (q + 1) * WQ; ++i) sW[buf * BN * 8 + swz(lrow + i * RPP, lc)] = ws[i];
+        };
+        auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+        // stage kt: set (lx, lw) receives stage kt + 2, set (sx, sw) holds stage kt + 1
+        auto stage_deep = [&](int kq, chunk_t (&lx)[XL], chunk_t (&lw)[WL], chunk_t (&sx)[XL], chunk_t (&sw)[WL], bool more,
+                              bool load2, bool partial2) {
+            const int buf = kq & 1;
+#pragma unroll
+            for (int kk = 0; kk < 3; ++kk) {
+                const int cur = kk & 1;
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) xf[cur ^ 1][tb] = read_x(buf, kk + 1, tb);
+#pragma unroll
+                for (int nb = 0; nb < NBN; ++nb) {
+#pragma unroll
+                    for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[cur][tb]);
+                    wf[nb] = read_w(buf, kk + 1, nb);
+                }
+                if (load2) gload_q(lx, lw, kq + 2, kk, partial2);
+                if (more) lstore_q(sx, sw, buf ^ 1, kk);
+                __builtin_amdgcn_sched_barrier(0);  // nothing moves between k-steps: register lifetimes stay as written
+            }
+            constexpr int H = NBN > 1 ? NBN / 2 : 1;
+#pragma unroll
+            for (int nb = 0; nb < H; ++nb)
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
+            if (load2) gload_q(lx, lw, kq + 2, 3, partial2);
+            if (more) lstore_q(sx, sw, buf ^ 1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) {
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) xf[0][tb] = read_x(buf ^ 1, 0, tb);
+#pragma unroll
+                for (int nb = 0; nb < H; ++nb) wf[nb] = read_w(buf ^ 1, 0, nb);
+            }
+#pragma unroll
+            for (int nb = H; nb < NBN; ++nb) {
+#pragma unroll
+                for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
+                if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
+            }
+        };
+        for (; kt + 3 < KT_full; kt += 2) {  // the steady state, two stages per trip: the sets swap roles
+            stage_deep(kt, xr2, wr2, xr, wr, true, true, false);  // (stage 1 came into the first set before the loop)
+            stage_deep(kt + 1, xr, wr, xr2, wr2, true, true, false);
+        }
+        for (; kt < KT; kt += 2) {
+            stage_deep(kt, xr2, wr2, xr, wr, kt + 1 < KT, kt + 2 < KT, kt + 2 >= KT_full);
+            if (kt + 1 < KT) stage_deep(kt + 1, xr, wr, xr2, wr2, kt + 2 < KT, kt + 3 < KT, kt + 3 >= KT_full);
+        }
+    } else if (KT_full > 2) {
         stage(0, true, true, false, false, false);
         for (kt = 1; kt + 2 < KT_full; ++kt) stage(kt, true, true, false, true, false);  // the steady state
     }

@@ -305,14 +305,14 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         return c;
     }
     // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency (measured per
-    // round at K = 4096: 256x256 124 us, 256x128 83 us, 128x128 38 us).
+    // round at K = 4096: 256x256 on 4 waves 104 us, 256x128 71 us, 128x128 36 us).
     struct Cand {
         int variant, bm, bn;
         double eff;
     };
-    const Cand cands[] = {{kGemmTile256x256, 256, 256, 1.00},
-                          {kGemmTile256x128, 256, 128, 0.75},
-                          {kGemmTile128x128, 128, 128, 0.82},
+    const Cand cands[] = {{kGemmTile256x256w4, 256, 256, 1.00},
+                          {kGemmTile256x128, 256, 128, 0.70},
+                          {kGemmTile128x128, 128, 128, 0.74},
                           {kGemmTile64x64, 64, 64, 0.45}};
     double best = 0.0;
     bool have = false;
@@ -366,8 +366,9 @@ int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
     if (d->K <= 0 || d->N <= 0 || (d->K & 7) != 0) return LORA_ERR_SHAPE;
     if (d->ldx < d->K || d->ldw < d->K || d->ldy < d->N) return LORA_ERR_SHAPE;
     if (d->ldx % ce || d->ldw % ce || d->ldy % ce) return LORA_ERR_ALIGNMENT;
-    // the kernels address X and W0 with 32-bit offsets in 16-byte units: 64 GiB each
-    if (plan->T * (d->ldx / ce) >= (1ll << 32) || (int64_t)d->N * (d->ldw / ce) >= (1ll << 32)) return LORA_ERR_SHAPE;
+    // the tiled kernels address X with 32-bit byte offsets from its start, W0 from a tile's first row
+    const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
+    if (plan->T * d->ldx * es >= (1ll << 32) || 256 * d->ldw * es >= (1ll << 32)) return LORA_ERR_SHAPE;
     if (plan->T > 0) {
         if (!d->X || !d->W0 || !d->Y) return LORA_ERR_INVALID_ARG;
         if (((uintptr_t)d->X | (uintptr_t)d->W0 | (uintptr_t)d->Y) & 15u) return LORA_ERR_ALIGNMENT;
