@@ -52,9 +52,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     constexpr int XL = BM * 8 / NT, WL = BN * 8 / NT;  // 16-byte loads per thread per stage
     constexpr int RPP = NT / 8;                        // rows covered per load pass
     static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
-    // The largest tile on 4 waves (512 registers each) runs the base product as a deeper software pipeline, with
-    // two register sets of staged operands; on 8 waves the second set does not fit.
-    constexpr bool DEEP = XL % 4 == 0 && WL % 4 == 0 && BM * BN >= 256 * 256 && WM * WN <= 4;
+    // On 4 waves (up to 512 registers each) the base product runs as a deeper software pipeline, with two
+    // register sets of staged operands; on 8 waves the second set does not fit beside a 256x256 tile.
+    constexpr bool DEEP = XL % 4 == 0 && WL % 4 == 0 && WM * WN <= 4;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     chunk_t *sW = reinterpret_cast<chunk_t *>(smem);                 // [2][BN*8]
@@ -434,7 +434,7 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
         case kGemmTile128x128:
             return launch_tile<E, 128, 128, 2, 2>(a, stream, timer);
         case kGemmTile256x128:
-            return launch_tile<E, 256, 128, 4, 2>(a, stream, timer);
+            return launch_tile<E, 256, 128, 2, 2>(a, stream, timer);
         case kGemmTile256x256:
             return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
         case kGemmTile256x256w4:

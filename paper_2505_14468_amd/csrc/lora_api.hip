@@ -305,14 +305,14 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         return c;
     }
     // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency (measured per
-    // round at K = 4096: 256x256 on 4 waves 104 us, 256x128 71 us, 128x128 36 us).
+    // round at K = 4096: 256x256 104 us, 256x128 64 us, 128x128 34 us, all on 4 waves).
     struct Cand {
         int variant, bm, bn;
         double eff;
     };
     const Cand cands[] = {{kGemmTile256x256w4, 256, 256, 1.00},
-                          {kGemmTile256x128, 256, 128, 0.70},
-                          {kGemmTile128x128, 128, 128, 0.74},
+                          {kGemmTile256x128, 256, 128, 0.81},
+                          {kGemmTile128x128, 128, 128, 0.77},
                           {kGemmTile64x64, 64, 64, 0.45}};
     double best = 0.0;
     bool have = false;
