@@ -81,7 +81,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     const int wn0 = (wave % WN) * WTN, wm0 = (wave / WN) * WTM;
     const int l31 = lane & 31, lh = lane >> 5;
 
-    const E *X = static_cast<const E *>(p.X);
     const E *W = static_cast<const E *>(p.W);
     const E *V = static_cast<const E *>(p.V);
 
@@ -168,6 +167,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             for (int i = 0; i < WL; ++i) wr[i] = keep_if(kv, buffer_load_chunk(Wd, woff[i] + adj, 0));
         }
     };
+    // Extension loads are requested unmasked (from a clamped address where a row or chunk column does not
+    // take part); the mask is applied when the stage is written to LDS.  Masking the loaded value at once would
+    // make every load wait for its own data right behind its issue: no two loads in flight.
     auto load_ext = [&](int se) {  // se = stage inside the current table batch
         const int idx = se * 8 + lc;
         const E *bp = static_cast<const E *>(tab->ptr[idx]);
@@ -176,15 +178,27 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         for (int i = 0; i < XL; ++i) {
             const int row = lrow + i * RPP;
             const bool ok = row >= lo && row < hi;  // rows of other adapters contribute nothing
-            xr[i] = keep_if(ok, load_chunk(V + (ok ? (int64_t)xrowi[i] * p.r_max + j : 0)));
+            xr[i] = load_chunk(V + (ok ? (int64_t)xrowi[i] * p.r_max + j : 0));
         }
         const bool wok = bp != nullptr;
         const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
 #pragma unroll
         for (int i = 0; i < WL; ++i) {
             const int n = min(n0 + lrow + i * RPP, p.N - 1);
-            wr[i] = keep_if(wok, load_chunk(bsrc + (wok ? (int64_t)n * r : 0)));
+            wr[i] = load_chunk(bsrc + (wok ? (int64_t)n * r : 0));
         }
+    };
+    auto store_stage_ext = [&](int buf, int se) {
+        const int idx = se * 8 + lc;
+        const bool wok = tab->ptr[idx] != nullptr;
+        const int lo = tab->lo[idx], hi = tab->hi[idx];
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int row = lrow + i * RPP;
+            sX[buf * BM * 8 + swz(row, lc)] = keep_if(row >= lo && row < hi, xr[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < WL; ++i) sW[buf * BN * 8 + swz(lrow + i * RPP, lc)] = keep_if(wok, wr[i]);
     };
     auto store_stage = [&](int buf) {
 #pragma unroll
@@ -381,13 +395,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         }
         const int nst = (min(ext_chunks - chunk0, kTabCap) + 7) >> 3;
         load_ext(0);
-        store_stage(0);
+        store_stage_ext(0, 0);
         __syncthreads();
         for (int se = 0; se < nst; ++se) {
             const bool more = se + 1 < nst;
             if (more) load_ext(se + 1);
             compute(se & 1, se);
-            if (more) store_stage((se + 1) & 1);
+            if (more) store_stage_ext((se + 1) & 1, se + 1);
             __syncthreads();
         }
     }
