@@ -408,16 +408,39 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 
     // ---- single store of Y: acc[nb][tb][g*4+e] = D[n = nb*32 + g*8 + lh*4 + e][t = tb*32 + l31] -------
     E *Y = static_cast<E *>(p.Y);
+    if (p.D == nullptr) {
 #pragma unroll
-    for (int tb = 0; tb < NBT; ++tb) {
-        const int t = m0 + wm0 + tb * 32 + l31;
-        const bool row_ok = t < p.T;
-        const int row = p.plan.perm[min(t, p.T - 1)];
-        E *yrow = Y + (int64_t)row * p.ldy;
-        // the adapter term, when a kernel of its own has computed it (rows with an adapter only)
-        const float *drow = (p.D != nullptr && p.plan.row_adapter[row] >= 0) ? p.D + (int64_t)row * p.ldd : nullptr;
+        for (int tb = 0; tb < NBT; ++tb) {
+            const int t = m0 + wm0 + tb * 32 + l31;
+            E *yrow = Y + (int64_t)p.plan.perm[min(t, p.T - 1)] * p.ldy;
 #pragma unroll
-        for (int nb = 0; nb < NBN; ++nb) store_acc_tile<E>(acc[nb][tb], yrow, drow, n0 + wn0 + nb * 32, lh, p.N, row_ok);
+            for (int nb = 0; nb < NBN; ++nb) store_acc_tile<E>(acc[nb][tb], yrow, nullptr, n0 + wn0 + nb * 32, lh, p.N, t < p.T);
+        }
+    } else {
+        // The adapter term, when a kernel of its own has computed it (rows with an adapter only), is read one
+        // row block ahead of the stores it is added into: written inside the store loop, every piece of it
+        // would be a round trip to memory of its own (the compiler does not move a load above a store).
+        float term[2][NBN][16];
+        auto row_of = [&](int tb) { return p.plan.perm[min(m0 + wm0 + tb * 32 + l31, p.T - 1)]; };
+        auto fetch = [&](int tb, int row, float (&d)[NBN][16]) {
+            const float *drow = p.plan.row_adapter[row] >= 0 ? p.D + (int64_t)row * p.ldd : nullptr;
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb) load_term_tile(drow, p.D, n0 + wn0 + nb * 32, lh, (int)p.ldd, d[nb]);
+        };
+        int row = row_of(0);
+        fetch(0, row, term[0]);
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) {
+            const int t = m0 + wm0 + tb * 32 + l31;
+            E *yrow = Y + (int64_t)row * p.ldy;
+            if (tb + 1 < NBT) {
+                row = row_of(tb + 1);
+                fetch(tb + 1, row, term[(tb + 1) & 1]);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb)
+                store_acc_tile_with<E>(acc[nb][tb], term[tb & 1][nb], yrow, n0 + wn0 + nb * 32, lh, p.N, t < p.T);
+        }
     }
 }
 

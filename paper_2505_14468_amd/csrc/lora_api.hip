@@ -350,7 +350,7 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     w.xpack_bytes = (dtype == LORA_DTYPE_BF16 && T > 0 && T <= kSkinnyMaxRows) ? xpack_bytes_for(T, K) : 0;
     off = align_up(off + w.xpack_bytes, 256);
     w.total = off < 256 ? 256 : off;
-    w.ldd = align_up((size_t)N, 4);
+    w.ldd = align_up((size_t)N, 8);  // (the GEMM's epilogue reads whole 8-column pieces of a row)
     w.d_off = w.total;
     w.d_bytes = T > kSkinnyMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
     w.total_preferred = align_up(w.d_off + w.d_bytes, 256);
