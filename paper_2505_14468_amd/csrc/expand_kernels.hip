@@ -147,6 +147,91 @@ __device__ __forceinline__ void expand_unit(const ExpandArgs &p, const E *Ba, in
     }
 }
 
+// The common shapes -- a whole group of 1024 columns, rank <= 128 (bf16) -- with every index a compile-time constant:
+// S MFMA steps per 16-column block (2: at most 8 chunks of rank, 4: at most 16), the B_a loads of RING blocks in flight
+// per wave (all 8: everything is requested before the first MFMA), the results of all 8 blocks kept in
+// registers and stored after the last load has been consumed.  Loads and stores are counted by one in-order
+// counter, so a store issued between loads makes the next wait for a load wait for the store's acknowledgement
+// from memory as well; and no load sits behind a branch, so that the compiler can count the loads in flight.
+template <typename E, int TB, int S, int RING>
+__device__ __forceinline__ void expand_unit_whole(const ExpandArgs &p, const E *Ba, int r, int slot0, int nrows, int nwg0,
+                                                  unsigned char *smem) {
+    constexpr int CE = Elem<E>::CE;
+    constexpr int NBLK = kExBlocksPerWave;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int rchunks = r / CE;
+    const int vstride = rchunks + kExPad;
+    chunk_t *vs = reinterpret_cast<chunk_t *>(smem);
+    const E *V = static_cast<const E *>(p.V);
+
+    // ---- the unit's rows of V: two chunks per thread at most (64 rows x 16 chunks), requested first ----
+    chunk_t vreg[2];
+    int vdst[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int e = tid + u * (kExWaves * 64);
+        const bool ok = e < nrows * rchunks;
+        const int t = ok ? e / rchunks : 0, c = ok ? e - t * rchunks : 0;
+        vdst[u] = ok ? t * vstride + c : -1;
+        vreg[u] = load_chunk(V + (int64_t)p.plan.perm[slot0 + t] * p.r_max + (int64_t)c * CE);
+    }
+    // ---- B_a: lane -> (column block_n0 + li, chunk of the step); chunks past the rank are read from chunk 0
+    //      and meet a zeroed V operand ----
+    auto block_n0 = [&](int b) { return nwg0 + (2 * wave + (b & 1) + 2 * kExWaves * (b >> 1)) * 16; };
+    int kc[S];
+    bool kok[S];
+#pragma unroll
+    for (int st = 0; st < S; ++st) {
+        const int c = (st >> 1) * 8 + 2 * lg + (st & 1);
+        kok[st] = c < rchunks;
+        kc[st] = kok[st] ? c : 0;
+    }
+    auto load_block = [&](int b, chunk_t (&wf)[S]) {
+        const E *brow = Ba + (int64_t)(block_n0(b) + li) * r;
+#pragma unroll
+        for (int st = 0; st < S; ++st) wf[st] = load_chunk(brow + kc[st] * CE);
+    };
+    chunk_t ring[RING][S];
+#pragma unroll
+    for (int i = 0; i < RING; ++i) load_block(i, ring[i]);
+    LORA_TS(p.trace, 2);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (vdst[u] >= 0) vs[vdst[u]] = vreg[u];
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");  // LDS only: the B_a loads stay in flight
+    LORA_TS(p.trace, 3);  // V staged
+
+    // V operands of this lane: row tb * 16 + li (clamped), the step's chunk; the same for every block
+    chunk_t vop[TB][S];
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+        for (int st = 0; st < S; ++st) vop[tb][st] = keep_if(kok[st], vs[min(tb * 16 + li, nrows - 1) * vstride + kc[st]]);
+
+    f32x4_t acc[NBLK][TB];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb) acc[b][tb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < S; ++st)
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) Elem<E>::mma16(acc[b][tb], ring[b % RING][st], vop[tb][st]);
+        if (b + RING < NBLK) load_block(b + RING, ring[b % RING]);
+    }
+    LORA_TS(p.trace, 4);
+    // acc[b][tb][e] = D[n = block_n0(b) + lg*4 + e][t = tb*16 + li]: a lane stores 4 consecutive columns of one row
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+        const int t = tb * 16 + li;
+        if (t >= nrows) continue;
+        float *drow = p.D + (int64_t)p.plan.perm[slot0 + t] * p.ldd;
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) store4(drow + block_n0(b) + lg * 4, acc[b][tb][0], acc[b][tb][1], acc[b][tb][2], acc[b][tb][3]);
+    }
+}
+
 template <typename E>
 __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -170,10 +255,24 @@ __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
         }
         return;
     }
-    if (nrows <= 16)
+    const int rchunks = r / Elem<E>::CE;
+    if ((cg + 1) * kExCols <= p.N && rchunks <= 16) {  // a whole column group, at most 4 MFMA steps along the rank
+        if (nrows <= 16) {
+            if (rchunks <= 8)
+                expand_unit_whole<E, 1, 2, 8>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+            else
+                expand_unit_whole<E, 1, 4, 8>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+        } else {
+            if (rchunks <= 8)
+                expand_unit_whole<E, 4, 2, 8>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+            else
+                expand_unit_whole<E, 4, 4, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+        }
+    } else if (nrows <= 16) {
         expand_unit<E, 1>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
-    else
+    } else {
         expand_unit<E, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+    }
     LORA_TS(p.trace, 5);
 }
 
