@@ -49,6 +49,24 @@ def test_tile_kernels_ragged_multi_tile(variant, dtype):
     reset_options()
 
 
+@pytest.mark.parametrize("variant", ["tile_128x128", "tile_256x128", "tile_256x256w4", "tile_256x256"])
+def test_tile_kernels_short_contraction_axes(variant):
+    """One to five stages of the contraction axis, with and without a partial last stage: the prologue and
+    the last stages of the software-pipelined loops (two stages of loads ahead) for every stage count."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
+    ids, L = _mixed_batch(19, R=9, n_ad=3, max_len=40, zero_len=False)
+    ctx().set_option("gemm_variant", VARIANTS[variant])
+    # (a small adapter term: with a handful of products per output the sum is heavy-tailed, and a bf16 output
+    # of 8 sigma is off by more than 2e-2 * RMS from its one rounding alone)
+    for dtype, Ks in (("bf16", (24, 64, 72, 128, 136, 192, 200, 256, 264, 320)), ("f32", (8, 32, 40, 64, 72, 96, 104, 160))):
+        for K in Ks:
+            wl = make_custom(seed=600 + K, dtype=dtype, K=K, N=72, ranks=(8, 16, 24), scales=(1.0, 0.5, 2.0),
+                             req_adapter=ids, req_ntok=L, sigma_b=0.005, name=f"shortk_{variant}_{dtype}_{K}")
+            e = check_against_oracle(wl, gpu_linear(wl))
+    print(f"{variant}: last err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_separate_expand_kernel_ragged(dtype):
     """The adapter term added by the expand kernel of its own (many small segments) instead of inside the
