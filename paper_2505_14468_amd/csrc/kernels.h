@@ -122,6 +122,7 @@ struct ShrinkArgs {
     const float *scale;    // device table
     void *V;               // [T, r_max] of E
     int32_t r_max;
+    int32_t n_adapters;    // entries of the A / scale tables
     int32_t rank_block;    // ranks per workgroup: 8 or 16 (few units: spread them over the chip) or kShrinkRanks
     int32_t rank_groups;   // ceil(r_max / rank_block)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)

@@ -424,6 +424,7 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.scale = ad ? d->tbl->scale : nullptr;
     a.V = ws + w.v_off;
     a.r_max = plan->r_max;
+    a.n_adapters = ad ? d->tbl->n_adapters : 0;
     // units <= sum over segments of ceil(rows/64) <= T/64 + number of adapter segments
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;

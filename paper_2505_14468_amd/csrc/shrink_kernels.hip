@@ -319,6 +319,13 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     const int bid = blockIdx.x - p.pack_wgs;
     const int jg = bid % p.rank_groups;
     const int unit = bid / p.rank_groups;
+    // Guessed ahead, in the same round trip as the record: lane i reads entry i of the adapter tables and of the
+    // row map.  A decode batch (at most 64 rows, a pool of at most 64 adapters) finds everything it needs there
+    // and skips the second round trip.
+    const int lane = tid & 63;
+    const void *a_guess = lane < p.n_adapters ? p.A[lane] : nullptr;
+    const float s_guess = lane < p.n_adapters ? p.scale[lane] : 0.f;
+    const int perm_guess = lane < p.T ? p.plan.perm[lane] : 0;
     const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
     const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
     if (status != 0 || unit >= n_units) return;
@@ -332,15 +339,32 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     // Rows past the end of the unit are clamped to its last one: they only feed accumulator
     // entries that are never stored.
     int prow[4][2];  // lane -> row lane / 8 + 8 i of each 16-row block (the operand loads' mapping)
+    const bool rows_guessed = slot0 + nrows <= 64;  // (uniform)
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int row = ((tid & 63) >> 3) + 8 * i;
-        prow[0][i] = p.plan.perm[slot0 + min(row, nrows - 1)];
+        const int row = (lane >> 3) + 8 * i;
+        if (rows_guessed) {
+            prow[0][i] = __shfl(perm_guess, slot0 + min(row, nrows - 1));
 #pragma unroll
-        for (int tb = 1; tb < 4; ++tb) prow[tb][i] = nrows > 16 ? p.plan.perm[slot0 + min(tb * 16 + row, nrows - 1)] : prow[0][i];
+            for (int tb = 1; tb < 4; ++tb) prow[tb][i] = nrows > 16 ? __shfl(perm_guess, slot0 + min(tb * 16 + row, nrows - 1)) : prow[0][i];
+        } else {
+            prow[0][i] = p.plan.perm[slot0 + min(row, nrows - 1)];
+#pragma unroll
+            for (int tb = 1; tb < 4; ++tb) prow[tb][i] = nrows > 16 ? p.plan.perm[slot0 + min(tb * 16 + row, nrows - 1)] : prow[0][i];
+        }
     }
-    const E *Aa = static_cast<const E *>(p.A[a]);
-    const float scale = p.scale[a];
+    const E *Aa;
+    float scale;
+    if (a < 64) {  // (uniform: the record is the same for every lane)
+        const int as = __builtin_amdgcn_readfirstlane(a);
+        const unsigned long long bits = (unsigned long long)a_guess;
+        const unsigned lo = __builtin_amdgcn_readlane((unsigned)bits, as), hi = __builtin_amdgcn_readlane((unsigned)(bits >> 32), as);
+        Aa = reinterpret_cast<const E *>(((unsigned long long)hi << 32) | lo);
+        scale = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(s_guess), as));
+    } else {
+        Aa = static_cast<const E *>(p.A[a]);
+        scale = p.scale[a];
+    }
 
     if (Aa == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
         E *V = static_cast<E *>(p.V);
