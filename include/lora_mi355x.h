@@ -147,7 +147,8 @@ int lora_ctx_destroy(lora_ctx *ctx);
  * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
  * decode-sized plan kernel, "expand_split" = 0 / 1: adapter term always
  * computed inside the GEMM / by the separate expand kernel whenever the
- * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64);
+ * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64,
+ * "shrink_row_split" = 1 / 4);
  * value < 0 restores the built-in heuristic.  Results never depend on them
  * beyond fp32 summation order.  Errors: INVALID_ARG for an unknown name or a
  * value the option does not take. */

@@ -125,6 +125,7 @@ struct ShrinkArgs {
     int32_t n_adapters;    // entries of the A / scale tables
     int32_t rank_block;    // ranks per workgroup: 8 or 16 (few units: spread them over the chip) or kShrinkRanks
     int32_t rank_groups;   // ceil(r_max / rank_block)
+    int32_t row_split;     // 1, or 4: a unit's rows are dealt in blocks of 16 to 4 workgroups (few units, decode-sized)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
     int32_t xlds_bytes;    // LDS for staging the X rows of small units: 0 or 64 KiB (decode-sized batches)
     // Fragment-major copy of X for the decode-sized GEMM (null = not needed): for MFMA step s

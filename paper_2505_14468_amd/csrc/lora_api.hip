@@ -57,6 +57,7 @@ struct lora_ctx {
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
     int opt_shrink_rank_block = -1;
+    int opt_shrink_row_split = -1;
     int opt_plan_variant = -1;
     int opt_expand_split = -1;
     // profiling mode: event pairs recorded tightly around each kernel
@@ -443,6 +444,10 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     if (ctx->opt_shrink_rank_block > 0) rank_block = ctx->opt_shrink_rank_block;
     a.rank_block = rank_block;
     a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
+    // Few units of many rows in a small batch (one function's own decode batch): blocks of 16 rows go to
+    // workgroups of their own, as long as that still leaves CUs to spare.
+    a.row_split = ad && small_x && plan->T > 16 && (int64_t)a.max_units * a.rank_groups * 4 <= (int64_t)ctx->num_cu ? 4 : 1;
+    if (ctx->opt_shrink_row_split > 0) a.row_split = ctx->opt_shrink_row_split == 4 ? 4 : 1;
     a.xlds_bytes = ad && plan->T <= 256 ? 64 * 1024 : 0;  // small batches: units of a few rows, one workgroup per CU is plenty
     a.xpack = pack ? ws + w.xpack_off : nullptr;
     a.pack_tblk = pack ? skinny_tblk(plan->T) : 0;
@@ -590,6 +595,9 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     } else if (!strcmp(name, "plan_variant")) {
         if (value > 1) return LORA_ERR_INVALID_ARG;
         ctx->opt_plan_variant = value;
+    } else if (!strcmp(name, "shrink_row_split")) {
+        if (value != -1 && value != 1 && value != 4) return LORA_ERR_INVALID_ARG;
+        ctx->opt_shrink_row_split = value;
     } else if (!strcmp(name, "shrink_rank_block")) {
         if (value > 0 && value != 8 && value != 16 && value != 32 && value != 64) return LORA_ERR_INVALID_ARG;
         ctx->opt_shrink_rank_block = value;
