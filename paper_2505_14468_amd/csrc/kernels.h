@@ -36,6 +36,7 @@ struct PlanBuildArgs {
     int32_t *unit_rec;     // [unit_cap*4] shrink work list: adapter, rank, first slot, rows
     int32_t *ext_rec;      // [ext_cap*4]
     int32_t *scalars;      // [8]
+    long long *trace = nullptr;  // phase stamps (trace builds only)
 };
 
 // Optional pair of events recorded tightly around one kernel (profiling mode): the elapsed time

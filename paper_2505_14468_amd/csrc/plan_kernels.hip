@@ -349,6 +349,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
     __shared__ unsigned long long s_sum;
     const int tid = threadIdx.x;
     const int R = p.n_req, n_ad = p.n_adapters;
+    LORA_TS(p.trace, 0);
 
     for (int i = tid; i < R + 64; i += kPlanThreads) {
         const int a = i < R ? p.req_adapter[i] : -3;
@@ -389,6 +390,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         return;
     }
 
+    LORA_TS(p.trace, 1);  // requests read, validated, histogram
     // 2. first row of every request
     {
         int carry = 0;
@@ -409,6 +411,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         }
     }
 
+    LORA_TS(p.trace, 2);  // token offsets
     // 3. segments
     int c_seg = 0, c_row = 0, c_ext = 0, c_unit = 0;
     {
@@ -481,6 +484,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         p.seg_unit[s] = s_sun[s];
     }
 
+    LORA_TS(p.trace, 3);  // segments
     // 4. stable destination of every request, 64 requests (one wave) at a time.
     //    4a, all waves, a chunk of 64 requests each: rows of earlier requests of the chunk with the same key,
     //        and whether a later request of the chunk has the key -- the other requests' (key, rows) are
@@ -507,6 +511,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         }
     }
     __syncthreads();
+    LORA_TS(p.trace, 4);  // ranking inside chunks
     if (tid < 64) {
         volatile int *cur = s_cur;
         const int lane = tid;
@@ -529,6 +534,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
     }
     __syncthreads();
 
+    LORA_TS(p.trace, 5);  // chunk walk
     // 5. per-row scatter
     for (int t = tid; t < c_row; t += kPlanThreads) {
         int lo = 0, hi = R;
@@ -545,6 +551,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         p.row_seg[slot] = s_kseg[a < 0 ? n_ad : a];
         p.row_adapter[t] = a;
     }
+    LORA_TS(p.trace, 6);  // row scatter
     // 6. one record per 8 ranks of the extension axis, one per shrink work unit
     for (int q = tid; q < (c_ext >> 3); q += kPlanThreads) {
         const int pel = q << 3;
@@ -580,6 +587,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
     }
+    LORA_TS(p.trace, 7);
 }
 
 // Decode-sized batches (at most 64 requests, any number of adapter slots): one lane per request.
@@ -832,8 +840,17 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
 hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, int variant, hipStream_t stream, const KernelTimer *timers) {
     if (fuse_fill && variant != 1 && a.n_req <= kTinyReq && a.T <= kSmallRows)
         return launch_kernel(plan_tiny_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
-    if (fuse_fill && a.n_req <= kSmallReq && a.n_adapters + 1 <= kSmallKeys && a.T <= kSmallRows)
+    if (fuse_fill && a.n_req <= kSmallReq && a.n_adapters + 1 <= kSmallKeys && a.T <= kSmallRows) {
+#ifdef LORA_TRACE
+        return trace_launch("plan_small", 1, [&](long long *buf) {
+            PlanBuildArgs b = a;
+            b.trace = buf;
+            return launch_kernel(plan_small_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, b);
+        });
+#else
         return launch_kernel(plan_small_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
+#endif
+    }
     hipError_t e = launch_kernel(plan_segments_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a,
                                  fuse_fill ? 1 : 0);
     if (e != hipSuccess) return e;
