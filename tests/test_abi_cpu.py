@@ -116,6 +116,8 @@ def test_lora_linear_validates_before_touching_the_gpu():
     assert run(ldy=68) == B.LORA_ERR_ALIGNMENT
     assert run(X=4096 + 2) == B.LORA_ERR_ALIGNMENT
     assert run(Y=4096) == B.LORA_ERR_INVALID_ARG  # Y aliases X
+    assert run(ldx=1 << 30) == B.LORA_ERR_SHAPE  # 4 rows x 2^30 elements: X would span more than the 4 GiB the kernels address
+    assert run(ldw=1 << 23) == B.LORA_ERR_SHAPE  # a 256-row tile of W0 would
     assert run(workspace=65536 + 64) == B.LORA_ERR_ALIGNMENT
     assert run(workspace_bytes=ws_bytes - 1) == B.LORA_ERR_WORKSPACE_TOO_SMALL
     bad = _fake_plan()
