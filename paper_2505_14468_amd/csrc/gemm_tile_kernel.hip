@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
     // On 4 waves (up to 512 registers each) the base product runs as a deeper software pipeline, with two
     // register sets of staged operands; on 8 waves the second set does not fit beside a 256x256 tile.
-    constexpr bool DEEP = XL % 4 == 0 && WL % 4 == 0 && WM * WN <= 4;
+    constexpr bool DEEP = XL + WL >= 4 && WM * WN <= 4;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     chunk_t *sW = reinterpret_cast<chunk_t *>(smem);                 // [2][BN*8]
@@ -307,27 +307,34 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         // burst and a load has a whole stage to arrive.  The barrier waits for LDS traffic only, never for
         // the loads in flight across it.
         chunk_t xr2[XL], wr2[WL];
-        constexpr int XQ = XL / 4, WQ = WL / 4;
+        // the XL + WL load slots of a stage (X slots first), dealt to the four k-steps as evenly as they divide
+        constexpr int NS = XL + WL;
         auto gload_q = [&](chunk_t (&xs)[XL], chunk_t (&ws)[WL], int kq, int q, bool partial) {
-            if (!partial) {
+            const bool kv = !partial || (kq * 8 + lc) * CE < p.K;
+            // (partial stage: all of the offset per lane -- the scalar one must be uniform; dropped loads read the row start)
+            const unsigned adj = !partial ? 0u : (kv ? (unsigned)kq * 128u : 0u - (unsigned)lc * 16u);
+            const int soff = partial ? 0 : kq * 128;
 #pragma unroll
-                for (int i = q * XQ; i < (q + 1) * XQ; ++i) xs[i] = buffer_load_chunk(Xd, xoff[i], kq * 128);
-#pragma unroll
-                for (int i = q * WQ; i < (q + 1) * WQ; ++i) ws[i] = buffer_load_chunk(Wd, woff[i], kq * 128);
-            } else {
-                const bool kv = (kq * 8 + lc) * CE < p.K;
-                const unsigned adj = kv ? (unsigned)kq * 128u : 0u - (unsigned)lc * 16u;
-#pragma unroll
-                for (int i = q * XQ; i < (q + 1) * XQ; ++i) xs[i] = keep_if(kv, buffer_load_chunk(Xd, xoff[i] + adj, 0));
-#pragma unroll
-                for (int i = q * WQ; i < (q + 1) * WQ; ++i) ws[i] = keep_if(kv, buffer_load_chunk(Wd, woff[i] + adj, 0));
+            for (int s = 0; s < NS; ++s) {
+                if (s * 4 / NS != q) continue;
+                if (s < XL) {
+                    xs[s < XL ? s : 0] = buffer_load_chunk(Xd, xoff[s < XL ? s : 0] + adj, soff);
+                    if (partial) xs[s < XL ? s : 0] = keep_if(kv, xs[s < XL ? s : 0]);
+                } else {
+                    ws[s >= XL ? s - XL : 0] = buffer_load_chunk(Wd, woff[s >= XL ? s - XL : 0] + adj, soff);
+                    if (partial) ws[s >= XL ? s - XL : 0] = keep_if(kv, ws[s >= XL ? s - XL : 0]);
+                }
             }
         };
         auto lstore_q = [&](const chunk_t (&xs)[XL], const chunk_t (&ws)[WL], int buf, int q) {
 #pragma unroll
-            for (int i = q * XQ; i < (q + 1) * XQ; ++i) sX[buf * BM * 8 + swz(lrow + i * RPP, lc)] = xs[i];
-#pragma unroll
-            for (int i = q * WQ; i < (q + 1) * WQ; ++i) sW[buf * BN * 8 + swz(lrow + i * RPP, lc)] = ws[i];
+            for (int s = 0; s < NS; ++s) {
+                if (s * 4 / NS != q) continue;
+                if (s < XL)
+                    sX[buf * BM * 8 + swz(lrow + s * RPP, lc)] = xs[s < XL ? s : 0];
+                else
+                    sW[buf * BN * 8 + swz(lrow + (s - XL) * RPP, lc)] = ws[s >= XL ? s - XL : 0];
+            }
         };
         auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
         // stage kt: set (lx, lw) receives stage kt + 2, set (sx, sw) holds stage kt + 1
@@ -476,6 +483,8 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
             return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
         case kGemmTile256x256w4:
             return launch_tile<E, 256, 256, 2, 2>(a, stream, timer);
+        case kGemmTile128x192:
+            return launch_tile<E, 128, 192, 2, 2>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

@@ -182,6 +182,7 @@ enum GemmVariant {
     kGemmPipe256x256w8 = 6,  // direct-to-LDS software pipeline, 256x256 tile on 8 waves
     kGemmPipe256x256w4 = 7,  // same on 4 waves (128x128 per wave)
     kGemmPipe128x128w4 = 8,  // 128x128 tile on 4 waves
+    kGemmTile128x192 = 9,    // 128 rows x 192 columns on 4 waves (fills the chip where 256x128 leaves CUs idle)
     kGemmVariantCount
 };
 

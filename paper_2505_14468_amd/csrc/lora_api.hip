@@ -306,13 +306,14 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         return c;
     }
     // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency (measured per
-    // round at K = 4096: 256x256 104 us, 256x128 64 us, 128x128 34 us, all on 4 waves).
+    // round at K = 4096: 256x256 104 us, 256x128 64 us, 128x192 51 us, 128x128 34 us, all on 4 waves).
     struct Cand {
         int variant, bm, bn;
         double eff;
     };
     const Cand cands[] = {{kGemmTile256x256w4, 256, 256, 1.00},
                           {kGemmTile256x128, 256, 128, 0.81},
+                          {kGemmTile128x192, 128, 192, 0.77},
                           {kGemmTile128x128, 128, 128, 0.77},
                           {kGemmTile64x64, 64, 64, 0.45}};
     double best = 0.0;
@@ -478,7 +479,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.K = d->K;
     a.N = d->N;
     GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
-    if (c.variant >= kGemmPipe256x256w8) {  // these address W0 / X with 31-bit byte offsets
+    if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) {  // these address W0 / X with 31-bit byte offsets
         const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
         if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
     }
@@ -521,7 +522,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     const KernelTimer *tg = !timed ? nullptr : (split ? &second : &timer);
     if (c.variant == kGemmSkinny)
         LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, tg));
-    else if (c.variant >= kGemmPipe256x256w8)
+    else if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4)
         LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, tg));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
@@ -791,6 +792,9 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
             break;
         case kGemmPipe256x256w4:
             snprintf(buf, sizeof buf, "pipe_256x256_w4");
+            break;
+        case kGemmTile128x192:
+            snprintf(buf, sizeof buf, "tile_128x192");
             break;
         case kGemmPipe128x128w4:
             snprintf(buf, sizeof buf, "pipe_128x128_w4");
