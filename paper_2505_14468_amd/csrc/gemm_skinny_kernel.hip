@@ -324,7 +324,7 @@ hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *t
 
 }  // namespace
 
-// tblk: 16-row blocks (1, 2, 4, 8); nb: 16-column blocks per workgroup (1, 2, 4; nb * tblk <= 8).
+// tblk: 16-row blocks (1, 2, 4, 6, 8); nb: 16-column blocks per workgroup (1, 2, 4; nb * tblk <= 8).
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer) {
     if (a.T <= 0 || a.N <= 0) return hipSuccess;
     if (a.Xpack == nullptr) return hipErrorInvalidValue;
@@ -338,6 +338,7 @@ hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t s
     LORA_SK_CASE(2, 4);
     LORA_SK_CASE(4, 1);
     LORA_SK_CASE(4, 2);
+    LORA_SK_CASE(6, 1);
     LORA_SK_CASE(8, 1);
 #undef LORA_SK_CASE
     return hipErrorInvalidValue;

@@ -272,7 +272,7 @@ int check_plan_buf(const void *plan_buf, size_t plan_buf_bytes, const PlanLayout
 }
 
 // ---- kernel selection ---------------------------------------------------------------------------------
-int skinny_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : 8; }
+int skinny_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : T <= 96 ? 6 : 8; }
 
 struct GemmChoice {
     int variant;
