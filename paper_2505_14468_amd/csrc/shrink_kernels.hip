@@ -34,9 +34,13 @@ constexpr int kXldsChunks = 2;                    // ... of at most this many ch
 // Dynamic LDS of the kernel: [reduction area][operand buffers][X staging area (only when launched with it)].
 constexpr int kShSmemBase = kRedBytes > kPartBytes ? kRedBytes : kPartBytes;
 
-template <typename E, int TB, int JB>
+// (AH: the unit's block of ranks has at most 8 of them -- one load instruction per stage of A_a covers it; the
+// upper half of the MFMA tile then multiplies stale LDS contents into accumulator rows that are never stored)
+template <typename E, int TB, int JB, bool AH = false>
 __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, float scale, int slot0, int nrows, int j0,
                                             int nj, const int (&prow)[4][2], unsigned char *smem) {
+    static_assert(!AH || JB == 1, "half blocks of ranks: one block only");
+    constexpr int AI = AH ? 1 : 2;  // load instructions per stage and 16-rank block of A_a
     constexpr int CE = Elem<E>::CE;
     constexpr int LPS = TB + JB;
     // Stages (128 bytes of every row: two MFMA steps) of operand loads in flight per wave, held in a ring of
@@ -110,12 +114,12 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
     };
     auto load_a = [&](int sg, int jb, StageRegs &f) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) f.a[jb][i] = load_chunk(Ab + (unsigned)sg * 128u + aoff[jb][i]);
+        for (int i = 0; i < AI; ++i) f.a[jb][i] = load_chunk(Ab + (unsigned)sg * 128u + aoff[jb][i]);
     };
     // one 16-row block of one stage: through the wave's buffer into the two steps' operands
-    auto to_operands = [&](const chunk_t (&in)[2], chunk_t (&out)[2]) {
+    auto to_operands = [&](const chunk_t (&in)[2], chunk_t (&out)[2], bool both = true) {
         buf[wdst[0]] = in[0];
-        buf[wdst[1]] = in[1];
+        if (both) buf[wdst[1]] = in[1];
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");  // keeps the compiler from reordering across the exchange
         out[0] = buf[rsrc + (lg ^ rswz)];
         out[1] = buf[rsrc + ((4 + lg) ^ rswz)];
@@ -145,7 +149,7 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
 #pragma unroll
         for (int jb = 0; jb < JB; ++jb) {
             chunk_t a[2];
-            to_operands(f.a[jb], a);
+            to_operands(f.a[jb], a, !AH);
             if (again) load_a(next, jb, f);
 #pragma unroll
             for (int h = 0; h < 2; ++h)
@@ -381,7 +385,9 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
 
     // unit shape -> instantiation (all branches are uniform over the workgroup)
     if (nrows <= 16) {
-        if (nj <= 16)
+        if (nj <= 8)
+            shrink_unit<E, 1, 1, true>(p, Aa, scale, slot0, nrows, j0, nj, prow, smem);
+        else if (nj <= 16)
             shrink_unit<E, 1, 1>(p, Aa, scale, slot0, nrows, j0, nj, prow, smem);
         else if (nj <= 32)
             shrink_unit<E, 1, 2>(p, Aa, scale, slot0, nrows, j0, nj, prow, smem);
