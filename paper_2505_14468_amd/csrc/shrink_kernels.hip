@@ -22,8 +22,7 @@ namespace lora {
 namespace {
 
 constexpr int kShWaves = 8;
-constexpr int kRS = kShrinkRanks + 1;             // padded row stride of the serial reduction buffer
-constexpr int kRedBytes = kShrinkRows * kRS * 4;  // serial reduction buffer (large units)
+constexpr int kRedBytes = 16 * 64 * 16;           // serial reduction buffer (large units): [16 tiles][64 lanes] float4
 constexpr int kPartBytes = kShWaves * 4 * 1024;   // per-wave partial tiles (units of at most 4 MFMA tiles)
 constexpr int kStageBytes = kShWaves * 2048;       // per-wave buffers that turn loaded lines into MFMA operands
 constexpr int kXldsBytes = 64 * 1024;             // rows of X staged in LDS (units of a few rows)
@@ -262,25 +261,42 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
             if constexpr (CE == 8) store4(dst + 4, scale * sum[4], scale * sum[5], scale * sum[6], scale * sum[7]);
         }
     } else {
-        // large tiles (long K loops behind them): one wave after the other adds into one buffer
-        float *red = reinterpret_cast<float *>(smem);
+        // large tiles (long K loops behind them): one wave after the other adds into one buffer, every lane into
+        // its own 16-byte slot of every tile -- [tile][lane] float4: one conflict-free LDS read and write per tile
+        float4 *red = reinterpret_cast<float4 *>(smem);
         for (int w = 0; w < kShWaves; ++w) {
             if (wave == w) {
 #pragma unroll
                 for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-                    for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            float *dst = &red[(tb * 16 + li) * kRS + jb * 16 + lg * 4 + e];
-                            *dst = (w == 0) ? acc[tb][jb][e] : (*dst + acc[tb][jb][e]);
+                    for (int jb = 0; jb < JB; ++jb) {
+                        float4 *dst = &red[(tb * JB + jb) * 64 + lane];
+                        float4 v = make_float4(acc[tb][jb][0], acc[tb][jb][1], acc[tb][jb][2], acc[tb][jb][3]);
+                        if (w != 0) {
+                            const float4 o = *dst;
+                            v.x += o.x;
+                            v.y += o.y;
+                            v.z += o.z;
+                            v.w += o.w;
                         }
+                        *dst = v;
+                    }
             }
             __syncthreads();
         }
+        // element (t, j) of the unit sits in tile (t / 16, j / 16), lane t % 16 + 16 * (j % 16 / 4), component j % 4
         for (int e = tid; e < nrows * jchunks; e += kShWaves * 64) {
             const int t = e / jchunks, jc = e - t * jchunks;
-            const float *src = &red[t * kRS + jc * CE];
+            float src[CE];
+#pragma unroll
+            for (int q = 0; q < CE / 4; ++q) {
+                const int j = jc * CE + q * 4;
+                const float4 v = red[((t >> 4) * JB + (j >> 4)) * 64 + (t & 15) + 16 * ((j & 15) >> 2)];
+                src[q * 4 + 0] = v.x;
+                src[q * 4 + 1] = v.y;
+                src[q * 4 + 2] = v.z;
+                src[q * 4 + 3] = v.w;
+            }
             E *dst = V + (int64_t)p.plan.perm[slot0 + t] * p.r_max + j0 + jc * CE;
             store4(dst, scale * src[0], scale * src[1], scale * src[2], scale * src[3]);
             if constexpr (CE == 8) store4(dst + 4, scale * src[4], scale * src[5], scale * src[6], scale * src[7]);
