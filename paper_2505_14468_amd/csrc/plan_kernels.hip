@@ -826,6 +826,294 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
     }
 }
 
+// Up to 128 requests: the same one-lane-per-request scheme on more waves.  Wave (g, q), g < 2, keeps the requests
+// 64 g .. 64 g + 63 (one per lane) and takes quarter q of the broadcasts: 16 lanes of each 64-request group of
+// sources, read with v_readlane out of registers that hold (key, rows) of that group; the four waves of a
+// group add their partial sums through LDS.  The second pass (first requests of the segments: segment index,
+// rank and unit prefixes) needs flags of all groups, which go through LDS once.
+constexpr int kMidReq = 128;  // (the work grows with the square of the request count: beyond this the scans of the general kernel win)
+constexpr int kMidGroups = kMidReq / 64;
+constexpr int kMidParts = kPlanWaves / kMidGroups;  // waves per group of 64 requests
+constexpr int kMidLanes = 64 / kMidParts;            // source lanes of a group that one wave broadcasts
+
+__global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p) {
+    __shared__ int s_p1[kPlanWaves][5][64];  // pass 1 partials: less, equal-before, rows of key, rows before, earlier-same flag
+    __shared__ int s_p2[kPlanWaves][3][64];  // pass 2 partials: segments, ranks, units of smaller keys
+    __shared__ unsigned long long s_rows[kPlanWaves];
+    __shared__ int s_tot[kPlanWaves][2];  // ranks, units of all segments (per wave's share)
+    __shared__ int s_flag[kMidGroups][5];  // per group: any bad id, negative length, not resident, rank too large, bad rank
+    __shared__ int s_first[kMidReq], s_rkf[kMidReq], s_units[kMidReq];
+    __shared__ int s_tok[kMidReq + 1], s_dst[kMidReq], s_rseg[kMidReq], s_a[kMidReq];
+    __shared__ int s_sad[kMidReq + 1], s_sip[kMidReq + 1], s_srk[kMidReq + 1], s_sex[kMidReq + 1], s_sun[kMidReq + 1];
+    __shared__ int s_hdr[4];  // status, segments, total ranks, total units
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = wave / kMidParts, q = wave % kMidParts;
+    const int R = p.n_req, n_ad = p.n_adapters;
+    const int G = (R + 63) >> 6;  // groups in use
+
+    // (key, rows) of a request; key n_ad = "no adapter", idle or invalid requests match nothing that counts
+    auto classify = [&](int j, int &a, int &L, bool &bad, bool &neg, bool &active, int &key, int &rows) {
+        const bool valid = j < R;
+        a = valid ? p.req_adapter[j] : -1;
+        L = valid ? p.req_ntok[j] : 0;
+        bad = valid && (a < -1 || a >= n_ad);
+        neg = valid && !bad && L < 0;
+        active = valid && !bad && !neg && L > 0;
+        key = active ? (a < 0 ? n_ad : a) : INT_MAX;
+        rows = active ? L : 0;
+    };
+    // this lane's own request, and the sources of every group
+    const int i = 64 * g + lane;
+    int a, L, key, rows;
+    bool bad, neg, active;
+    classify(i, a, L, bad, neg, active, key, rows);
+    const int rk = (active && a >= 0) ? p.rank[a] : 0;  // wanted after pass 1 only: in flight during it
+    int skey[kMidGroups], srow[kMidGroups];
+#pragma unroll
+    for (int sg = 0; sg < kMidGroups; ++sg) {
+        int a2, L2;
+        bool b2, n2, act2;
+        classify(64 * sg + lane, a2, L2, b2, n2, act2, skey[sg], srow[sg]);
+    }
+
+    // ---- pass 1: this wave's quarter of every group of sources, broadcast one by one ----
+    {
+        int less = 0, eqb = 0, h = 0, before = 0, earlier = 0;
+        unsigned long long total = 0ull;
+#pragma unroll
+        for (int sg = 0; sg < kMidGroups; ++sg) {
+            if (sg < G) {
+#pragma unroll
+                for (int jj = 0; jj < kMidLanes; ++jj) {
+                    const int l2 = q * kMidLanes + jj, j = 64 * sg + l2;
+                    if (j < R) {
+                        const int kj = __builtin_amdgcn_readlane(skey[sg], l2);
+                        const int Lj = __builtin_amdgcn_readlane(srow[sg], l2);
+                        const bool same = kj == key, prior = j < i;
+                        less += kj < key ? Lj : 0;
+                        h += same ? Lj : 0;
+                        eqb += (same && prior) ? Lj : 0;
+                        before += prior ? Lj : 0;
+                        earlier |= (same && prior) ? 1 : 0;
+                        total += (unsigned long long)(unsigned)Lj;
+                    }
+                }
+            }
+        }
+        s_p1[wave][0][lane] = less;
+        s_p1[wave][1][lane] = eqb;
+        s_p1[wave][2][lane] = h;
+        s_p1[wave][3][lane] = before;
+        s_p1[wave][4][lane] = earlier;
+        if (lane == 0) s_rows[wave] = total;
+    }
+    __syncthreads();
+
+    int less = 0, eqb = 0, h = 0, before = 0, earlier = 0;
+#pragma unroll
+    for (int w = 0; w < kMidParts; ++w) {
+        less += s_p1[g * kMidParts + w][0][lane];
+        eqb += s_p1[g * kMidParts + w][1][lane];
+        h += s_p1[g * kMidParts + w][2][lane];
+        before += s_p1[g * kMidParts + w][3][lane];
+        earlier |= s_p1[g * kMidParts + w][4][lane];
+    }
+    const bool first = active && earlier == 0;
+    const bool seg_ad = first && a >= 0;
+    const bool not_res = seg_ad && rk <= 0;
+    const bool shape = seg_ad && rk > 0 && (rk & 7) != 0;
+    const bool large = seg_ad && rk > 0 && (rk & 7) == 0 && rk > p.r_max;
+    const int rkf = (seg_ad && !not_res && !shape && !large) ? rk : 0;
+    const int units = seg_ad ? (h + kShrinkRows - 1) / kShrinkRows : 0;
+    if (q == 0) {  // one wave per group passes the group's flags and per-request values on
+        const int f0 = __builtin_amdgcn_ballot_w64(bad) != 0ull, f1 = __builtin_amdgcn_ballot_w64(neg) != 0ull;
+        const int f2 = __builtin_amdgcn_ballot_w64(not_res) != 0ull, f3 = __builtin_amdgcn_ballot_w64(large) != 0ull;
+        const int f4 = __builtin_amdgcn_ballot_w64(shape) != 0ull;
+        if (lane == 0) {
+            s_flag[g][0] = f0;
+            s_flag[g][1] = f1;
+            s_flag[g][2] = f2;
+            s_flag[g][3] = f3;
+            s_flag[g][4] = f4;
+        }
+        s_first[i] = first ? 1 : 0;
+        s_rkf[i] = rkf;
+        s_units[i] = units;
+    }
+    __syncthreads();
+
+    // status, in the order and with the precedence of the general kernel (the smallest code wins)
+    int st = 0;
+    {
+        int any[5] = {0, 0, 0, 0, 0};
+#pragma unroll
+        for (int sg = 0; sg < kMidGroups; ++sg)
+#pragma unroll
+            for (int f = 0; f < 5; ++f) any[f] |= s_flag[sg][f];
+        if (any[0]) st = min(st, kErrBadAdapterId);
+        if (any[1]) st = min(st, kErrLengthMismatch);
+        if (st == 0) {
+            unsigned long long total = 0ull;
+#pragma unroll
+            for (int w = 0; w < kMidParts; ++w) total += s_rows[w];  // the waves of a group cover every source once
+            if (total != (unsigned long long)(unsigned)p.T) st = kErrLengthMismatch;
+        }
+        if (st == 0) {
+            if (any[2]) st = min(st, kErrNotResident);
+            if (any[3]) st = min(st, kErrRankTooLarge);
+            if (any[4]) st = min(st, kErrShape);
+        }
+    }
+    if (st != 0) {  // (uniform over the workgroup)
+        if (tid == 0) write_failed(p, st);
+        return;
+    }
+
+    // ---- pass 2: the first requests of the segments, this wave's quarter of every group, broadcast one by one ----
+    unsigned long long fmask[kMidGroups];
+    int c_seg = 0;
+    {
+        int srk[kMidGroups], sun[kMidGroups];
+#pragma unroll
+        for (int sg = 0; sg < kMidGroups; ++sg) {
+            fmask[sg] = __builtin_amdgcn_ballot_w64(s_first[64 * sg + lane] != 0);
+            srk[sg] = s_rkf[64 * sg + lane];
+            sun[sg] = s_units[64 * sg + lane];
+            c_seg += __builtin_popcountll(fmask[sg]);
+        }
+        int seg = 0, ext = 0, un = 0, tot_ext = 0, tot_un = 0;
+#pragma unroll
+        for (int sg = 0; sg < kMidGroups; ++sg) {
+            if (sg < G) {
+#pragma unroll
+                for (int jj = 0; jj < kMidLanes; ++jj) {
+                    const int l2 = q * kMidLanes + jj;
+                    if ((fmask[sg] >> l2) & 1ull) {
+                        const int kj = __builtin_amdgcn_readlane(skey[sg], l2);
+                        const int rj = __builtin_amdgcn_readlane(srk[sg], l2);
+                        const int uj = __builtin_amdgcn_readlane(sun[sg], l2);
+                        const bool lt = kj < key;
+                        seg += lt ? 1 : 0;
+                        ext += lt ? rj : 0;
+                        un += lt ? uj : 0;
+                        tot_ext += rj;
+                        tot_un += uj;
+                    }
+                }
+            }
+        }
+        s_p2[wave][0][lane] = seg;
+        s_p2[wave][1][lane] = ext;
+        s_p2[wave][2][lane] = un;
+        if (lane == 0) {
+            s_tot[wave][0] = tot_ext;
+            s_tot[wave][1] = tot_un;
+        }
+    }
+    __syncthreads();
+
+    if (q == 0) {  // publish: request arrays and segment arrays, to LDS for the fill below and to the plan
+        int seg = 0, ext = 0, un = 0, c_ext = 0, c_unit = 0;
+#pragma unroll
+        for (int w = 0; w < kMidParts; ++w) {
+            seg += s_p2[g * kMidParts + w][0][lane];
+            ext += s_p2[g * kMidParts + w][1][lane];
+            un += s_p2[g * kMidParts + w][2][lane];
+            c_ext += s_tot[w][0];  // (the waves of a group cover every source once)
+            c_unit += s_tot[w][1];
+        }
+        if (i < R) {
+            s_tok[i] = before;
+            s_dst[i] = less + eqb;
+            s_rseg[i] = seg;
+            s_a[i] = a;
+            p.tok_off[i] = before;
+        }
+        if (first) {
+            s_sad[seg] = a >= 0 ? a : -1;
+            s_sip[seg] = less;
+            s_srk[seg] = rkf;
+            s_sex[seg] = ext;
+            s_sun[seg] = un;
+            p.seg_adapter[seg] = a >= 0 ? a : -1;
+            p.seg_indptr[seg] = less;
+            p.seg_rank[seg] = rkf;
+            p.seg_ext[seg] = ext;
+            p.seg_unit[seg] = un;
+        }
+        if (wave == 0 && lane == 0) {
+            s_tok[R] = p.T;
+            p.tok_off[R] = p.T;
+            s_sip[c_seg] = p.T;
+            s_sex[c_seg] = c_ext;
+            s_sun[c_seg] = c_unit;
+            p.seg_indptr[c_seg] = p.T;
+            p.seg_ext[c_seg] = c_ext;
+            p.seg_unit[c_seg] = c_unit;
+            p.scalars[kScNSeg] = c_seg;
+            p.scalars[kScStatus] = 0;
+            p.scalars[kScExtTotal] = c_ext;
+            p.scalars[kScNUnits] = c_unit;
+            p.scalars[kScT] = p.T;
+            s_hdr[1] = c_seg;
+            s_hdr[2] = c_ext;
+            s_hdr[3] = c_unit;
+        }
+    }
+    __syncthreads();
+    const int c_ext = s_hdr[2], c_unit = s_hdr[3];
+
+    // per-row scatter, extension records, shrink work list: as in the small-batch kernel
+    for (int t = tid; t < p.T; t += kPlanThreads) {
+        int lo = 0, hi = R;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_tok[mid + 1] > t)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int slot = s_dst[lo] + (t - s_tok[lo]);
+        p.perm[slot] = t;
+        p.row_seg[slot] = s_rseg[lo];
+        p.row_adapter[t] = s_a[lo];
+    }
+    for (int u = tid; u < (c_ext >> 3); u += kPlanThreads) {
+        const int pel = u << 3;
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sex[mid + 1] > pel)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = (s_srk[lo] << 16) | (pel - s_sex[lo]);
+        rec.z = s_sip[lo];
+        rec.w = s_sip[lo + 1];
+        reinterpret_cast<int4 *>(p.ext_rec)[u] = rec;
+    }
+    for (int u = tid; u < c_unit; u += kPlanThreads) {
+        int lo = 0, hi = c_seg;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_sun[mid + 1] > u)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        int4 rec;
+        rec.x = s_sad[lo];
+        rec.y = s_srk[lo];
+        rec.z = slot0;
+        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
+    }
+}
+
 __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
     if (p.scalars[kScStatus] != 0) return;
     const int start = blockIdx.x * 256 + threadIdx.x;
@@ -840,6 +1128,8 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanBuildArgs p) {
 hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, int variant, hipStream_t stream, const KernelTimer *timers) {
     if (fuse_fill && variant != 1 && a.n_req <= kTinyReq && a.T <= kSmallRows)
         return launch_kernel(plan_tiny_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
+    if (fuse_fill && variant != 1 && a.n_req <= kMidReq && a.T <= kSmallRows)
+        return launch_kernel(plan_mid_kernel, dim3(1), dim3(kPlanThreads), 0, stream, timers ? &timers[0] : nullptr, a);
     if (fuse_fill && a.n_req <= kSmallReq && a.n_adapters + 1 <= kSmallKeys && a.T <= kSmallRows) {
 #ifdef LORA_TRACE
         return trace_launch("plan_small", 1, [&](long long *buf) {

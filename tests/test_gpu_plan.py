@@ -83,6 +83,23 @@ def test_plan_decode_sized_batches(seed):
         _check_plan(ids, L, ranks, False, plan_variant=variant)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_plan_65_to_128_requests(seed):
+    """65..128 requests: the one-lane-per-request kernel on all 16 waves, against the reference and with the
+    same batch through the general kernels (plan_variant=1); larger batches for the general kernels alone."""
+    rng = np.random.default_rng(700 + seed)
+    n_ad = int(rng.choice([1, 2, 7, 100, 300, 3000]))
+    R = int(rng.choice([65, 73, 100, 127, 128, 129, 200, 256]))
+    ranks = rng.choice([8, 16, 24, 64], size=n_ad)
+    ids = rng.integers(-1, n_ad, size=R)
+    if seed % 2 == 0:
+        ids[rng.integers(0, R, size=R // 2)] = ids[0]  # one long segment: several shrink units
+    L = rng.integers(0, 3, size=R) if seed < 4 else rng.integers(0, 30, size=R)
+    for variant in (-1, 1):
+        _check_plan(ids, L, ranks, True, plan_variant=variant)
+        _check_plan(ids, L, ranks, False, plan_variant=variant)
+
+
 @pytest.mark.parametrize("fused_rows", [0, 1 << 20])
 def test_plan_both_fill_paths_and_many_requests(fused_rows):
     rng = np.random.default_rng(5)
@@ -122,6 +139,13 @@ def test_plan_device_reports_errors_in_status_word():
         (([0, 1], [1, 1], [8, 12], 16, 2), B.LORA_ERR_SHAPE),
     ]
     cases.append((([0, 5, 1], [1, 1, -1], [8, 8], 8, 1), B.LORA_ERR_LENGTH_MISMATCH))  # two faults: the smaller code
+    # the same kinds of fault in a batch of 150 requests, each in the last group of 64
+    many = lambda bad_id, bad_len: ([0] * 140 + [bad_id] + [1] * 9, [1] * 145 + [bad_len] + [1] * 4)
+    cases.append(((*many(7, 1), [8, 8], 8, 150), B.LORA_ERR_BAD_ADAPTER_ID))
+    cases.append(((*many(1, -1), [8, 8], 8, 148), B.LORA_ERR_LENGTH_MISMATCH))
+    cases.append(((*many(1, 1), [8, 8], 8, 151), B.LORA_ERR_LENGTH_MISMATCH))
+    cases.append(((*many(1, 1), [8, 0], 8, 150), B.LORA_ERR_ADAPTER_NOT_RESIDENT))
+    cases.append(((*many(1, 1), [8, 16], 8, 150), B.LORA_ERR_RANK_TOO_LARGE))
     for (ids, L, ranks, r_max, T), want in cases:
         for variant in (1, -1):  # other kernels, then the decode-sized one
             c.set_option("plan_variant", variant)
