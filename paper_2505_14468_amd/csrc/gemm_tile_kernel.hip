@@ -14,8 +14,11 @@
 // blocks that hold no row of the adapter at hand.
 //
 // Tile: BM token rows x BN output columns, BK = 8 chunks (128 bytes) of the contraction axis
-// per stage, double-buffered in LDS, global -> registers -> LDS with the next stage's loads
-// in flight during the current stage's MFMAs.  MFMA orientation: M = output column n (W rows),
+// per stage, double-buffered in LDS, global -> registers -> LDS.  The base product is a
+// hand-written software pipeline: MFMA operands are read from LDS one use ahead, the last
+// k-step of a stage is split around the stage's barrier, and on 4 waves two register sets of
+// staged operands keep the loads of the stage after next in flight while the next one is
+// written to LDS, a quarter per k-step.  MFMA orientation: M = output column n (W rows),
 // N = token row t (X rows), so that every lane ends up with 4 consecutive n of one row.
 // LDS rows are 8 chunks long and XOR-swizzled by (row >> 1) & 7 so that both the 16-byte
 // stores (8 lanes per row) and the MFMA operand reads (32 rows, one chunk column) spread

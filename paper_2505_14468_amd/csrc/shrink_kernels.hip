@@ -3,15 +3,17 @@
 //
 // One workgroup = one work unit = (segment, block of <= 64 of its rows, group of <= 64 ranks).
 // The unit list is part of the plan; the grid is an upper bound and surplus workgroups
-// leave at once.  Inside a unit the NW waves split the contraction axis K between
+// leave at once.  Inside a unit the 8 waves split the contraction axis K between
 // them; each wave runs 16x16 MFMA tiles with the adapter rows (ranks) as the MFMA M dimension
-// and the token rows as the N dimension, both operands loaded straight from global memory as
-// 16-byte chunks (A_a is [r, K] and X is [T, K]: both are contiguous along K, which is what
-// the MFMA operand layout wants).  Loads are issued in batches of several MFMA steps with two
-// batches in flight, because for decode-sized segments (a handful of rows, MFMA tile mostly
-// empty) the kernel is bound by the latency and bandwidth of streaming A_a once.  The unit's
-// shape picks the instantiation (1 or 4 token blocks, 1 / 2 / 4 rank blocks) so that small
-// units spend their registers on loads in flight rather than on empty tiles.
+// and the token rows as the N dimension.  A_a is [r, K] and X is [T, K], both contiguous along
+// K: a wave loads a stage (128 bytes of every row, two MFMA steps) of a 16-row block as two
+// instructions of 8 rows x 128 bytes -- whole cache lines -- and turns it into MFMA operand
+// layout through a 2 KB wave-private LDS buffer.  A ring of stages is kept in registers and a
+// block is requested again for the stage one ring later as soon as it has been consumed, because
+// for decode-sized segments (a handful of rows, MFMA tile mostly empty) the kernel is bound by
+// the latency and bandwidth of streaming A_a once.  The unit's shape picks the instantiation
+// (1 or 4 token blocks, 1 / 2 / 4 rank blocks) so that small units spend their registers on
+// loads in flight rather than on empty tiles.
 // The per-wave partial tiles are summed through LDS in wave order, so the result is
 // deterministic, scaled by s_a in fp32 and stored once (bf16 or fp32), in original row order.
 #include <type_traits>
