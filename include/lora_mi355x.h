@@ -146,7 +146,7 @@ int lora_ctx_destroy(lora_ctx *ctx);
 /* Tuning overrides for experiments ("gemm_variant" = 0 tile 128x128,
  * 1 256x128, 2 256x256 on 8 waves, 3 64x64, 4 the decode-sized kernel (up to
  * 128 rows, bf16), 5 256x256 on 4 waves, 6 / 7 / 8 the direct-to-LDS pipeline
- * 256x256 on 8 / on 4 waves / 128x128, 9 128x192, 10 256x192; "skinny_nb",
+ * 256x256 on 8 / on 4 waves / 128x128, 9 128x192, 10 256x192, 11 256x224; "skinny_nb",
  * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
  * one-lane-per-request plan kernels, "expand_split" = 0 / 1: adapter term always
  * computed inside the GEMM / by the separate expand kernel whenever the

@@ -490,6 +490,8 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
             return launch_tile<E, 128, 192, 2, 2>(a, stream, timer);
         case kGemmTile256x192:
             return launch_tile<E, 256, 192, 2, 2>(a, stream, timer);
+        case kGemmTile256x224:
+            return launch_tile<E, 256, 224, 4, 1>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

@@ -184,6 +184,7 @@ enum GemmVariant {
     kGemmPipe128x128w4 = 8,  // 128x128 tile on 4 waves
     kGemmTile128x192 = 9,    // 128 rows x 192 columns on 4 waves (fills the chip where 256x128 leaves CUs idle)
     kGemmTile256x192 = 10,   // 256 x 192 on 4 waves (a tile count just below a whole number of rounds where 256x256 is just above)
+    kGemmTile256x224 = 11,   // 256 x 224 on 4 waves of 64 x 224 (likewise)
     kGemmVariantCount
 };
 

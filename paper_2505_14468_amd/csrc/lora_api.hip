@@ -306,13 +306,14 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         return c;
     }
     // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency (measured per
-    // round at K = 4096: 256x256 104 us, 256x192 88 us, 256x128 64 us, 128x192 51 us, 128x128 34 us, all on 4 waves).
+    // round at K = 4096: 256x256 104 us, 256x224 100 us, 256x192 88 us, 256x128 64 us, 128x192 51 us, 128x128 34 us, all on 4 waves).
     struct Cand {
         int variant, bm, bn;
         double eff;
     };
     const Cand cands[] = {{kGemmTile256x256w4, 256, 256, 1.00},
                           {kGemmTile256x128, 256, 128, 0.81},
+                          {kGemmTile256x224, 256, 224, 0.905},
                           {kGemmTile256x192, 256, 192, 0.89},
                           {kGemmTile128x192, 128, 192, 0.77},
                           {kGemmTile128x128, 128, 128, 0.77},
@@ -799,6 +800,9 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
             break;
         case kGemmTile256x192:
             snprintf(buf, sizeof buf, "tile_256x192");
+            break;
+        case kGemmTile256x224:
+            snprintf(buf, sizeof buf, "tile_256x224");
             break;
         case kGemmPipe128x128w4:
             snprintf(buf, sizeof buf, "pipe_128x128_w4");

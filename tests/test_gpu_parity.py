@@ -9,7 +9,7 @@ from workloads import make_custom, make_workload, same_adapter_decode, to_f64
 pytestmark = pytest.mark.gpu
 
 VARIANTS = {"tile_128x128": 0, "tile_256x128": 1, "tile_256x256": 2, "tile_64x64": 3, "skinny": 4, "tile_256x256w4": 5,
-            "pipe_256x256_w8": 6, "pipe_256x256_w4": 7, "pipe_128x128_w4": 8, "tile_128x192": 9, "tile_256x192": 10}
+            "pipe_256x256_w8": 6, "pipe_256x256_w4": 7, "pipe_128x128_w4": 8, "tile_128x192": 9, "tile_256x192": 10, "tile_256x224": 11}
 
 
 def _mixed_batch(seed, R, n_ad, max_len, with_none=True, zero_len=True):
@@ -30,7 +30,7 @@ def test_config0_fp32_all_tile_variants():
     reset_options()
 
 
-@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256", "tile_256x256w4", "tile_128x192", "tile_256x192",
+@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256", "tile_256x256w4", "tile_128x192", "tile_256x192", "tile_256x224",
                                      "pipe_256x256_w8", "pipe_256x256_w4", "pipe_128x128_w4"])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_tile_kernels_ragged_multi_tile(variant, dtype):
@@ -49,7 +49,7 @@ def test_tile_kernels_ragged_multi_tile(variant, dtype):
     reset_options()
 
 
-@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256w4", "tile_256x256", "tile_128x192", "tile_256x192"])
+@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256w4", "tile_256x256", "tile_128x192", "tile_256x192", "tile_256x224"])
 def test_tile_kernels_short_contraction_axes(variant):
     """One to five stages of the contraction axis, with and without a partial last stage: the prologue and
     the last stages of the software-pipelined loops (two stages of loads ahead) for every stage count."""
