@@ -105,6 +105,7 @@ typedef struct lora_plan_t {
     int32_t seg_cap;        /* capacity of the seg_* arrays                                 */
     int32_t ext_cap;        /* capacity of ext_rec                                          */
     int32_t magic;
+    int32_t unit_rows;      /* most rows of a work unit: 64, or 16 in a plan of few rows and segments */
     const int32_t *perm;        /* device [T]        slot -> row index of X / Y             */
     const int32_t *row_seg;     /* device [T]        slot -> segment                        */
     const int32_t *row_adapter; /* device [T]        row (original order) -> adapter id     */
@@ -112,8 +113,8 @@ typedef struct lora_plan_t {
     const int32_t *seg_indptr;  /* device [seg_cap+1] first slot of the segment             */
     const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
     const int32_t *seg_ext;     /* device [seg_cap+1] exclusive prefix sum of seg_rank      */
-    const int32_t *seg_unit;    /* device [seg_cap+1] prefix sum of ceil(rows/64) (shrink work list) */
-    const int32_t *unit_rec;    /* device [(T/64+seg_cap)*4] shrink work units: adapter, rank, first slot, rows */
+    const int32_t *seg_unit;    /* device [seg_cap+1] prefix sum of ceil(rows/unit_rows) (work list) */
+    const int32_t *unit_rec;    /* device [(T/16+seg_cap)*4] work units: adapter, rank, first slot, rows */
     const int32_t *ext_rec;     /* device [ext_cap*4] per 8 ranks: adapter, rank<<16|j0, slot_lo, slot_hi */
     const int32_t *tok_off;     /* device [n_req+1]  first row of every request             */
     int32_t *scalars;           /* device [8]: n_seg, status, ext_total, n_units, ...       */
@@ -150,8 +151,7 @@ int lora_ctx_destroy(lora_ctx *ctx);
  * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
  * one-lane-per-request plan kernels, "expand_split" = 0 / 1: adapter term always
  * computed inside the GEMM / by the separate expand kernel whenever the
- * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64,
- * "shrink_row_split" = 1 / 4);
+ * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64);
  * value < 0 restores the built-in heuristic.  Results never depend on them
  * beyond fp32 summation order.  Errors: INVALID_ARG for an unknown name or a
  * value the option does not take. */

@@ -19,6 +19,7 @@ struct PlanBuildArgs {
     int32_t n_req, n_adapters, r_max;
     int32_t T;
     int32_t seg_cap, ext_cap;
+    int32_t unit_rows, unit_shift;  // rows per work unit (kShrinkRows or kShrinkRowsSmall) and its log2
     // outputs / scratch, all device int32 arrays inside plan_buf
     int32_t *tok_off;      // [n_req+1]
     int32_t *req_dst;      // [n_req]  first slot of each request's rows
@@ -126,7 +127,6 @@ struct ShrinkArgs {
     int32_t n_adapters;    // entries of the A / scale tables
     int32_t rank_block;    // ranks per workgroup: 8 or 16 (few units: spread them over the chip) or kShrinkRanks
     int32_t rank_groups;   // ceil(r_max / rank_block)
-    int32_t row_split;     // 1, or 4: a unit's rows are dealt in blocks of 16 to 4 workgroups (few units, decode-sized)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
     int32_t xlds_bytes;    // LDS for staging the X rows of small units: 0 or 64 KiB (decode-sized batches)
     // Fragment-major copy of X for the decode-sized GEMM (null = not needed): for MFMA step s

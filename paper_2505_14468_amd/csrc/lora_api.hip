@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 
@@ -57,7 +58,6 @@ struct lora_ctx {
     int opt_skinny_max_rows = -1;
     int opt_plan_fused_rows = -1;
     int opt_shrink_rank_block = -1;
-    int opt_shrink_row_split = -1;
     int opt_plan_variant = -1;
     int opt_expand_split = -1;
     // profiling mode: event pairs recorded tightly around each kernel
@@ -149,7 +149,7 @@ PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_m
     L.seg_rank = take((size_t)L.seg_cap);
     L.seg_ext = take((size_t)L.seg_cap + 1);
     L.seg_unit = take((size_t)L.seg_cap + 1);
-    L.unit_rec = take(((size_t)T / kShrinkRows + (size_t)L.seg_cap) * 4);
+    L.unit_rec = take(((size_t)T / kShrinkRowsSmall + (size_t)L.seg_cap) * 4);  // (room for either unit size)
     L.ext_rec = take((size_t)L.ext_cap * 4);
     L.scalars = take(8);
     L.total_bytes = off * sizeof(int32_t);
@@ -216,6 +216,13 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.T = (int32_t)T;
     a.seg_cap = L.seg_cap;
     a.ext_cap = L.ext_cap;
+    // Work units of 16 rows while that keeps their number within one workgroup per CU (decode batches, small mixed
+    // batches: the long segments then spread over the chip instead of holding a few CUs four times as long), of 64
+    // rows otherwise (a unit of 64 rows reads its adapter once for four times the rows).
+    const int64_t seg_bound = std::min<int64_t>(std::min<int64_t>(n_req, n_adapters), T);
+    const bool small_units = T / kShrinkRowsSmall + seg_bound <= (int64_t)ctx->num_cu;
+    a.unit_rows = small_units ? kShrinkRowsSmall : kShrinkRows;
+    a.unit_shift = small_units ? 4 : 6;
     a.tok_off = base + L.tok_off;
     a.req_dst = base + L.req_dst;
     a.hist = base + L.hist;
@@ -248,6 +255,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     out->seg_cap = L.seg_cap;
     out->ext_cap = L.ext_cap;
     out->magic = kPlanMagic;
+    out->unit_rows = a.unit_rows;
     out->perm = a.perm;
     out->row_seg = a.row_seg;
     out->row_adapter = a.row_adapter;
@@ -364,6 +372,7 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
 int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d) {
     if (!plan || !d) return LORA_ERR_INVALID_ARG;
     if (plan->magic != kPlanMagic || plan->T < 0 || !plan->scalars) return LORA_ERR_PLAN;
+    if (plan->unit_rows != kShrinkRows && plan->unit_rows != kShrinkRowsSmall) return LORA_ERR_PLAN;
     if (d->dtype != LORA_DTYPE_BF16 && d->dtype != LORA_DTYPE_F32) return LORA_ERR_INVALID_ARG;
     if (d->flags != 0) return LORA_ERR_INVALID_ARG;
     const int ce = d->dtype == LORA_DTYPE_BF16 ? 8 : 4;
@@ -429,10 +438,10 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.V = ws + w.v_off;
     a.r_max = plan->r_max;
     a.n_adapters = ad ? d->tbl->n_adapters : 0;
-    // units <= sum over segments of ceil(rows/64) <= T/64 + number of adapter segments
+    // units <= sum over segments of ceil(rows / unit_rows) <= T / unit_rows + number of adapter segments
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
-    a.max_units = ad ? (int32_t)(plan->T / kShrinkRows + seg_bound2) : 0;
+    a.max_units = ad ? (int32_t)(plan->T / plan->unit_rows + seg_bound2) : 0;
     // With few units (decode-sized batches) a unit's ranks are dealt to several workgroups: every A_a
     // is streamed once either way, and it takes most of the chip to stream them at HBM speed.
     const int64_t wide_groups = (plan->r_max + kShrinkRanks - 1) / kShrinkRanks;
@@ -447,10 +456,6 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     if (ctx->opt_shrink_rank_block > 0) rank_block = ctx->opt_shrink_rank_block;
     a.rank_block = rank_block;
     a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
-    // Few units of many rows in a small batch (one function's own decode batch): blocks of 16 rows go to
-    // workgroups of their own, as long as that still leaves CUs to spare.
-    a.row_split = ad && small_x && plan->T > 16 && (int64_t)a.max_units * a.rank_groups * 4 <= (int64_t)ctx->num_cu ? 4 : 1;
-    if (ctx->opt_shrink_row_split > 0) a.row_split = ctx->opt_shrink_row_split == 4 ? 4 : 1;
     a.xlds_bytes = ad && plan->T <= 256 ? 64 * 1024 : 0;  // small batches: units of a few rows, one workgroup per CU is plenty
     a.xpack = pack ? ws + w.xpack_off : nullptr;
     a.pack_tblk = pack ? skinny_tblk(plan->T) : 0;
@@ -513,7 +518,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         e.N = d->N;
         const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
         const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
-        e.max_units = (int32_t)(plan->T / kShrinkRows + seg_bound2);  // as for the shrink grid
+        e.max_units = (int32_t)(plan->T / plan->unit_rows + seg_bound2);  // as for the shrink grid
         e.col_groups = 0;
         LORA_HIP(launch_expand(e, d->dtype, stream, timed ? &first : nullptr));
         a.B = nullptr;
@@ -598,9 +603,6 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     } else if (!strcmp(name, "plan_variant")) {
         if (value > 1) return LORA_ERR_INVALID_ARG;
         ctx->opt_plan_variant = value;
-    } else if (!strcmp(name, "shrink_row_split")) {
-        if (value != -1 && value != 1 && value != 4) return LORA_ERR_INVALID_ARG;
-        ctx->opt_shrink_row_split = value;
     } else if (!strcmp(name, "shrink_rank_block")) {
         if (value > 0 && value != 8 && value != 16 && value != 32 && value != 64) return LORA_ERR_INVALID_ARG;
         ctx->opt_shrink_rank_block = value;

@@ -160,12 +160,12 @@ __device__ void fill_units(const PlanBuildArgs &p, int start, int stride) {
                 lo = mid + 1;
         }
         const int s = lo;
-        const int slot0 = p.seg_indptr[s] + (u - p.seg_unit[s]) * kShrinkRows;
+        const int slot0 = p.seg_indptr[s] + (u - p.seg_unit[s]) * p.unit_rows;
         int4 rec;
         rec.x = p.seg_adapter[s];
         rec.y = p.seg_rank[s];
         rec.z = slot0;
-        rec.w = min(kShrinkRows, p.seg_indptr[s + 1] - slot0);
+        rec.w = min(p.unit_rows, p.seg_indptr[s + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
     }
 }
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
                     st = min(st, kErrRankTooLarge);
                     rk = 0;
                 }
-                units = (h + kShrinkRows - 1) / kShrinkRows;
+                units = (h + p.unit_rows - 1) >> p.unit_shift;
             }
             int4 ex4, tot4;
             block_exscan4(make_int4(flag, h, rk, units), ex4, tot4, &wave_sums[0][0]);
@@ -433,7 +433,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
                     st = min(st, kErrRankTooLarge);
                     rk = 0;
                 }
-                units = (h + kShrinkRows - 1) / kShrinkRows;
+                units = (h + p.unit_rows - 1) >> p.unit_shift;
             }
             int4 ex4, tot4;
             block_exscan4(make_int4(flag, h, rk, units), ex4, tot4, &wave_sums[0][0]);
@@ -579,12 +579,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
             else
                 lo = mid + 1;
         }
-        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
         rec.y = s_srk[lo];
         rec.z = slot0;
-        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
     }
     LORA_TS(p.trace, 7);
@@ -684,7 +684,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
             if (__builtin_amdgcn_ballot_w64(large) != 0ull) st = min(st, kErrRankTooLarge);
             if (__builtin_amdgcn_ballot_w64(shape) != 0ull) st = min(st, kErrShape);
             rkf = (seg_ad && !not_res && !shape && !large) ? rk : 0;
-            units = seg_ad ? (h + kShrinkRows - 1) / kShrinkRows : 0;
+            units = seg_ad ? (h + p.unit_rows - 1) >> p.unit_shift : 0;
         }
 
         // ---- pass 2: the first requests of the segments (this wave's quarter), broadcast one by one ----
@@ -816,12 +816,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
             else
                 lo = mid + 1;
         }
-        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
         rec.y = s_srk[lo];
         rec.z = slot0;
-        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
     }
 }
@@ -924,7 +924,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p)
     const bool shape = seg_ad && rk > 0 && (rk & 7) != 0;
     const bool large = seg_ad && rk > 0 && (rk & 7) == 0 && rk > p.r_max;
     const int rkf = (seg_ad && !not_res && !shape && !large) ? rk : 0;
-    const int units = seg_ad ? (h + kShrinkRows - 1) / kShrinkRows : 0;
+    const int units = seg_ad ? (h + p.unit_rows - 1) >> p.unit_shift : 0;
     if (q == 0) {  // one wave per group passes the group's flags and per-request values on
         const int f0 = __builtin_amdgcn_ballot_w64(bad) != 0ull, f1 = __builtin_amdgcn_ballot_w64(neg) != 0ull;
         const int f2 = __builtin_amdgcn_ballot_w64(not_res) != 0ull, f3 = __builtin_amdgcn_ballot_w64(large) != 0ull;
@@ -1104,12 +1104,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p)
             else
                 lo = mid + 1;
         }
-        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * kShrinkRows;
+        const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
         rec.y = s_srk[lo];
         rec.z = slot0;
-        rec.w = min(kShrinkRows, s_sip[lo + 1] - slot0);
+        rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
     }
 }

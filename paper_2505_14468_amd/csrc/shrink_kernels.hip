@@ -338,10 +338,12 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     // round trip to memory in a kernel that lasts a few of them: loads that do not depend on each other
     // are issued together.  The grid is an upper bound of the unit count and the work list is that
     // long, so the record can be read before the unit is known to exist.
+    // The unit index runs fastest over the grid: consecutive workgroups go to the eight XCDs in turn, and the rank
+    // blocks that often have nothing to do (those past a small adapter's rank) must not all land on the same XCDs
+    // while the others hold every unit with work.
     const int bid = blockIdx.x - p.pack_wgs;
-    const int jg = bid % p.rank_groups;
-    const int rsplit = (bid / p.rank_groups) % p.row_split;
-    const int unit = bid / (p.rank_groups * p.row_split);
+    const int unit = bid % p.max_units;
+    const int jg = bid / p.max_units;
     // Guessed ahead, in the same round trip as the record: lane i reads entry i of the adapter tables and of the
     // row map.  A decode batch (at most 64 rows, a pool of at most 64 adapters) finds everything it needs there
     // and skips the second round trip.
@@ -355,9 +357,8 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     LORA_TS(p.trace, 1);  // work-list record read
 
     // the plan's work list names the unit: adapter, rank, first slot, rows (one load, no search)
-    // (row_split 4: this workgroup takes rows 16 * rsplit .. of the unit; every part streams A_a again, from L2)
-    const int a = rec.x, r = rec.y, slot0 = rec.z + 16 * rsplit;
-    const int nrows = p.row_split > 1 ? min(16, rec.w - 16 * rsplit) : rec.w;
+    const int a = rec.x, r = rec.y, slot0 = rec.z;
+    const int nrows = rec.w;
     const int j0 = jg * p.rank_block;
     if (a < 0 || j0 >= r || nrows <= 0) return;
     const int nj = min(p.rank_block, r - j0);
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
 }  // namespace
 
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    const long grid = (long)a.max_units * a.rank_groups * a.row_split + a.pack_wgs;
+    const long grid = (long)a.max_units * a.rank_groups + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
     const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;

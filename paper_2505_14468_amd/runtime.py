@@ -124,7 +124,7 @@ class Plan:
 
     def to_host(self, ctx: Context) -> dict:
         status, n_seg = self.status(ctx)
-        out = dict(status=status, n_seg=n_seg)
+        out = dict(status=status, n_seg=n_seg, unit_rows=int(self.struct.unit_rows))
         if status != 0:
             return out
         T = self.T

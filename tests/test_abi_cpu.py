@@ -38,7 +38,7 @@ def test_status_codes_match_header():
 def test_struct_layouts_match_c():
     # sizes as a C compiler lays the header's structs out on x86-64
     assert C.sizeof(B.lora_adapter_table_t) == 32
-    assert C.sizeof(B.lora_plan_t) == 8 + 6 * 4 + 12 * 8
+    assert C.sizeof(B.lora_plan_t) == 8 + 7 * 4 + 4 + 12 * 8  # (4 bytes of padding before the pointers)
     assert C.sizeof(B.lora_linear_desc) == 16 + 6 * 8 + 8 + 8 + 8
 
 
@@ -91,7 +91,7 @@ def test_lora_plan_validates_before_touching_the_gpu():
 
 def _fake_plan(T=4, n_adapters=2, r_max=16):
     p = B.lora_plan_t()
-    p.T, p.n_req, p.n_adapters, p.r_max, p.magic = T, 1, n_adapters, r_max, 0x4C6F5241
+    p.T, p.n_req, p.n_adapters, p.r_max, p.magic, p.unit_rows = T, 1, n_adapters, r_max, 0x4C6F5241, 16
     p.scalars = 256  # never dereferenced on the host
     return p
 
@@ -123,6 +123,9 @@ def test_lora_linear_validates_before_touching_the_gpu():
     bad = _fake_plan()
     bad.magic = 1
     d = B.make_linear_desc(B.LORA_DTYPE_BF16, 64, 64, 4096, 64, 8192, 64, 16384, 64, None, 65536, ws_bytes)
+    assert B.lora_linear(None, bad, d, None, raw=True) == B.LORA_ERR_PLAN
+    bad = _fake_plan()
+    bad.unit_rows = 32  # a work-unit size no plan kernel writes
     assert B.lora_linear(None, bad, d, None, raw=True) == B.LORA_ERR_PLAN
     tbl = B.make_adapter_table(1, 512, 512, 512)  # fewer slots than the plan was built for
     assert run(tbl=tbl) == B.LORA_ERR_INVALID_ARG

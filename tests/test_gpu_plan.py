@@ -32,15 +32,18 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1, plan_variant=-1):
     assert np.array_equal(got["row_adapter"], np.repeat(ids, L))
     # derived tables: shrink work list and one record per 8 ranks
     rows = np.diff(ref["seg_indptr"])
-    units = np.where(ref["seg_adapter"] >= 0, (rows + 63) // 64, 0)
+    ur = got["unit_rows"]  # 16 for plans of few rows and segments (they then fill more of the chip), else 64
+    seg_bound = min(len(ids), len(ranks), int(L.sum()))
+    assert ur == (16 if int(L.sum()) // 16 + seg_bound <= 256 else 64)  # (256 CUs)
+    units = np.where(ref["seg_adapter"] >= 0, (rows + ur - 1) // ur, 0)
     assert np.array_equal(got["seg_unit"], np.concatenate([[0], np.cumsum(units)]))
     want_units = []
     for s in range(ref["n_seg"]):
         if ref["seg_adapter"][s] < 0:
             continue
-        for slot0 in range(int(ref["seg_indptr"][s]), int(ref["seg_indptr"][s + 1]), 64):
+        for slot0 in range(int(ref["seg_indptr"][s]), int(ref["seg_indptr"][s + 1]), ur):
             want_units.append([int(ref["seg_adapter"][s]), int(ref["seg_rank"][s]), slot0,
-                               min(64, int(ref["seg_indptr"][s + 1]) - slot0)])
+                               min(ur, int(ref["seg_indptr"][s + 1]) - slot0)])
     assert got["unit_rec"].tolist() == want_units
     rec = got["ext_rec"]
     q = 0
