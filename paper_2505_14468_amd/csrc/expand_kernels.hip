@@ -232,8 +232,12 @@ __device__ __forceinline__ void expand_unit_whole(const ExpandArgs &p, const E *
     }
 }
 
-template <typename E>
-__global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
+// SMALL: every unit of the plan has at most 16 rows.  That instantiation keeps a quarter of the accumulators and
+// half the loads in flight, fits 128 registers (4 waves per SIMD), and two workgroups share a CU: a unit of a few
+// rows is a chain of dependent round trips (work list, row map and adapter table, operands) more than it is a
+// stream, and one workgroup's chain overlaps the other's loads.
+template <typename E, bool SMALL>
+__global__ __launch_bounds__(kExWaves * 64, SMALL ? 4 : 2) void expand_kernel(ExpandArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     LORA_TS(p.trace, 0);
     const int unit = blockIdx.x / p.col_groups;
@@ -257,7 +261,12 @@ __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
     }
     const int rchunks = r / Elem<E>::CE;
     if ((cg + 1) * kExCols <= p.N && rchunks <= 16) {  // a whole column group, at most 4 MFMA steps along the rank
-        if (nrows <= 16) {
+        if constexpr (SMALL) {
+            if (rchunks <= 8)
+                expand_unit_whole<E, 1, 2, 8>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+            else
+                expand_unit_whole<E, 1, 4, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
+        } else if (nrows <= 16) {
             if (rchunks <= 8)
                 expand_unit_whole<E, 1, 2, 8>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
             else
@@ -268,7 +277,7 @@ __global__ __launch_bounds__(kExWaves * 64) void expand_kernel(ExpandArgs p) {
             else
                 expand_unit_whole<E, 4, 4, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
         }
-    } else if (nrows <= 16) {
+    } else if (SMALL || nrows <= 16) {
         expand_unit<E, 1>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
     } else {
         expand_unit<E, 4>(p, Ba, r, slot0, nrows, cg * kExCols, smem);
@@ -289,24 +298,34 @@ hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, co
     a.col_groups = (a.N + kExCols - 1) / kExCols;
     const long grid = (long)a.max_units * a.col_groups;
     const size_t smem = expand_smem_bytes(a.r_max, dtype);
-    static size_t attr_bytes[2] = {0, 0};  // more than the default 64 KB of dynamic LDS (ranks above ~480)
-    if (smem > 64 * 1024 && smem > attr_bytes[dtype == 1]) {
-        const void *fn = dtype == 1 ? reinterpret_cast<const void *>(expand_kernel<__bf16>)
-                                    : reinterpret_cast<const void *>(expand_kernel<float>);
+    const bool small = a.unit_rows <= kShrinkRowsSmall;
+    const void *fn = dtype == 1 ? (small ? reinterpret_cast<const void *>(expand_kernel<__bf16, true>)
+                                         : reinterpret_cast<const void *>(expand_kernel<__bf16, false>))
+                                : (small ? reinterpret_cast<const void *>(expand_kernel<float, true>)
+                                         : reinterpret_cast<const void *>(expand_kernel<float, false>));
+    static size_t attr_bytes[4] = {0, 0, 0, 0};  // more than the default 64 KB of dynamic LDS (ranks above ~480)
+    size_t &have = attr_bytes[(dtype == 1 ? 2 : 0) + (small ? 1 : 0)];
+    if (smem > 64 * 1024 && smem > have) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_bytes[dtype == 1] = smem;
+        have = smem;
     }
+    auto launch = [&](const ExpandArgs &b) {
+        const dim3 g((unsigned)grid), t(kExWaves * 64);
+        if (dtype == 1)
+            return small ? launch_kernel(expand_kernel<__bf16, true>, g, t, smem, stream, timer, b)
+                         : launch_kernel(expand_kernel<__bf16, false>, g, t, smem, stream, timer, b);
+        return small ? launch_kernel(expand_kernel<float, true>, g, t, smem, stream, timer, b)
+                     : launch_kernel(expand_kernel<float, false>, g, t, smem, stream, timer, b);
+    };
 #ifdef LORA_TRACE
     return trace_launch("expand", grid, [&](long long *buf) {
         ExpandArgs b = a;
         b.trace = buf;
-        if (dtype == 1) return launch_kernel(expand_kernel<__bf16>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, b);
-        return launch_kernel(expand_kernel<float>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, b);
+        return launch(b);
     });
 #else
-    if (dtype == 1) return launch_kernel(expand_kernel<__bf16>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
-    return launch_kernel(expand_kernel<float>, dim3((unsigned)grid), dim3(kExWaves * 64), smem, stream, timer, a);
+    return launch(a);
 #endif
 }
 

@@ -168,6 +168,7 @@ struct ExpandArgs {
     int32_t N;
     int32_t max_units;     // upper bound of work units (grid = max_units * col_groups)
     int32_t col_groups;    // set by the launcher: ceil(N / columns per workgroup)
+    int32_t unit_rows;     // most rows of a work unit in this plan (16 or 64)
     long long *trace = nullptr;  // phase stamps (trace builds only)
 };
 hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);

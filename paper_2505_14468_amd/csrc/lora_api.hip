@@ -519,6 +519,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
         const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
         e.max_units = (int32_t)(plan->T / plan->unit_rows + seg_bound2);  // as for the shrink grid
+        e.unit_rows = plan->unit_rows;
         e.col_groups = 0;
         LORA_HIP(launch_expand(e, d->dtype, stream, timed ? &first : nullptr));
         a.B = nullptr;
