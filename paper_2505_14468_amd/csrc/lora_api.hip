@@ -149,7 +149,8 @@ PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_m
     L.seg_rank = take((size_t)L.seg_cap);
     L.seg_ext = take((size_t)L.seg_cap + 1);
     L.seg_unit = take((size_t)L.seg_cap + 1);
-    L.unit_rec = take(((size_t)T / kShrinkRowsSmall + (size_t)L.seg_cap) * 4);  // (room for either unit size)
+    // (room for either unit size, and for the shrink grid, padded to eight units, to read the records of its padding)
+    L.unit_rec = take(((size_t)T / kShrinkRowsSmall + (size_t)L.seg_cap + 8) * 4);
     L.ext_rec = take((size_t)L.ext_cap * 4);
     L.scalars = take(8);
     L.total_bytes = off * sizeof(int32_t);

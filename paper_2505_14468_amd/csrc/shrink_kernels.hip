@@ -338,12 +338,17 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     // round trip to memory in a kernel that lasts a few of them: loads that do not depend on each other
     // are issued together.  The grid is an upper bound of the unit count and the work list is that
     // long, so the record can be read before the unit is known to exist.
-    // The unit index runs fastest over the grid: consecutive workgroups go to the eight XCDs in turn, and the rank
-    // blocks that often have nothing to do (those past a small adapter's rank) must not all land on the same XCDs
-    // while the others hold every unit with work.
+    // Grid order, chosen from the plan's totals (read in the same round trip as the work-list records of both
+    // orders).  Adapters mostly of full rank (sum of the used ranks >= 3/4 of segments x r_max): the rank blocks of
+    // a unit next to each other -- they read the same rows of X, and run at the same time.  Otherwise the unit index
+    // fastest: the rank blocks past a small adapter's rank have nothing to do and exit at once, and with them
+    // interleaved (period = rank_groups, a divisor of the eight XCDs the workgroups go to in turn) every unit with
+    // work sits on the same XCDs and in the grid's second round.
     const int bid = blockIdx.x - p.pack_wgs;
-    const int unit = bid % p.max_units;
-    const int jg = bid / p.max_units;
+    const int mu8 = (p.max_units + 7) / 8 * 8;
+    const int unit_a = bid % mu8, unit_b = bid / p.rank_groups;
+    const int4 rec_a = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit_a];
+    const int4 rec_b = p.rank_groups > 1 ? reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit_b] : rec_a;
     // Guessed ahead, in the same round trip as the record: lane i reads entry i of the adapter tables and of the
     // row map.  A decode batch (at most 64 rows, a pool of at most 64 adapters) finds everything it needs there
     // and skips the second round trip.
@@ -351,9 +356,13 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     const void *a_guess = lane < p.n_adapters ? p.A[lane] : nullptr;
     const float s_guess = lane < p.n_adapters ? p.scale[lane] : 0.f;
     const int perm_guess = lane < p.T ? p.plan.perm[lane] : 0;
-    const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
     const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
-    if (status != 0 || unit >= n_units) return;
+    const int n_seg = p.plan.scalars[kScNSeg], ext_total = p.plan.scalars[kScExtTotal];
+    const bool full_ranks = p.rank_groups > 1 && (long long)ext_total * 4 >= 3ll * p.r_max * n_seg;
+    const int unit = full_ranks ? unit_b : unit_a;
+    const int jg = full_ranks ? bid % p.rank_groups : bid / mu8;
+    const int4 rec = full_ranks ? rec_b : rec_a;
+    if (status != 0 || unit >= n_units) return;  // (n_units <= max_units: the grid's padding to eight units ends here too)
     LORA_TS(p.trace, 1);  // work-list record read
 
     // the plan's work list names the unit: adapter, rank, first slot, rows (one load, no search)
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
 }  // namespace
 
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    const long grid = (long)a.max_units * a.rank_groups + a.pack_wgs;
+    const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
     const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;
