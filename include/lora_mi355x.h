@@ -114,7 +114,7 @@ typedef struct lora_plan_t {
     const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
     const int32_t *seg_ext;     /* device [seg_cap+1] exclusive prefix sum of seg_rank      */
     const int32_t *seg_unit;    /* device [seg_cap+1] prefix sum of ceil(rows/unit_rows) (work list) */
-    const int32_t *unit_rec;    /* device [(T/16+seg_cap)*4] work units: adapter, rank, first slot, rows */
+    const int32_t *unit_rec;    /* device [(T/16+seg_cap+8)*4] work units: adapter, rank (| 1<<16: segment of >= 64 rows), first slot, rows */
     const int32_t *ext_rec;     /* device [ext_cap*4] per 8 ranks: adapter, rank<<16|j0, slot_lo, slot_hi */
     const int32_t *tok_off;     /* device [n_req+1]  first row of every request             */
     int32_t *scalars;           /* device [8]: n_seg, status, ext_total, n_units, ...       */

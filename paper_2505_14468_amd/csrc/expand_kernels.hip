@@ -246,8 +246,9 @@ __global__ __launch_bounds__(kExWaves * 64, SMALL ? 4 : 2) void expand_kernel(Ex
     const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
     const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
     if (status != 0 || unit >= n_units) return;
-    const int a = rec.x, r = rec.y, slot0 = rec.z, nrows = rec.w;
+    const int a = rec.x, r = rec.y & 0xffff, slot0 = rec.z, nrows = rec.w;
     if (a < 0 || r <= 0 || nrows <= 0) return;
+    if (p.skip_long && (rec.y & kUnitLongFlag)) return;  // the GEMM computes this segment's term itself
     const E *Ba = static_cast<const E *>(p.B[a]);
     LORA_TS(p.trace, 1);  // work-list record read
     if (Ba == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing

@@ -44,6 +44,8 @@ struct ExtTable {
     int j[kTabCap];            // column offset inside V / B_a
     int lo[kTabCap];           // tile-relative rows [lo, hi) that belong to the adapter
     int hi[kTabCap];
+    int live[kTabCap / 8];     // stage (8 chunk columns) has a column in use
+    unsigned char use_d[256];  // tile row takes its adapter term from D (the expand kernel's result)
 };
 
 template <typename E, int BM, int BN, int WM, int WN>
@@ -55,6 +57,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     constexpr int XL = BM * 8 / NT, WL = BN * 8 / NT;  // 16-byte loads per thread per stage
     constexpr int RPP = NT / 8;                        // rows covered per load pass
     static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
+    static_assert(kTabCap % NT == 0 && BM <= 256, "extension table layout");
     // On 4 waves (up to 512 registers each) the base product runs as a deeper software pipeline, with two
     // register sets of staged operands; on 8 waves the second set does not fit beside a 256x256 tile.
     constexpr bool DEEP = XL + WL >= 4 && WM * WN <= 4;
@@ -114,14 +117,28 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         pend = p.plan.seg_ext[s_last + 1];
     }
     const int ext_chunks = (pend - pbeg) / CE;
+    // Which rows take their adapter term from D: those with an adapter -- of a short segment only, when the long
+    // segments' term is computed here (long_rows > 0).  Read in the epilogue.
+    if (p.D != nullptr) {
+        for (int r = tid; r < BM; r += NT) {
+            const int s = p.plan.row_seg[min(m0 + r, p.T - 1)];
+            const bool lng = p.long_rows > 0 && p.plan.seg_indptr[s + 1] - p.plan.seg_indptr[s] >= p.long_rows;
+            tab->use_d[r] = p.plan.seg_adapter[s] >= 0 && !lng;
+        }
+    }
 
     auto build_table = [&](int chunk0) {
         for (int idx = tid; idx < kTabCap; idx += NT) {
             const int pe = pbeg + (chunk0 + idx) * CE;
             const void *ptr = nullptr;
             int r = 0, j = 0, lo = INT_MAX, hi = INT_MIN;
-            if (pe < pend) {
-                const int4 rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[pe >> 3];
+            bool wanted = pe < pend;
+            int4 rec = make_int4(-1, 0, 0, 0);
+            if (wanted) {
+                rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[pe >> 3];
+                wanted = rec.w - rec.z >= p.long_rows;  // (short segments' term comes in D when long_rows > 0)
+            }
+            if (wanted) {
                 const E *b = rec.x >= 0 ? static_cast<const E *>(p.B[rec.x]) : nullptr;
                 if (b != nullptr) {
                     r = rec.y >> 16;
@@ -138,6 +155,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             tab->j[idx] = j;
             tab->lo[idx] = lo;
             tab->hi[idx] = hi;
+            // (kTabCap is a multiple of the workgroup size: whole waves get here, 8 consecutive lanes = one stage)
+            const unsigned long long used = __builtin_amdgcn_ballot_w64(ptr != nullptr);
+            if ((lane & 7) == 0) tab->live[idx >> 3] = ((used >> (lane & 56)) & 0xffull) != 0ull;
         }
     };
     if (ext_chunks > 0) build_table(0);  // visible after the first barrier of the base loop
@@ -301,6 +321,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
         }
     };
+    // stages of the extension table without a column in use (segments whose term comes in D, adapters no longer
+    // resident) are skipped whole
+    auto next_live = [&](int se, int nst) {
+        while (se < nst && tab->live[se] == 0) ++se;
+        return se;
+    };
+    int ext_first = 0;
+    bool ext_loaded = false;
     // (stage 1 was requested by every wave before the loop)
     int kt = 0;
     if constexpr (DEEP) {
@@ -386,9 +414,23 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             stage_deep(kt, xr2, wr2, xr, wr, true, true, false);  // (stage 1 came into the first set before the loop)
             stage_deep(kt + 1, xr, wr, xr2, wr2, true, true, false);
         }
+        // The last stage loads and stores nothing, so both register sets are free: the first extension stage in
+        // use is requested in front of it and arrives while it is multiplied.
+        auto prefetch_ext = [&]() __attribute__((always_inline)) {
+            if (ext_chunks > 0) {
+                const int nst0 = (min(ext_chunks, kTabCap) + 7) >> 3;
+                ext_first = next_live(0, nst0);
+                ext_loaded = ext_first < nst0;
+                if (ext_loaded) load_ext(ext_first);
+            }
+        };
         for (; kt < KT; kt += 2) {
+            if (kt + 1 == KT) prefetch_ext();
             stage_deep(kt, xr2, wr2, xr, wr, kt + 1 < KT, kt + 2 < KT, kt + 2 >= KT_full);
-            if (kt + 1 < KT) stage_deep(kt + 1, xr, wr, xr2, wr2, kt + 2 < KT, kt + 3 < KT, kt + 3 >= KT_full);
+            if (kt + 1 < KT) {
+                if (kt + 2 == KT) prefetch_ext();
+                stage_deep(kt + 1, xr, wr, xr2, wr2, kt + 2 < KT, kt + 3 < KT, kt + 3 >= KT_full);
+            }
         }
     } else if (KT_full > 2) {
         stage(0, true, true, false, false, false);
@@ -404,15 +446,21 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             __syncthreads();
         }
         const int nst = (min(ext_chunks - chunk0, kTabCap) + 7) >> 3;
-        load_ext(0);
-        store_stage_ext(0, 0);
-        __syncthreads();
-        for (int se = 0; se < nst; ++se) {
-            const bool more = se + 1 < nst;
-            if (more) load_ext(se + 1);
-            compute(se & 1, se);
-            if (more) store_stage_ext((se + 1) & 1, se + 1);
+        int se = chunk0 == 0 && ext_loaded ? ext_first : next_live(0, nst), buf = 0;
+        if (se < nst) {
+            if (!(chunk0 == 0 && ext_loaded)) load_ext(se);
+            store_stage_ext(0, se);
             __syncthreads();
+        }
+        while (se < nst) {
+            const int nx = next_live(se + 1, nst);
+            const bool more = nx < nst;
+            if (more) load_ext(nx);
+            compute(buf, se);
+            if (more) store_stage_ext(buf ^ 1, nx);
+            __syncthreads();
+            se = nx;
+            buf ^= 1;
         }
     }
 
@@ -433,7 +481,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         float term[2][NBN][16];
         auto row_of = [&](int tb) { return p.plan.perm[min(m0 + wm0 + tb * 32 + l31, p.T - 1)]; };
         auto fetch = [&](int tb, int row, float (&d)[NBN][16]) {
-            const float *drow = p.plan.row_adapter[row] >= 0 ? p.D + (int64_t)row * p.ldd : nullptr;
+            const float *drow = tab->use_d[wm0 + tb * 32 + l31] ? p.D + (int64_t)row * p.ldd : nullptr;
 #pragma unroll
             for (int nb = 0; nb < NBN; ++nb) load_term_tile(drow, p.D, n0 + wn0 + nb * 32, lh, (int)p.ldd, d[nb]);
         };

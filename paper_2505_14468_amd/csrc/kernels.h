@@ -149,9 +149,11 @@ struct GemmArgs {
     int64_t ldy;
     const void *V;         // [T, r_max] of E, original row order (null when no adapters)
     const void *Xpack;     // fragment-major copy of X (decode-sized kernel only)
-    const void *const *B;  // device table (null when no adapters, or when the adapter term comes in D)
+    const void *const *B;  // device table (null when no adapters, or when all of the adapter term comes in D)
     const float *D;        // adapter term in fp32, [T, ldd], original row order, rows with an adapter only (null = none)
     int64_t ldd;
+    int32_t long_rows = 0;  // > 0 (with B and D both set): D holds the term of segments shorter than this only,
+                            // the tiled GEMM computes the others' as extension stages
     int32_t r_max;
     int32_t T, K, N;
     long long *trace = nullptr;  // phase stamps (trace builds only)
@@ -169,6 +171,7 @@ struct ExpandArgs {
     int32_t max_units;     // upper bound of work units (grid = max_units * col_groups)
     int32_t col_groups;    // set by the launcher: ceil(N / columns per workgroup)
     int32_t unit_rows;     // most rows of a work unit in this plan (16 or 64)
+    int32_t skip_long;     // 1: units of long segments (kUnitLongFlag) are left to the GEMM
     long long *trace = nullptr;  // phase stamps (trace builds only)
 };
 hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);

@@ -522,9 +522,19 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         e.max_units = (int32_t)(plan->T / plan->unit_rows + seg_bound2);  // as for the shrink grid
         e.unit_rows = plan->unit_rows;
         e.col_groups = 0;
+        // The tiled GEMM keeps the long segments' term to itself (an extension stage per 64 ranks of each such segment
+        // of an M tile, ~2 us each, against 8 bytes of D traffic per element and the units' reads of B_a saved: worth
+        // it up to rank 64 -- C3 gate_proj 150 -> 140 us; at rank 128, C4, 428 -> 434 us) and takes the short
+        // segments' from D; the other kernels take all of it from D.
+        const bool tiled = !(c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) && plan->r_max <= 64;
+        e.skip_long = tiled ? 1 : 0;
         LORA_HIP(launch_expand(e, d->dtype, stream, timed ? &first : nullptr));
-        a.B = nullptr;
-        a.V = nullptr;
+        if (tiled) {
+            a.long_rows = kLongSegRows;
+        } else {
+            a.B = nullptr;
+            a.V = nullptr;
+        }
         a.D = e.D;
         a.ldd = e.ldd;
     }

@@ -163,7 +163,7 @@ __device__ void fill_units(const PlanBuildArgs &p, int start, int stride) {
         const int slot0 = p.seg_indptr[s] + (u - p.seg_unit[s]) * p.unit_rows;
         int4 rec;
         rec.x = p.seg_adapter[s];
-        rec.y = p.seg_rank[s];
+        rec.y = p.seg_rank[s] | (p.seg_indptr[s + 1] - p.seg_indptr[s] >= kLongSegRows ? kUnitLongFlag : 0);
         rec.z = slot0;
         rec.w = min(p.unit_rows, p.seg_indptr[s + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
@@ -582,7 +582,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
-        rec.y = s_srk[lo];
+        rec.y = s_srk[lo] | (s_sip[lo + 1] - s_sip[lo] >= kLongSegRows ? kUnitLongFlag : 0);
         rec.z = slot0;
         rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
@@ -819,7 +819,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
         const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
-        rec.y = s_srk[lo];
+        rec.y = s_srk[lo] | (s_sip[lo + 1] - s_sip[lo] >= kLongSegRows ? kUnitLongFlag : 0);
         rec.z = slot0;
         rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;
@@ -1107,7 +1107,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p)
         const int slot0 = s_sip[lo] + (u - s_sun[lo]) * p.unit_rows;
         int4 rec;
         rec.x = s_sad[lo];
-        rec.y = s_srk[lo];
+        rec.y = s_srk[lo] | (s_sip[lo + 1] - s_sip[lo] >= kLongSegRows ? kUnitLongFlag : 0);
         rec.z = slot0;
         rec.w = min(p.unit_rows, s_sip[lo + 1] - slot0);
         reinterpret_cast<int4 *>(p.unit_rec)[u] = rec;

@@ -366,7 +366,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     LORA_TS(p.trace, 1);  // work-list record read
 
     // the plan's work list names the unit: adapter, rank, first slot, rows (one load, no search)
-    const int a = rec.x, r = rec.y, slot0 = rec.z;
+    const int a = rec.x, r = rec.y & 0xffff, slot0 = rec.z;
     const int nrows = rec.w;
     const int j0 = jg * p.rank_block;
     if (a < 0 || j0 >= r || nrows <= 0) return;

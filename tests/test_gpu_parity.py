@@ -91,6 +91,36 @@ def test_separate_expand_kernel_ragged(dtype):
     reset_options()
 
 
+@pytest.mark.parametrize("variant", ["tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256", "tile_256x256w4", "tile_128x192",
+                                     "tile_256x192", "tile_256x224", "pipe_128x128_w4"])
+def test_long_segments_in_the_gemm_short_ones_in_the_expand_kernel(variant):
+    """Ranks up to 64 with the separate expand kernel on: the tiled GEMM computes the term of segments of 64 rows
+    and more itself and adds the expand kernel's result for the shorter ones (the other GEMM kernels take all of
+    it from the expand kernel).  Segments of exactly 63 and 64 rows, one spanning several M tiles, single rows,
+    rows without an adapter, an adapter that is resident but unused; plans of 16-row and of 64-row units."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, TOL
+    for dtype in ("bf16", "f32"):
+        for case, (ids, L) in enumerate([
+                # few requests: T/16 + segments fits the CUs -> 16-row units
+                ([3, 0, -1, 5, 3, 1, 6, 2, 5, 3, 0, 4, -1, 6], [150, 1, 9, 64, 150, 63, 1, 17, 0, 141, 2, 5, 30, 1]),
+                # many one-row requests around two long segments -> 64-row units
+                ([2] * 70 + list(np.arange(400) % 7) + [-1] * 33 + [4] * 30, [30] * 70 + [1] * 400 + [1] * 33 + [80] * 30)]):
+            wl = make_custom(seed=910 + case, dtype=dtype, K=200, N=1100, ranks=(8, 16, 64, 40, 8, 24, 32, 48),
+                             scales=(2.0, 0.5, 1.0, 0.25, 1.5, 1.0, 0.75, 1.0), req_adapter=np.asarray(ids), req_ntok=np.asarray(L),
+                             name=f"hybrid_{variant}_{dtype}_{case}")
+            assert wl.T > 256 and (wl.T // 16 + 8 > 256) == bool(case)
+            out = {}
+            ctx().set_option("gemm_variant", VARIANTS[variant])
+            for split in (1, 0):
+                ctx().set_option("expand_split", split)
+                out[split] = gpu_linear(wl, device_plan=bool(case))
+                e = check_against_oracle(wl, out[split])
+            rms = float(np.sqrt((out[0] ** 2).mean()))
+            assert float(np.abs(out[0] - out[1]).max()) <= TOL[dtype] * rms
+            print(f"{wl.name}: T={wl.T} err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
 def test_skinny_kernel_row_counts(T):
     """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""

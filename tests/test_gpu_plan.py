@@ -42,7 +42,8 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1, plan_variant=-1):
         if ref["seg_adapter"][s] < 0:
             continue
         for slot0 in range(int(ref["seg_indptr"][s]), int(ref["seg_indptr"][s + 1]), ur):
-            want_units.append([int(ref["seg_adapter"][s]), int(ref["seg_rank"][s]), slot0,
+            long_flag = 0x10000 if int(ref["seg_indptr"][s + 1]) - int(ref["seg_indptr"][s]) >= 64 else 0
+            want_units.append([int(ref["seg_adapter"][s]), int(ref["seg_rank"][s]) | long_flag, slot0,
                                min(ur, int(ref["seg_indptr"][s + 1]) - slot0)])
     assert got["unit_rec"].tolist() == want_units
     rec = got["ext_rec"]
