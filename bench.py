@@ -39,13 +39,71 @@ def _layer_variant(wl, layer):
     return w2
 
 
+def _whole_layer(args, wl, B, rt, torch, np):
+    """--proj -1: one step = one plan + ``lora_linear`` for every projection of the workload (config 3: the seven
+    projections of a decoder layer, each with its own X, as the workload defines them); a side measurement
+    with per-projection times, not the line the default run prints."""
+    ctx = rt.Context(0)
+    for opt in args.option:
+        name, val = opt.split("=")
+        ctx.set_option(name, int(val))
+    dev, T, r_max = ctx.device, wl.T, wl.r_max
+    tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    req_adapter = torch.from_numpy(np.ascontiguousarray(wl.req_adapter)).to(dev)
+    req_ntok = torch.from_numpy(np.ascontiguousarray(wl.req_ntok)).to(dev)
+    ranks = torch.from_numpy(np.ascontiguousarray(wl.ranks)).to(dev)
+    plan_bytes = B.lora_plan_bytes(wl.n_req, T, wl.n_adapters, r_max)
+    plan_buf = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
+    plan0 = rt.plan_device(ctx, req_adapter, req_ntok, ranks, r_max, T, buf=plan_buf)
+    keep, descs = [], []
+    for q, pr in enumerate(wl.projections):
+        X, W0, table = rt.upload_workload(wl, q, dev)
+        Y = torch.empty((T, pr.N), dtype=tdtype, device=dev)
+        ws = rt.workspace(T, pr.K, pr.N, r_max, tdtype, dev)
+        keep.append((X, W0, table, Y, ws))
+        descs.append(rt.linear_desc(plan0, X, W0, Y, table, ws))
+    h, stream = ctx.handle, int(torch.cuda.current_stream().cuda_stream)
+    ra_p, rn_p, rk_p, pb_p = req_adapter.data_ptr(), req_ntok.data_ptr(), ranks.data_ptr(), plan_buf.data_ptr()
+
+    def step(_):
+        plan = B.lora_plan_device(h, ra_p, rn_p, wl.n_req, rk_p, wl.n_adapters, r_max, T, pb_p, plan_bytes, stream)
+        for d in descs:
+            B.lora_linear(h, plan, d, stream)
+
+    def timed(fn, k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(k):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / k
+
+    for i in range(args.warmup):
+        step(i)
+    status, n_seg = plan0.status(ctx)
+    assert status == 0, f"plan status {status}"
+    sec = timed(step, args.steps)
+    per_proj = {pr.name: round(timed(lambda i, d=d: B.lora_linear(h, plan0.struct, d, stream), max(10, args.steps // 4)) * 1e3, 5)
+                for pr, d in zip(wl.projections, descs)}
+    flops = sum(wl.useful_flops(q) for q in range(len(wl.projections)))
+    print(json.dumps({
+        "metric": "multi-LoRA linear TFLOP/s + adapter-path GB/s (roofline %), ms/layer", "value": round(flops / sec / 1e12, 3),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}:all_projections", "tokens": T, "requests": wl.n_req, "adapters_resident": wl.n_adapters,
+                   "segments": n_seg, "rank_max": r_max, "step": f"lora_plan_device + {len(descs)} x lora_linear"},
+        "ms_per_layer_by_projection": per_proj, "roofline": None, "cpu_baseline": None}))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=1, help="workload: index into BASELINE.json configs (default 1)")
-    ap.add_argument("--proj", type=int, default=0, help="projection of a multi-projection workload (config 3)")
+    ap.add_argument("--proj", type=int, default=0,
+                    help="projection of a multi-projection workload (config 3); -1 = all of them in one step, with one plan")
     ap.add_argument("--same-adapter", type=int, default=0, metavar="ROWS",
                     help="instead of --config: ROWS single-token requests on ONE adapter at config 1's shape "
                          "(one function's own batch, the regime of the paper's section 6)")
@@ -77,6 +135,9 @@ def main():
     from workloads import make_workload, same_adapter_decode, to_f64
 
     wl = same_adapter_decode(args.same_adapter) if args.same_adapter > 0 else make_workload(args.config)
+    if args.proj < 0:
+        _whole_layer(args, wl, B, rt, torch, np)
+        return
     p = args.proj
     pr = wl.projections[p]
     K, N, T = pr.K, pr.N, wl.T
