@@ -44,7 +44,7 @@ struct ExtTable {
     int j[kTabCap];            // column offset inside V / B_a
     int lo[kTabCap];           // tile-relative rows [lo, hi) that belong to the adapter
     int hi[kTabCap];
-    int live[kTabCap / 8];     // stage (8 chunk columns) has a column in use
+    int cnt[kTabCap / 64];     // columns in use per wave-sized piece of a batch (while the table is built)
     unsigned char use_d[256];  // tile row takes its adapter term from D (the expand kernel's result)
 };
 
@@ -127,11 +127,20 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         }
     }
 
-    auto build_table = [&](int chunk0) {
-        for (int idx = tid; idx < kTabCap; idx += NT) {
+    // One batch of the table: the chunk columns [chunk0, chunk0 + kTabCap) of the tile's extension axis, those in
+    // use (a resident adapter; a long segment, when the short ones' term comes in D) packed to the front in axis
+    // order -- a stage then holds 8 columns in use whatever the ranks in between add up to.  Returns their number.
+    // Two phases around a barrier: count per wave, then place.
+    auto build_table = [&](int chunk0) -> int {
+        constexpr int IT = kTabCap / NT, WV = NT / 64;
+        const void *e_ptr[IT];
+        int e_r[IT], e_j[IT], e_lo[IT], e_hi[IT];
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int idx = it * NT + tid;
             const int pe = pbeg + (chunk0 + idx) * CE;
-            const void *ptr = nullptr;
-            int r = 0, j = 0, lo = INT_MAX, hi = INT_MIN;
+            e_ptr[it] = nullptr;
+            e_r[it] = 0, e_j[it] = 0, e_lo[it] = INT_MAX, e_hi[it] = INT_MIN;
             bool wanted = pe < pend;
             int4 rec = make_int4(-1, 0, 0, 0);
             if (wanted) {
@@ -141,26 +150,48 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             if (wanted) {
                 const E *b = rec.x >= 0 ? static_cast<const E *>(p.B[rec.x]) : nullptr;
                 if (b != nullptr) {
-                    r = rec.y >> 16;
-                    j = (rec.y & 0xffff) + (pe & 7);
-                    lo = max(rec.z - m0, 0);
-                    hi = min(rec.w - m0, BM);
-                    ptr = b + j;
+                    e_r[it] = rec.y >> 16;
+                    e_j[it] = (rec.y & 0xffff) + (pe & 7);
+                    e_lo[it] = max(rec.z - m0, 0);
+                    e_hi[it] = min(rec.w - m0, BM);
+                    e_ptr[it] = b + e_j[it];
                 } else {
                     atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
                 }
             }
-            tab->ptr[idx] = ptr;
-            tab->r[idx] = r;
-            tab->j[idx] = j;
-            tab->lo[idx] = lo;
-            tab->hi[idx] = hi;
-            // (kTabCap is a multiple of the workgroup size: whole waves get here, 8 consecutive lanes = one stage)
-            const unsigned long long used = __builtin_amdgcn_ballot_w64(ptr != nullptr);
-            if ((lane & 7) == 0) tab->live[idx >> 3] = ((used >> (lane & 56)) & 0xffull) != 0ull;
+            const unsigned long long used = __builtin_amdgcn_ballot_w64(e_ptr[it] != nullptr);
+            if (lane == 0) tab->cnt[it * WV + wave] = __builtin_popcountll(used);
         }
+        __syncthreads();
+        int total = 0;
+#pragma unroll
+        for (int k = 0; k < IT * WV; ++k) total += tab->cnt[k];
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            int pos = 0;
+#pragma unroll
+            for (int k = 0; k < IT * WV; ++k) pos += k < it * WV + wave ? tab->cnt[k] : 0;
+            const unsigned long long used = __builtin_amdgcn_ballot_w64(e_ptr[it] != nullptr);
+            pos += __builtin_popcountll(used & ((1ull << lane) - 1ull));
+            if (e_ptr[it] != nullptr) {
+                tab->ptr[pos] = e_ptr[it];
+                tab->r[pos] = e_r[it];
+                tab->j[pos] = e_j[it];
+                tab->lo[pos] = e_lo[it];
+                tab->hi[pos] = e_hi[it];
+            }
+        }
+        if (tid < 8 && total + tid < ((total + 7) & ~7)) {  // the unused columns of the last stage
+            tab->ptr[total + tid] = nullptr;
+            tab->r[total + tid] = 0;
+            tab->j[total + tid] = 0;
+            tab->lo[total + tid] = INT_MAX;
+            tab->hi[total + tid] = INT_MIN;
+        }
+        return total;
     };
-    if (ext_chunks > 0) build_table(0);  // visible after the first barrier of the base loop
+    int ext_used = 0;  // columns in use in the current batch of the table
+    if (ext_chunks > 0) ext_used = build_table(0);  // visible after the first barrier of the base loop
 
     f32x16_t acc[NBN][NBT];
 #pragma unroll
@@ -321,13 +352,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
         }
     };
-    // stages of the extension table without a column in use (segments whose term comes in D, adapters no longer
-    // resident) are skipped whole
-    auto next_live = [&](int se, int nst) {
-        while (se < nst && tab->live[se] == 0) ++se;
-        return se;
-    };
-    int ext_first = 0;
     bool ext_loaded = false;
     // (stage 1 was requested by every wave before the loop)
     int kt = 0;
@@ -417,12 +441,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         // The last stage loads and stores nothing, so both register sets are free: the first extension stage in
         // use is requested in front of it and arrives while it is multiplied.
         auto prefetch_ext = [&]() __attribute__((always_inline)) {
-            if (ext_chunks > 0) {
-                const int nst0 = (min(ext_chunks, kTabCap) + 7) >> 3;
-                ext_first = next_live(0, nst0);
-                ext_loaded = ext_first < nst0;
-                if (ext_loaded) load_ext(ext_first);
-            }
+            ext_loaded = ext_used > 0;
+            if (ext_loaded) load_ext(0);
         };
         for (; kt < KT; kt += 2) {
             if (kt + 1 == KT) prefetch_ext();
@@ -442,25 +462,21 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // ---- extension: sum over the concatenated ranks of this tile's adapters -----------------------
     for (int chunk0 = 0; chunk0 < ext_chunks; chunk0 += kTabCap) {
         if (chunk0 > 0) {
-            build_table(chunk0);
+            ext_used = build_table(chunk0);
             __syncthreads();
         }
-        const int nst = (min(ext_chunks - chunk0, kTabCap) + 7) >> 3;
-        int se = chunk0 == 0 && ext_loaded ? ext_first : next_live(0, nst), buf = 0;
-        if (se < nst) {
-            if (!(chunk0 == 0 && ext_loaded)) load_ext(se);
-            store_stage_ext(0, se);
+        const int nst = (ext_used + 7) >> 3;
+        if (nst > 0) {
+            if (!(chunk0 == 0 && ext_loaded)) load_ext(0);
+            store_stage_ext(0, 0);
             __syncthreads();
         }
-        while (se < nst) {
-            const int nx = next_live(se + 1, nst);
-            const bool more = nx < nst;
-            if (more) load_ext(nx);
-            compute(buf, se);
-            if (more) store_stage_ext(buf ^ 1, nx);
+        for (int se = 0; se < nst; ++se) {
+            const bool more = se + 1 < nst;
+            if (more) load_ext(se + 1);
+            compute(se & 1, se);
+            if (more) store_stage_ext((se + 1) & 1, se + 1);
             __syncthreads();
-            se = nx;
-            buf ^= 1;
         }
     }
 
