@@ -121,6 +121,42 @@ def test_long_segments_in_the_gemm_short_ones_in_the_expand_kernel(variant):
     reset_options()
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_random_segment_mixes_fused_and_separate(seed):
+    """Random batches of long and short segments, ranks 8..64, with the adapter term fused, separate, and by the
+    built-in choice; in the fused runs an M tile of 256 rows holds up to ~150 adapters (more than 4096 ranks: the
+    extension table of a tile is built in more than one batch)."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, TOL
+    rng = np.random.default_rng(4000 + seed)
+    n_ad = 400
+    ranks = tuple(int(r) for r in rng.choice([8, 16, 24, 32, 48, 64], size=n_ad, p=[0.05, 0.05, 0.05, 0.1, 0.15, 0.6]))
+    scales = tuple(float(x) for x in rng.choice([0.25, 0.5, 1.0, 2.0], size=n_ad))
+    R = 800
+    ids = rng.integers(-1, n_ad, size=R)
+    L = rng.integers(0, 3, size=R)
+    for a in rng.choice(n_ad, size=3, replace=False):  # three adapters with long segments
+        k = rng.integers(0, R, size=4)
+        ids[k] = a
+        L[k] = rng.integers(20, 90, size=4)
+    dtype = "bf16" if seed % 2 == 0 else "f32"
+    # (sigma_b 0.01: with K this short the default would make the adapter term the larger half of Y, and the one
+    # rounding of V to bf16 then uses up the tolerance by itself)
+    wl = make_custom(seed=4100 + seed, dtype=dtype, K=136, N=520, ranks=ranks, scales=scales, req_adapter=ids, req_ntok=L,
+                     sigma_b=0.01, name=f"random_mix_{seed}")
+    assert wl.T > 600
+    out = {}
+    for variant in ("tile_256x224", "tile_128x192", None):
+        ctx().set_option("gemm_variant", VARIANTS[variant] if variant else -1)
+        for split in (0, 1, -1):
+            ctx().set_option("expand_split", split)
+            out[split] = gpu_linear(wl, device_plan=bool(seed & 1))
+            e = check_against_oracle(wl, out[split])
+        rms = float(np.sqrt((out[0] ** 2).mean()))
+        assert float(np.abs(out[0] - out[1]).max()) <= TOL[dtype] * rms
+    print(f"{wl.name}: T={wl.T} {dtype} err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
 def test_skinny_kernel_row_counts(T):
     """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""
