@@ -65,10 +65,32 @@ def _whole_layer(args, wl, B, rt, torch, np):
     h, stream = ctx.handle, int(torch.cuda.current_stream().cuda_stream)
     ra_p, rn_p, rk_p, pb_p = req_adapter.data_ptr(), req_ntok.data_ptr(), ranks.data_ptr(), plan_buf.data_ptr()
 
+    # --fuse: projections that read the same activations in a decoder layer (q, k, v; gate, up) go through one
+    # lora_linear_multi call each, on the first one's X
+    groups = [[q] for q in range(len(descs))]
+    if args.fuse:
+        names = [pr.name for pr in wl.projections]
+        groups, seen = [], set()
+        for fam in (("q_proj", "k_proj", "v_proj"), ("o_proj",), ("gate_proj", "up_proj"), ("down_proj",)):
+            g = [names.index(n) for n in fam if n in names]
+            if g:
+                groups.append(g)
+                seen.update(g)
+        groups += [[q] for q in range(len(descs)) if q not in seen]
+        for g in groups:
+            for q in g[1:]:
+                X0, (Xq, W0, table, Y, ws) = keep[g[0]][0], keep[q]
+                assert X0.shape == Xq.shape
+                keep[q] = (X0, W0, table, Y, ws)
+                descs[q] = rt.linear_desc(plan0, X0, W0, Y, table, ws)
+
     def step(_):
         plan = B.lora_plan_device(h, ra_p, rn_p, wl.n_req, rk_p, wl.n_adapters, r_max, T, pb_p, plan_bytes, stream)
-        for d in descs:
-            B.lora_linear(h, plan, d, stream)
+        for g in groups:
+            if len(g) == 1:
+                B.lora_linear(h, plan, descs[g[0]], stream)
+            else:
+                B.lora_linear_multi(h, plan, [descs[q] for q in g], stream)
 
     def timed(fn, k):
         torch.cuda.synchronize()
@@ -91,7 +113,8 @@ def _whole_layer(args, wl, B, rt, torch, np):
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}:all_projections", "tokens": T, "requests": wl.n_req, "adapters_resident": wl.n_adapters,
-                   "segments": n_seg, "rank_max": r_max, "step": f"lora_plan_device + {len(descs)} x lora_linear"},
+                   "segments": n_seg, "rank_max": r_max,
+                   "step": "lora_plan_device + " + " + ".join("lora_linear" if len(g) == 1 else f"lora_linear_multi({len(g)})" for g in groups)},
         "ms_per_layer_by_projection": per_proj, "roofline": None, "cpu_baseline": None}))
     ctx.close()
 
@@ -104,6 +127,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload: index into BASELINE.json configs (default 1)")
     ap.add_argument("--proj", type=int, default=0,
                     help="projection of a multi-projection workload (config 3); -1 = all of them in one step, with one plan")
+    ap.add_argument("--fuse", action="store_true",
+                    help="with --proj -1: q/k/v and gate/up share their activations and go through lora_linear_multi")
     ap.add_argument("--same-adapter", type=int, default=0, metavar="ROWS",
                     help="instead of --config: ROWS single-token requests on ONE adapter at config 1's shape "
                          "(one function's own batch, the regime of the paper's section 6)")

@@ -239,6 +239,21 @@ int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
  * PLAN, SHAPE, ALIGNMENT, WORKSPACE_TOO_SMALL; HIP if a launch fails. */
 int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
+/* Several projections of the SAME activations in one call -- fused QKV, gate + up
+ * of a decoder layer (all seven of which carry LoRA here): descs (HOST array
+ * of n HOST pointers, 1 <= n <= LORA_MAX_MULTI) share X, ldx, K, dtype and the
+ * plan; each has its own W0, N, Y, adapter table and workspace (of its own
+ * lora_linear_workspace_bytes[_preferred]).  Computes what n calls of
+ * lora_linear compute (same formula per projection; fp32 summation order may
+ * differ, as between tile shapes); for batches above 128 rows the base products
+ * run as one GEMM launch whose grid holds the column tiles of all projections.
+ * Errors: those of lora_linear for any desc; INVALID_ARG also for n out of
+ * range, descs that differ in X / ldx / K / dtype, or two descs with the same Y
+ * or workspace. */
+#define LORA_MAX_MULTI 4
+int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int32_t n,
+                      lora_stream_t stream);
+
 /* Profiling mode, for benchmarks: between lora_profile_begin() and
  * lora_profile_end() every kernel the library launches through `ctx` is
  * bracketed by its own pair of HIP events (at most max_launches per kernel

@@ -35,6 +35,7 @@ EXPORTS = [
     "lora_ctx_create", "lora_ctx_destroy", "lora_ctx_set_option",
     "lora_plan_validate", "lora_plan_bytes", "lora_plan", "lora_plan_device", "lora_plan_status",
     "lora_linear_workspace_bytes", "lora_linear_workspace_bytes_preferred", "lora_shrink", "lora_gemm_expand", "lora_linear",
+    "lora_linear_multi",
     "lora_profile_begin", "lora_profile_end",
     "lora_gemm_kernel_name", "lora_strerror", "lora_last_hip_error",
 ]
@@ -99,6 +100,8 @@ def lib():
         L.lora_linear_workspace_bytes_preferred.restype = C.c_size_t
         for name in ("lora_shrink", "lora_gemm_expand", "lora_linear"):
             getattr(L, name).argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(lora_linear_desc), C.c_void_p]
+        L.lora_linear_multi.argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(C.POINTER(lora_linear_desc)), C.c_int32,
+                                        C.c_void_p]
         L.lora_profile_begin.argtypes = [C.c_void_p, C.c_int]
         L.lora_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), i32p]
         L.lora_gemm_kernel_name.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
@@ -236,6 +239,20 @@ def lora_gemm_expand(ctx, plan, desc, stream: int, *, raw: bool = False):
 
 def lora_linear(ctx, plan, desc, stream: int, *, raw: bool = False):
     return _stage("lora_linear", ctx, plan, desc, stream, raw)
+
+
+LORA_MAX_MULTI = 4
+
+
+def lora_linear_multi(ctx, plan, descs, stream: int, *, raw: bool = False):
+    """descs: a sequence of lora_linear_desc that share X, ldx, K and dtype."""
+    n = len(descs)
+    arr = (C.POINTER(lora_linear_desc) * max(n, 1))(*[C.pointer(d) for d in descs])
+    st = lib().lora_linear_multi(C.c_void_p(ctx), C.byref(plan), arr, C.c_int32(n), C.c_void_p(stream))
+    if raw:
+        return st
+    _check(st, "lora_linear_multi")
+    return None
 
 
 PROFILE_KINDS = ("plan_segments", "plan_fill", "shrink", "gemm_expand")

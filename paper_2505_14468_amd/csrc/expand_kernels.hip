@@ -237,11 +237,26 @@ __device__ __forceinline__ void expand_unit_whole(const ExpandArgs &p, const E *
 // rows is a chain of dependent round trips (work list, row map and adapter table, operands) more than it is a
 // stream, and one workgroup's chain overlaps the other's loads.
 template <typename E, bool SMALL>
-__global__ __launch_bounds__(kExWaves * 64, SMALL ? 4 : 2) void expand_kernel(ExpandArgs p) {
+__global__ __launch_bounds__(kExWaves * 64, SMALL ? 4 : 2) void expand_kernel(ExpandArgs p0) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    LORA_TS(p.trace, 0);
-    const int unit = blockIdx.x / p.col_groups;
-    const int cg = blockIdx.x - unit * p.col_groups;
+    LORA_TS(p0.trace, 0);
+    // several projections of the same batch: the single-projection grids one after the other
+    ExpandArgs p = p0;
+    int bid = blockIdx.x;
+    if (p0.n_sets > 0) {
+        int si = 0;
+        while (si + 1 < p0.n_sets && bid >= p0.set[si + 1].block0) ++si;
+        bid -= p0.set[si].block0;
+        p.V = p0.set[si].V;
+        p.B = p0.set[si].B;
+        p.D = p0.set[si].D;
+        p.ldd = p0.set[si].ldd;
+        p.N = p0.set[si].N;
+        p.skip_long = p0.set[si].skip_long;
+        p.col_groups = (p.N + kExCols - 1) / kExCols;
+    }
+    const int unit = bid / p.col_groups;
+    const int cg = bid - unit * p.col_groups;
     // the grid is an upper bound of the unit count and the work list is that long
     const int4 rec = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit];
     const int status = p.plan.scalars[kScStatus], n_units = p.plan.scalars[kScNUnits];
@@ -294,10 +309,20 @@ size_t expand_smem_bytes(int r_max, int dtype) {
 }
 
 hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    if (a0.max_units <= 0 || a0.N <= 0) return hipSuccess;
+    if (a0.max_units <= 0 || (a0.n_sets == 0 && a0.N <= 0)) return hipSuccess;
     ExpandArgs a = a0;
-    a.col_groups = (a.N + kExCols - 1) / kExCols;
-    const long grid = (long)a.max_units * a.col_groups;
+    long grid;
+    if (a.n_sets > 0) {
+        grid = 0;
+        for (int i = 0; i < a.n_sets; ++i) {
+            a.set[i].block0 = (int32_t)grid;
+            grid += (long)a.max_units * ((a.set[i].N + kExCols - 1) / kExCols);
+        }
+    } else {
+        a.col_groups = (a.N + kExCols - 1) / kExCols;
+        grid = (long)a.max_units * a.col_groups;
+    }
+    if (grid <= 0) return hipSuccess;
     const size_t smem = expand_smem_bytes(a.r_max, dtype);
     const bool small = a.unit_rows <= kShrinkRowsSmall;
     const void *fn = dtype == 1 ? (small ? reinterpret_cast<const void *>(expand_kernel<__bf16, true>)

@@ -80,15 +80,19 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     const int gsz = min(tiles_m - first_m, group_m);
     const int pm = first_m + (lin % width) % gsz;
     const int pn = (lin % width) / gsz;
-    const int m0 = pm * BM, n0 = pn * BN;
+    // the projection this column tile belongs to (one, or several that share X and the plan)
+    int si = 0;
+    while (si + 1 < p.n_sets && pn >= p.set[si + 1].tile0) ++si;
+    const GemmSet g = p.set[si];
+    const int m0 = pm * BM, n0 = (pn - g.tile0) * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wn0 = (wave % WN) * WTN, wm0 = (wave / WN) * WTM;
     const int l31 = lane & 31, lh = lane >> 5;
 
-    const E *W = static_cast<const E *>(p.W);
-    const E *V = static_cast<const E *>(p.V);
+    const E *W = static_cast<const E *>(g.W);
+    const E *V = static_cast<const E *>(g.V);
 
     // ---- per-thread load slots ------------------------------------------------------------
     const int lrow = tid >> 3, lc = tid & 7;
@@ -96,7 +100,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // a load then needs no vector address arithmetic at all, and one register of address.  X is
     // addressed from its start (the host checks that it is smaller than 4 GiB), W0 from the tile's first row.
     const BufferDesc Xd = make_buffer_desc(p.X);
-    const BufferDesc Wd = make_buffer_desc(static_cast<const char *>(p.W) + (int64_t)n0 * p.ldw * (int64_t)sizeof(E));
+    const BufferDesc Wd = make_buffer_desc(static_cast<const char *>(g.W) + (int64_t)n0 * g.ldw * (int64_t)sizeof(E));
     unsigned xoff[XL], woff[WL];
     int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
@@ -106,11 +110,11 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     }
 #pragma unroll
     for (int i = 0; i < WL; ++i)
-        woff[i] = (unsigned)(((int64_t)(min(n0 + lrow + i * RPP, p.N - 1) - n0) * p.ldw + lc * CE) * (int64_t)sizeof(E));
+        woff[i] = (unsigned)(((int64_t)(min(n0 + lrow + i * RPP, g.N - 1) - n0) * g.ldw + lc * CE) * (int64_t)sizeof(E));
 
     // ---- extension range of this M-tile -----------------------------------------------------
     int pbeg = 0, pend = 0;
-    if (p.B != nullptr) {
+    if (g.B != nullptr) {
         const int s_first = p.plan.row_seg[m0];
         const int s_last = p.plan.row_seg[min(m0 + BM, p.T) - 1];
         pbeg = p.plan.seg_ext[s_first];
@@ -119,10 +123,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     const int ext_chunks = (pend - pbeg) / CE;
     // Which rows take their adapter term from D: those with an adapter -- of a short segment only, when the long
     // segments' term is computed here (long_rows > 0).  Read in the epilogue.
-    if (p.D != nullptr) {
+    if (g.D != nullptr) {
         for (int r = tid; r < BM; r += NT) {
             const int s = p.plan.row_seg[min(m0 + r, p.T - 1)];
-            const bool lng = p.long_rows > 0 && p.plan.seg_indptr[s + 1] - p.plan.seg_indptr[s] >= p.long_rows;
+            const bool lng = g.long_rows > 0 && p.plan.seg_indptr[s + 1] - p.plan.seg_indptr[s] >= g.long_rows;
             tab->use_d[r] = p.plan.seg_adapter[s] >= 0 && !lng;
         }
     }
@@ -145,10 +149,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             int4 rec = make_int4(-1, 0, 0, 0);
             if (wanted) {
                 rec = reinterpret_cast<const int4 *>(p.plan.ext_rec)[pe >> 3];
-                wanted = rec.w - rec.z >= p.long_rows;  // (short segments' term comes in D when long_rows > 0)
+                wanted = rec.w - rec.z >= g.long_rows;  // (short segments' term comes in D when long_rows > 0)
             }
             if (wanted) {
-                const E *b = rec.x >= 0 ? static_cast<const E *>(p.B[rec.x]) : nullptr;
+                const E *b = rec.x >= 0 ? static_cast<const E *>(g.B[rec.x]) : nullptr;
                 if (b != nullptr) {
                     e_r[it] = rec.y >> 16;
                     e_j[it] = (rec.y & 0xffff) + (pe & 7);
@@ -238,7 +242,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         const E *bsrc = wok ? bp : W;  // W: some in-bounds address for the dropped loads
 #pragma unroll
         for (int i = 0; i < WL; ++i) {
-            const int n = min(n0 + lrow + i * RPP, p.N - 1);
+            const int n = min(n0 + lrow + i * RPP, g.N - 1);
             wr[i] = load_chunk(bsrc + (wok ? (int64_t)n * r : 0));
         }
     };
@@ -481,14 +485,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     }
 
     // ---- single store of Y: acc[nb][tb][g*4+e] = D[n = nb*32 + g*8 + lh*4 + e][t = tb*32 + l31] -------
-    E *Y = static_cast<E *>(p.Y);
-    if (p.D == nullptr) {
+    E *Y = static_cast<E *>(g.Y);
+    if (g.D == nullptr) {
 #pragma unroll
         for (int tb = 0; tb < NBT; ++tb) {
             const int t = m0 + wm0 + tb * 32 + l31;
-            E *yrow = Y + (int64_t)p.plan.perm[min(t, p.T - 1)] * p.ldy;
+            E *yrow = Y + (int64_t)p.plan.perm[min(t, p.T - 1)] * g.ldy;
 #pragma unroll
-            for (int nb = 0; nb < NBN; ++nb) store_acc_tile<E>(acc[nb][tb], yrow, nullptr, n0 + wn0 + nb * 32, lh, p.N, t < p.T);
+            for (int nb = 0; nb < NBN; ++nb) store_acc_tile<E>(acc[nb][tb], yrow, nullptr, n0 + wn0 + nb * 32, lh, g.N, t < p.T);
         }
     } else {
         // The adapter term, when a kernel of its own has computed it (rows with an adapter only), is read one
@@ -497,30 +501,40 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         float term[2][NBN][16];
         auto row_of = [&](int tb) { return p.plan.perm[min(m0 + wm0 + tb * 32 + l31, p.T - 1)]; };
         auto fetch = [&](int tb, int row, float (&d)[NBN][16]) {
-            const float *drow = tab->use_d[wm0 + tb * 32 + l31] ? p.D + (int64_t)row * p.ldd : nullptr;
+            const float *drow = tab->use_d[wm0 + tb * 32 + l31] ? g.D + (int64_t)row * g.ldd : nullptr;
 #pragma unroll
-            for (int nb = 0; nb < NBN; ++nb) load_term_tile(drow, p.D, n0 + wn0 + nb * 32, lh, (int)p.ldd, d[nb]);
+            for (int nb = 0; nb < NBN; ++nb) load_term_tile(drow, g.D, n0 + wn0 + nb * 32, lh, (int)g.ldd, d[nb]);
         };
         int row = row_of(0);
         fetch(0, row, term[0]);
 #pragma unroll
         for (int tb = 0; tb < NBT; ++tb) {
             const int t = m0 + wm0 + tb * 32 + l31;
-            E *yrow = Y + (int64_t)row * p.ldy;
+            E *yrow = Y + (int64_t)row * g.ldy;
             if (tb + 1 < NBT) {
                 row = row_of(tb + 1);
                 fetch(tb + 1, row, term[(tb + 1) & 1]);
             }
 #pragma unroll
             for (int nb = 0; nb < NBN; ++nb)
-                store_acc_tile_with<E>(acc[nb][tb], term[tb & 1][nb], yrow, n0 + wn0 + nb * 32, lh, p.N, t < p.T);
+                store_acc_tile_with<E>(acc[nb][tb], term[tb & 1][nb], yrow, n0 + wn0 + nb * 32, lh, g.N, t < p.T);
         }
     }
 }
 
 template <typename E, int BM, int BN, int WM, int WN>
-hipError_t launch_tile(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
-    const int tiles_m = (a.T + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
+hipError_t launch_tile(const GemmArgs &a0, hipStream_t stream, const KernelTimer *timer) {
+    GemmArgs a = a0;
+    if (a.n_sets == 0) {  // a single projection, described by the plain fields
+        a.n_sets = 1;
+        a.set[0] = GemmSet{a.W, a.ldw, a.Y, a.ldy, a.V, a.B, a.D, a.ldd, a.long_rows, a.N, 0, 0};
+    }
+    const int tiles_m = (a.T + BM - 1) / BM;
+    int tiles_n = 0;
+    for (int i = 0; i < a.n_sets; ++i) {
+        a.set[i].tile0 = tiles_n;
+        tiles_n += (a.set[i].N + BN - 1) / BN;
+    }
     const long total = (long)tiles_m * tiles_n;
     if (total <= 0) return hipSuccess;
     const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);

@@ -114,6 +114,17 @@ inline hipError_t launch_kernel(F kernel, dim3 grid, dim3 block, size_t smem, hi
 // decode-sized (one lane per request) kernel.  timers: [0] segments, [1] fill.
 hipError_t launch_plan_build(const PlanBuildArgs &a, bool fuse_fill, int variant, hipStream_t stream, const KernelTimer *timers);
 
+constexpr int kMaxGemmSets = 4;
+// One projection of a launch that covers several projections of the same X (fused QKV, gate + up): the grid of the
+// single-projection launch, once per projection.
+struct ShrinkSet {
+    const void *const *A;
+    const float *scale;
+    void *V;
+    int32_t n_adapters;
+    int32_t pad_;
+};
+
 struct ShrinkArgs {
     PlanView plan;
     const void *X;
@@ -136,8 +147,27 @@ struct ShrinkArgs {
     int32_t pack_tblk;
     long long *trace = nullptr;  // phase stamps (trace builds only)
     int32_t pack_wgs;      // extra workgroups in front of the shrink units that write the copy
+    int32_t n_sets = 0;    // > 0: the projections of the launch (A, scale, V, n_adapters above are then unused)
+    ShrinkSet set[kMaxGemmSets];
 };
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
+
+// One projection of a tiled GEMM launch that covers several projections of the same X: its
+// own weights, output, adapters and adapter term; the column tiles of the projections follow each other in the grid.
+struct GemmSet {
+    const void *W;
+    int64_t ldw;
+    void *Y;
+    int64_t ldy;
+    const void *V;
+    const void *const *B;
+    const float *D;
+    int64_t ldd;
+    int32_t long_rows;
+    int32_t N;
+    int32_t tile0;  // first column tile of this projection (set by the launcher)
+    int32_t pad_;
+};
 
 struct GemmArgs {
     PlanView plan;
@@ -156,7 +186,21 @@ struct GemmArgs {
                             // the tiled GEMM computes the others' as extension stages
     int32_t r_max;
     int32_t T, K, N;
+    // tiled kernel only: the projections of the launch (n_sets == 0: one, described by the fields above)
+    int32_t n_sets = 0;
+    GemmSet set[kMaxGemmSets];
     long long *trace = nullptr;  // phase stamps (trace builds only)
+};
+
+struct ExpandSet {
+    const void *V;
+    const void *const *B;
+    float *D;
+    int64_t ldd;
+    int32_t N;
+    int32_t skip_long;
+    int32_t block0;  // first workgroup of this projection (set by the launcher)
+    int32_t pad_;
 };
 
 // Separate expand kernel (many small segments): D[row, :] = V[row, :] B_a^T per shrink work unit, in fp32.
@@ -173,6 +217,8 @@ struct ExpandArgs {
     int32_t unit_rows;     // most rows of a work unit in this plan (16 or 64)
     int32_t skip_long;     // 1: units of long segments (kUnitLongFlag) are left to the GEMM
     long long *trace = nullptr;  // phase stamps (trace builds only)
+    int32_t n_sets = 0;    // > 0: the projections of the launch (V, B, D, ldd, N, skip_long above are then unused)
+    ExpandSet set[kMaxGemmSets];
 };
 hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 

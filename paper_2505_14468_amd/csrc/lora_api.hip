@@ -18,6 +18,7 @@ static_assert(LORA_ERR_LENGTH_MISMATCH == kErrLengthMismatch, "status codes out 
 static_assert(LORA_ERR_ADAPTER_NOT_RESIDENT == kErrNotResident, "status codes out of sync");
 static_assert(LORA_ERR_RANK_TOO_LARGE == kErrRankTooLarge, "status codes out of sync");
 static_assert(LORA_ERR_SHAPE == kErrShape, "status codes out of sync");
+static_assert(LORA_MAX_MULTI == kMaxGemmSets, "projection limit out of sync");
 
 namespace {
 
@@ -289,13 +290,15 @@ struct GemmChoice {
     int nb;    // skinny only: 16-column blocks per workgroup
 };
 
-GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
+// (ns / n_sets: the output widths of the projections one launch covers; the decode-sized kernel takes one)
+GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int32_t *ns, int n_sets, int32_t dtype) {
+    const int32_t N = ns[0];
     GemmChoice c{kGemmTile128x128, 0, 1};
     (void)K;
     const int cus = ctx ? ctx->num_cu : 256;
     const int max_rows = ctx && ctx->opt_skinny_max_rows >= 0 ? ctx->opt_skinny_max_rows : kSkinnyMaxRows;
     int forced = ctx ? ctx->opt_gemm_variant : -1;
-    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows;
+    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && n_sets == 1;
     if (forced == kGemmSkinny && !fits) forced = -1;
     const bool skinny = forced == kGemmSkinny || (forced < 0 && fits && T <= max_rows);
     if (skinny) {
@@ -330,7 +333,9 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
     double best = 0.0;
     bool have = false;
     for (const Cand &cd : cands) {
-        const int64_t tiles = ((T + cd.bm - 1) / cd.bm) * (int64_t)((N + cd.bn - 1) / cd.bn);
+        int64_t tiles_n = 0;
+        for (int i = 0; i < n_sets; ++i) tiles_n += (ns[i] + cd.bn - 1) / cd.bn;
+        const int64_t tiles = ((T + cd.bm - 1) / cd.bm) * tiles_n;
         const int64_t rounds = (tiles + cus - 1) / cus;
         const double cost = (double)rounds * cd.bm * cd.bn / cd.eff;
         if (!have || cost < best) {
@@ -340,6 +345,10 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
         }
     }
     return c;
+}
+
+GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
+    return choose_gemm_sets(ctx, T, K, &N, 1, dtype);
 }
 
 struct WorkspaceLayout {
@@ -370,7 +379,7 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     return w;
 }
 
-int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d) {
+int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, bool need_ctx = true) {
     if (!plan || !d) return LORA_ERR_INVALID_ARG;
     if (plan->magic != kPlanMagic || plan->T < 0 || !plan->scalars) return LORA_ERR_PLAN;
     if (plan->unit_rows != kShrinkRows && plan->unit_rows != kShrinkRowsSmall) return LORA_ERR_PLAN;
@@ -398,7 +407,7 @@ int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
         if ((uintptr_t)d->workspace & 255u) return LORA_ERR_ALIGNMENT;
         if (d->workspace_bytes < w.total) return LORA_ERR_WORKSPACE_TOO_SMALL;
     }
-    if (!ctx) return LORA_ERR_INVALID_ARG;  // last, so that the checks above run on a GPU-less host too
+    if (need_ctx && !ctx) return LORA_ERR_INVALID_ARG;  // last, so that the checks above run on a GPU-less host too
     return LORA_OK;
 }
 
@@ -422,9 +431,12 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
 }
 
-int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
-    const bool ad = has_adapters(plan, d);
-    const bool pack = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny;
+// (multi: one of several projections of the same X that go through one launch -- never decode-sized, so no copy of X)
+int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream,
+              const lora_linear_desc *const *multi = nullptr, int n_multi = 0) {
+    bool ad = has_adapters(plan, d);
+    for (int i = 0; i < n_multi; ++i) ad = ad || has_adapters(plan, multi[i]);
+    const bool pack = n_multi == 0 && choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny;
     if (!ad && !pack) return LORA_OK;
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
@@ -434,11 +446,22 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.ldx = d->ldx;
     a.K = d->K;
     a.T = (int32_t)plan->T;
-    a.A = ad ? d->tbl->A : nullptr;
-    a.scale = ad ? d->tbl->scale : nullptr;
+    a.A = ad && n_multi == 0 ? d->tbl->A : nullptr;
+    a.scale = ad && n_multi == 0 ? d->tbl->scale : nullptr;
     a.V = ws + w.v_off;
     a.r_max = plan->r_max;
-    a.n_adapters = ad ? d->tbl->n_adapters : 0;
+    a.n_adapters = ad && n_multi == 0 ? d->tbl->n_adapters : 0;
+    a.n_sets = n_multi;
+    for (int i = 0; i < n_multi; ++i) {
+        const lora_linear_desc *di = multi[i];
+        const bool adi = has_adapters(plan, di);
+        const WorkspaceLayout wi = workspace_layout(plan->T, di->K, di->N, plan->r_max, di->dtype);
+        a.set[i].A = adi ? di->tbl->A : nullptr;
+        a.set[i].scale = adi ? di->tbl->scale : nullptr;
+        a.set[i].V = static_cast<unsigned char *>(di->workspace) + wi.v_off;
+        a.set[i].n_adapters = adi ? di->tbl->n_adapters : 0;
+        a.set[i].pad_ = 0;
+    }
     // units <= sum over segments of ceil(rows / unit_rows) <= T / unit_rows + number of adapter segments
     const int64_t seg_bound = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;
     const int64_t seg_bound2 = seg_bound < plan->T ? seg_bound : plan->T;
@@ -467,47 +490,30 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     return LORA_OK;
 }
 
-int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
+// The adapter term of one projection: fused into the GEMM, or -- batches of many small segments, where an M tile
+// of the fused kernel would hold dozens of adapters, a few rows each -- computed per segment by a weight-streaming
+// kernel of its own into the workspace (fp32), which is launched here, and added by the GEMM to its accumulators;
+// the second only if the caller's workspace has the room.  Describes the projection for the GEMM in *out.
+// (collect: several projections in one launch -- the expand kernel's arguments are gathered there, not launched)
+int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, int variant, hipStream_t stream,
+                const KernelTimer *expand_timer, GemmSet *out, bool *split_out, ExpandArgs *collect = nullptr) {
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
-    GemmArgs a;
-    a.plan = view_of(plan);
-    a.X = d->X;
-    a.ldx = d->ldx;
-    a.W = d->W0;
-    a.ldw = d->ldw;
-    a.Y = d->Y;
-    a.ldy = d->ldy;
     const bool ad = has_adapters(plan, d);
-    a.V = ad ? ws + w.v_off : nullptr;
-    a.Xpack = w.xpack_bytes ? ws + w.xpack_off : nullptr;
-    a.B = ad ? d->tbl->B : nullptr;
-    a.r_max = plan->r_max;
-    a.T = (int32_t)plan->T;
-    a.K = d->K;
-    a.N = d->N;
-    GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
-    if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) {  // these address W0 / X with 31-bit byte offsets
-        const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
-        if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
-    }
-    // Batches of many small segments (an M tile of the fused kernel would hold dozens of adapters, a few
-    // rows each): a weight-streaming kernel computes the adapter term per segment into the workspace (fp32)
-    // and the GEMM adds it to its accumulators -- if the caller's workspace has the room.
+    GemmSet g{};
+    g.W = d->W0;
+    g.ldw = d->ldw;
+    g.Y = d->Y;
+    g.ldy = d->ldy;
+    g.V = ad ? ws + w.v_off : nullptr;
+    g.B = ad ? d->tbl->B : nullptr;
+    g.N = d->N;
     bool split = false;
-    if (ad && c.variant != kGemmSkinny && w.d_bytes > 0 && d->workspace_bytes >= w.total_preferred) {
+    if (ad && variant != kGemmSkinny && w.d_bytes > 0 && d->workspace_bytes >= w.total_preferred) {
         const int64_t segs = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;  // upper bound
         split = segs > 0 && plan->T / segs < 64;
         if (ctx->opt_expand_split >= 0) split = ctx->opt_expand_split == 1;
     }
-    a.D = nullptr;
-    a.ldd = 0;
-    KernelTimer timer;
-    const bool timed = next_timer(ctx, kProfGemm, &timer);
-    // (in split mode one event pair brackets both kernels: start with the first, stop with the second)
-    KernelTimer first = timer, second = timer;
-    first.stop = nullptr;
-    second.start = nullptr;
     if (split) {
         ExpandArgs e;
         e.plan = view_of(plan);
@@ -526,18 +532,67 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         // of an M tile, ~2 us each, against 8 bytes of D traffic per element and the units' reads of B_a saved: worth
         // it up to rank 64 -- C3 gate_proj 150 -> 140 us; at rank 128, C4, 428 -> 434 us) and takes the short
         // segments' from D; the other kernels take all of it from D.
-        const bool tiled = !(c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) && plan->r_max <= 64;
+        const bool tiled = !(variant >= kGemmPipe256x256w8 && variant <= kGemmPipe128x128w4) && plan->r_max <= 64;
         e.skip_long = tiled ? 1 : 0;
-        LORA_HIP(launch_expand(e, d->dtype, stream, timed ? &first : nullptr));
-        if (tiled) {
-            a.long_rows = kLongSegRows;
+        if (collect != nullptr) {
+            const int i = collect->n_sets;
+            e.n_sets = 0;
+            if (i == 0) *collect = e;
+            collect->set[i] = ExpandSet{e.V, e.B, e.D, e.ldd, e.N, e.skip_long, 0, 0};
+            collect->n_sets = i + 1;
         } else {
-            a.B = nullptr;
-            a.V = nullptr;
+            LORA_HIP(launch_expand(e, d->dtype, stream, expand_timer));
         }
-        a.D = e.D;
-        a.ldd = e.ldd;
+        if (tiled) {
+            g.long_rows = kLongSegRows;
+        } else {
+            g.B = nullptr;
+            g.V = nullptr;
+        }
+        g.D = e.D;
+        g.ldd = e.ldd;
     }
+    *out = g;
+    *split_out = split;
+    return LORA_OK;
+}
+
+int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
+    unsigned char *ws = static_cast<unsigned char *>(d->workspace);
+    GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
+    if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) {  // these address W0 / X with 31-bit byte offsets
+        const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
+        if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
+    }
+    KernelTimer timer;
+    const bool timed = next_timer(ctx, kProfGemm, &timer);
+    // (with a separate expand kernel one event pair brackets both kernels: start with the first, stop with the second)
+    KernelTimer first = timer, second = timer;
+    first.stop = nullptr;
+    second.start = nullptr;
+    GemmSet g;
+    bool split = false;
+    const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &first : nullptr, &g, &split);
+    if (rc != LORA_OK) return rc;
+    GemmArgs a;
+    a.plan = view_of(plan);
+    a.X = d->X;
+    a.ldx = d->ldx;
+    a.W = g.W;
+    a.ldw = g.ldw;
+    a.Y = g.Y;
+    a.ldy = g.ldy;
+    a.V = g.V;
+    a.Xpack = w.xpack_bytes ? ws + w.xpack_off : nullptr;
+    a.B = g.B;
+    a.D = g.D;
+    a.ldd = g.ldd;
+    a.long_rows = g.long_rows;
+    a.r_max = plan->r_max;
+    a.T = (int32_t)plan->T;
+    a.K = d->K;
+    a.N = d->N;
     const KernelTimer *tg = !timed ? nullptr : (split ? &second : &timer);
     if (c.variant == kGemmSkinny)
         LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, tg));
@@ -545,6 +600,50 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, tg));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
+    return LORA_OK;
+}
+
+// Several projections of the same X in one tiled GEMM launch (their column tiles side by side in one grid: one
+// ramp, one set of whole rounds of tiles for all of them).  False: this batch / these options take another kernel.
+bool multi_takes_tiled(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
+    int32_t ns[kMaxGemmSets];
+    for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
+    *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
+    if (plan->T <= kSkinnyMaxRows && descs[0]->dtype == LORA_DTYPE_BF16 && ctx->opt_gemm_variant < 0) return false;  // decode-sized
+    return c->variant != kGemmSkinny && !(c->variant >= kGemmPipe256x256w8 && c->variant <= kGemmPipe128x128w4);
+}
+
+int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, const GemmChoice &c,
+                  hipStream_t stream) {
+    GemmArgs a;
+    a.plan = view_of(plan);
+    a.X = descs[0]->X;
+    a.ldx = descs[0]->ldx;
+    a.W = nullptr;
+    a.ldw = 0;
+    a.Y = nullptr;
+    a.ldy = 0;
+    a.V = nullptr;
+    a.Xpack = nullptr;
+    a.B = nullptr;
+    a.D = nullptr;
+    a.ldd = 0;
+    a.r_max = plan->r_max;
+    a.T = (int32_t)plan->T;
+    a.K = descs[0]->K;
+    a.N = 0;
+    a.n_sets = n;
+    KernelTimer timer;
+    const bool timed = next_timer(ctx, kProfGemm, &timer);  // (the GEMM alone: the expand launches are not bracketed)
+    ExpandArgs e;
+    e.n_sets = 0;
+    for (int i = 0; i < n; ++i) {
+        bool split = false;
+        const int rc = prepare_set(ctx, plan, descs[i], c.variant, stream, nullptr, &a.set[i], &split, &e);
+        if (rc != LORA_OK) return rc;
+    }
+    if (e.n_sets > 0) LORA_HIP(launch_expand(e, descs[0]->dtype, stream, nullptr));  // one launch for every projection that takes it
+    LORA_HIP(launch_gemm_tile(a, descs[0]->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
 }
 
@@ -735,6 +834,38 @@ int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
     rc = do_shrink(ctx, plan, desc, s);
     if (rc != LORA_OK) return rc;
     return do_gemm(ctx, plan, desc, s);
+}
+
+int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int32_t n,
+                      lora_stream_t stream) {
+    if (!descs || n < 1 || n > LORA_MAX_MULTI) return LORA_ERR_INVALID_ARG;
+    for (int i = 0; i < n; ++i) {
+        if (!descs[i]) return LORA_ERR_INVALID_ARG;
+        const int rc = check_linear(ctx, plan, descs[i], false);
+        if (rc != LORA_OK) return rc;
+        if (descs[i]->X != descs[0]->X || descs[i]->ldx != descs[0]->ldx || descs[i]->K != descs[0]->K ||
+            descs[i]->dtype != descs[0]->dtype)
+            return LORA_ERR_INVALID_ARG;
+        for (int j = 0; j < i; ++j)
+            if (plan->T > 0 && (descs[i]->Y == descs[j]->Y || descs[i]->workspace == descs[j]->workspace)) return LORA_ERR_INVALID_ARG;
+    }
+    if (!ctx) return LORA_ERR_INVALID_ARG;  // (last: the checks above run on a GPU-less host too)
+    if (plan->T == 0) return LORA_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmChoice c;
+    if (n == 1 || !multi_takes_tiled(ctx, plan, descs, n, &c)) {  // one after the other
+        for (int i = 0; i < n; ++i) {
+            int rc = do_shrink(ctx, plan, descs[i], s);
+            if (rc == LORA_OK) rc = do_gemm(ctx, plan, descs[i], s);
+            if (rc != LORA_OK) return rc;
+        }
+        return LORA_OK;
+    }
+    const int rc = do_shrink(ctx, plan, descs[0], s, descs, n);  // one launch: the single projection's grid once per projection
+    if (rc != LORA_OK) return rc;
+    return do_gemm_multi(ctx, plan, descs, n, c, s);
 }
 
 int lora_profile_begin(lora_ctx *ctx, int max_launches) {

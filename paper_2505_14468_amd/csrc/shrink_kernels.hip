@@ -324,15 +324,28 @@ __device__ __forceinline__ void pack_x(const ShrinkArgs &p, int wg) {
 }
 
 template <typename E>
-__global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
+__global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
-    LORA_TS(p.trace, 0);
+    LORA_TS(p0.trace, 0);
 
-    if ((int)blockIdx.x < p.pack_wgs) {
-        if (p.plan.scalars[kScStatus] != 0) return;
-        pack_x<E>(p, blockIdx.x);
+    if ((int)blockIdx.x < p0.pack_wgs) {
+        if (p0.plan.scalars[kScStatus] != 0) return;
+        pack_x<E>(p0, blockIdx.x);
         return;
+    }
+    // several projections of the same X: the single-projection grid once per projection
+    ShrinkArgs p = p0;
+    int bid = blockIdx.x - p.pack_wgs;
+    if (p0.n_sets > 0) {
+        const int per = (p.max_units + 7) / 8 * 8 * p.rank_groups;
+        const int si = bid / per;
+        bid -= si * per;
+        p.A = p0.set[si].A;
+        p.scale = p0.set[si].scale;
+        p.V = p0.set[si].V;
+        p.n_adapters = p0.set[si].n_adapters;
+        if (p.A == nullptr) return;  // a projection without adapters
     }
     // A unit is a chain of dependent loads (work list -> row map and adapter table -> operands), each a
     // round trip to memory in a kernel that lasts a few of them: loads that do not depend on each other
@@ -344,7 +357,6 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
     // fastest: the rank blocks past a small adapter's rank have nothing to do and exit at once, and with them
     // interleaved (period = rank_groups, a divisor of the eight XCDs the workgroups go to in turn) every unit with
     // work sits on the same XCDs and in the grid's second round.
-    const int bid = blockIdx.x - p.pack_wgs;
     const int mu8 = (p.max_units + 7) / 8 * 8;
     const int unit_a = bid % mu8, unit_b = bid / p.rank_groups;
     const int4 rec_a = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit_a];
@@ -435,7 +447,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p) {
 }  // namespace
 
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups + a.pack_wgs;
+    const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups * (a.n_sets > 0 ? a.n_sets : 1) + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
     const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;

@@ -210,6 +210,23 @@ def linear(ctx: Context, pl: Plan, X: torch.Tensor, W0: torch.Tensor, table: Opt
     return Y
 
 
+def linear_multi(ctx: Context, pl: Plan, X: torch.Tensor, projections) -> List[torch.Tensor]:
+    """Run lora_linear_multi on the current stream: ``projections`` is a list of (W0, table) that share X;
+    returns the list of outputs."""
+    ce = 8 if X.dtype == torch.bfloat16 else 4
+    descs, outs, keep = [], [], []
+    for W0, table in projections:
+        N = W0.shape[0]
+        Y = torch.empty((pl.T, (N + ce - 1) // ce * ce), dtype=X.dtype, device=X.device)[:, :N]
+        ws = workspace(pl.T, W0.shape[1], N, pl.r_max, X.dtype, X.device)
+        descs.append(linear_desc(pl, X, W0, Y, table, ws))
+        outs.append(Y)
+        keep.append(ws)
+    B.lora_linear_multi(ctx.handle, pl.struct, descs, _stream())
+    pl._keep_multi = keep  # the workspaces live until the plan does (the kernels are still in flight)
+    return outs
+
+
 def upload_workload(wl, p: int, device, only_used: bool = False):
     """Device tensors of projection ``p`` of a ``workloads.Workload``: X, W0 and the adapter table."""
     X = tensor_from_bits(wl.X(p), device)

@@ -131,6 +131,13 @@ def test_lora_linear_validates_before_touching_the_gpu():
     assert run(tbl=tbl) == B.LORA_ERR_INVALID_ARG
     for stage in (B.lora_shrink, B.lora_gemm_expand):
         assert stage(None, plan, d, None, raw=True) == B.LORA_ERR_INVALID_ARG
+    # several projections in one call: the same checks per projection, before the context is needed
+    assert B.lora_linear_multi(None, plan, [d, d], None, raw=True) == B.LORA_ERR_INVALID_ARG
+    assert B.lora_linear_multi(None, plan, [], None, raw=True) == B.LORA_ERR_INVALID_ARG
+    assert B.lora_linear_multi(None, plan, [d] * (B.LORA_MAX_MULTI + 1), None, raw=True) == B.LORA_ERR_INVALID_ARG
+    d_bad = B.make_linear_desc(B.LORA_DTYPE_BF16, 60, 64, 4096, 64, 8192, 64, 32768, 64, None, 65536, ws_bytes)
+    assert B.lora_linear_multi(None, plan, [d, d_bad], None, raw=True) == B.LORA_ERR_SHAPE
+    assert B.lora_linear_multi(None, bad, [d], None, raw=True) == B.LORA_ERR_PLAN
 
 
 def test_kernel_selection_is_host_side():

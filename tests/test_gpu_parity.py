@@ -157,6 +157,59 @@ def test_random_segment_mixes_fused_and_separate(seed):
     reset_options()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_linear_multi_projections_of_the_same_activations(dtype):
+    """lora_linear_multi: three projections of one X (different widths, one ragged) in one call -- every output
+    against the oracle and against the single-projection call; tile shapes, adapter term fused / separate; a
+    decode-sized batch (taken one projection after the other); argument errors."""
+    import torch
+    from workloads.configs import Projection
+    from gpu_common import B, rt, ctx, check_against_oracle, reset_options, TOL
+    from workloads import to_f64
+    c = ctx()
+    for case, (ids, L) in enumerate([([3, 0, -1, 5, 3, 1, 6, 2, 5, 3, 0, 4, -1, 6], [150, 1, 9, 64, 150, 63, 1, 17, 0, 141, 2, 5, 30, 1]),
+                                     ([1, 1, 4, -1, 0, 7, 2], [3, 9, 1, 5, 7, 11, 4])]):
+        wl = make_custom(seed=930 + case, dtype=dtype, K=200, N=520, ranks=(8, 16, 64, 40, 8, 24, 32, 48),
+                         scales=(2.0, 0.5, 1.0, 0.25, 1.5, 1.0, 0.75, 1.0), req_adapter=np.asarray(ids), req_ntok=np.asarray(L),
+                         name=f"multi_{dtype}_{case}")
+        wl.projections = [Projection("a", 200, 520), Projection("b", 200, 264), Projection("c", 200, 1100)]
+        wl.shared_x = True
+        dev = c.device
+        up = [rt.upload_workload(wl, q, dev) for q in range(3)]
+        X = up[0][0]
+        assert all(torch.equal(u[0], X) for u in up)
+        pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks, wl.r_max)
+        for variant in (None, "tile_256x224", "tile_128x192", "tile_64x64", "pipe_128x128_w4"):
+            c.set_option("gemm_variant", VARIANTS[variant] if variant else -1)
+            for split in (-1, 0, 1):
+                c.set_option("expand_split", split)
+                outs = rt.linear_multi(c, pl, X, [(u[1], u[2]) for u in up])
+                torch.cuda.synchronize()
+                for q in range(3):
+                    got = to_f64(rt.bits_from_tensor(outs[q]))
+                    e = check_against_oracle(wl, got, p=q)
+                    single = to_f64(rt.bits_from_tensor(rt.linear(c, pl, X, up[q][1], up[q][2])))
+                    torch.cuda.synchronize()
+                    rms = float(np.sqrt((single ** 2).mean()))
+                    assert float(np.abs(got - single).max()) <= TOL[dtype] * rms
+        print(f"{wl.name}: T={wl.T} err/rms {e:.2e}", flush=True)
+        reset_options()
+        # argument errors: more projections than the limit, projections of different activations, one output twice
+        ws = [rt.workspace(pl.T, 200, u[1].shape[0], pl.r_max, X.dtype, dev) for u in up]
+        Ys = [torch.empty((pl.T, (u[1].shape[0] + 7) // 8 * 8), dtype=X.dtype, device=dev)[:, :u[1].shape[0]] for u in up]
+        d = [rt.linear_desc(pl, X, up[q][1], Ys[q], up[q][2], ws[q]) for q in range(3)]
+        st = torch.cuda.current_stream().cuda_stream
+        assert B.lora_linear_multi(c.handle, pl.struct, d + d[:2], st, raw=True) == B.LORA_ERR_INVALID_ARG
+        assert B.lora_linear_multi(c.handle, pl.struct, [], st, raw=True) == B.LORA_ERR_INVALID_ARG
+        X2 = X.clone()
+        d_other = rt.linear_desc(pl, X2, up[1][1], Ys[1], up[1][2], ws[1])
+        assert B.lora_linear_multi(c.handle, pl.struct, [d[0], d_other], st, raw=True) == B.LORA_ERR_INVALID_ARG
+        d_same_y = rt.linear_desc(pl, X, up[0][1], Ys[0], up[0][2], ws[1])
+        assert B.lora_linear_multi(c.handle, pl.struct, [d[0], d_same_y], st, raw=True) == B.LORA_ERR_INVALID_ARG
+        assert B.lora_linear_multi(c.handle, pl.struct, d, st, raw=True) == B.LORA_OK
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
 def test_skinny_kernel_row_counts(T):
     """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""

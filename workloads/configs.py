@@ -55,6 +55,7 @@ class Workload:
     sigma_b: float = 0.02
     sigma_a: Optional[float] = None  # None -> 1/sqrt(K) of the projection
     integer_valued: bool = False  # small integers in [-4, 4] (exact in every precision)
+    shared_x: bool = False  # every projection reads projection 0's X (fused QKV, gate + up; same K required)
     _cache: dict = field(default_factory=dict, repr=False)
 
     # ---- batch geometry -------------------------------------------------
@@ -100,6 +101,9 @@ class Workload:
         return self._cache[key]
 
     def X(self, p: int = 0) -> np.ndarray:
+        if self.shared_x:
+            assert self.projections[p].K == self.projections[0].K
+            p = 0
         pr = self.projections[p]
         return self._get(("X", p), lambda: self._draw(_TAG_X, p, 0, (self.T, pr.K), self.sigma_x))
 
