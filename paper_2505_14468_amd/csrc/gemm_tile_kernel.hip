@@ -444,9 +444,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         }
         // The last stage loads and stores nothing, so both register sets are free: the first extension stage in
         // use is requested in front of it and arrives while it is multiplied.
+        // (not beside a 256x256 tile on 4 waves: the registers that keeps alive through the last stage are spilled)
+        constexpr bool PREFETCH_EXT = XL + WL < 16;
         auto prefetch_ext = [&]() __attribute__((always_inline)) {
-            ext_loaded = ext_used > 0;
-            if (ext_loaded) load_ext(0);
+            if constexpr (PREFETCH_EXT) {
+                ext_loaded = ext_used > 0;
+                if (ext_loaded) load_ext(0);
+            }
         };
         for (; kt < KT; kt += 2) {
             if (kt + 1 == KT) prefetch_ext();
