@@ -245,8 +245,8 @@ int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
  * plan; each has its own W0, N, Y, adapter table and workspace (of its own
  * lora_linear_workspace_bytes[_preferred]).  Computes what n calls of
  * lora_linear compute (same formula per projection; fp32 summation order may
- * differ, as between tile shapes); for batches above 128 rows the base products
- * run as one GEMM launch whose grid holds the column tiles of all projections.
+ * differ, as between tile shapes); every kernel runs as one launch whose grid
+ * holds the work of all projections.
  * Errors: those of lora_linear for any desc; INVALID_ARG also for n out of
  * range, descs that differ in X / ldx / K / dtype, or two descs with the same Y
  * or workspace. */

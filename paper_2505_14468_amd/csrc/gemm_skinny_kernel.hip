@@ -37,7 +37,7 @@ constexpr int kSkWaves = 8;
 constexpr int kSkThreads = kSkWaves * 64;
 
 template <int TBLK, int NB>
-__global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
+__global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p0) {
     typedef __bf16 E;
     constexpr int CE = 8;
     constexpr int WS = 8 / NB;  // stages of W0 requested ahead (a stage = 2 MFMA steps = 64 k; 2 * NB loads per lane)
@@ -54,7 +54,22 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
     // the wave index as a scalar: K ranges, stage counters and stage offsets then live in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
-    const int n0 = blockIdx.x * (16 * NB);
+    // several projections of the same X: their column blocks follow each other in the grid
+    GemmArgs p = p0;
+    int blk = blockIdx.x;
+    if (p0.n_sets > 0) {
+        int si = 0;
+        while (si + 1 < p0.n_sets && blk >= p0.set[si + 1].tile0) ++si;
+        blk -= p0.set[si].tile0;
+        p.W = p0.set[si].W;
+        p.ldw = p0.set[si].ldw;
+        p.Y = p0.set[si].Y;
+        p.ldy = p0.set[si].ldy;
+        p.V = p0.set[si].V;
+        p.B = p0.set[si].B;
+        p.N = p0.set[si].N;
+    }
+    const int n0 = blk * (16 * NB);
     LORA_TS(p.trace, 0);
 
     const E *V = static_cast<const E *>(p.V);
@@ -300,8 +315,17 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p) {
 }
 
 template <int TBLK, int NB>
-hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *timer) {
-    const int n_tiles = (a.N + 16 * NB - 1) / (16 * NB);
+hipError_t launch_sk(const GemmArgs &a0, hipStream_t stream, const KernelTimer *timer) {
+    GemmArgs a = a0;
+    int n_tiles = (a.N + 16 * NB - 1) / (16 * NB);
+    if (a.n_sets > 0) {
+        n_tiles = 0;
+        for (int i = 0; i < a.n_sets; ++i) {
+            a.set[i].tile0 = n_tiles;
+            n_tiles += (a.set[i].N + 16 * NB - 1) / (16 * NB);
+        }
+    }
+    if (n_tiles <= 0) return hipSuccess;
     const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t);
     auto kern = gemm_skinny_kernel<TBLK, NB>;
     static bool attr_set = false;
@@ -326,7 +350,7 @@ hipError_t launch_sk(const GemmArgs &a, hipStream_t stream, const KernelTimer *t
 
 // tblk: 16-row blocks (1, 2, 4, 6, 8); nb: 16-column blocks per workgroup (1, 2, 4; nb * tblk <= 8).
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer) {
-    if (a.T <= 0 || a.N <= 0) return hipSuccess;
+    if (a.T <= 0 || (a.n_sets == 0 && a.N <= 0)) return hipSuccess;
     if (a.Xpack == nullptr) return hipErrorInvalidValue;
 #define LORA_SK_CASE(TB_, NB_) \
     if (tblk == TB_ && nb == NB_) return launch_sk<TB_, NB_>(a, stream, timer)

@@ -431,12 +431,13 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
 }
 
-// (multi: one of several projections of the same X that go through one launch -- never decode-sized, so no copy of X)
+// (multi: several projections of the same X that go through one launch)
 int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream,
-              const lora_linear_desc *const *multi = nullptr, int n_multi = 0) {
+              const lora_linear_desc *const *multi = nullptr, int n_multi = 0, bool multi_pack = false) {
     bool ad = has_adapters(plan, d);
     for (int i = 0; i < n_multi; ++i) ad = ad || has_adapters(plan, multi[i]);
-    const bool pack = n_multi == 0 && choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny;
+    // (several projections: one copy of the X they share, in the first one's workspace)
+    const bool pack = n_multi == 0 ? choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny : multi_pack;
     if (!ad && !pack) return LORA_OK;
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
@@ -603,14 +604,27 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     return LORA_OK;
 }
 
-// Several projections of the same X in one tiled GEMM launch (their column tiles side by side in one grid: one
-// ramp, one set of whole rounds of tiles for all of them).  False: this batch / these options take another kernel.
-bool multi_takes_tiled(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
+// Several projections of the same X in one GEMM launch (their column tiles side by side in one grid: one ramp, one
+// set of whole rounds of tiles for all of them).  0: this batch / these options take the projections one by one;
+// 1: the tiled kernel; 2: the decode-sized kernel.
+int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
     int32_t ns[kMaxGemmSets];
-    for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
+    int64_t n_total = 0;
+    for (int i = 0; i < n; ++i) {
+        ns[i] = descs[i]->N;
+        n_total += descs[i]->N;
+    }
+    const GemmChoice one = choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype);
+    if (one.variant == kGemmSkinny) {  // decode-sized: the widest column block that still gives every CU a workgroup
+        int nb = 8 / one.tblk > 4 ? 4 : 8 / one.tblk;
+        while (nb > 1 && (n_total + 16 * nb - 1) / (16 * nb) < ctx->num_cu) nb >>= 1;
+        if (ctx->opt_skinny_nb >= 1) nb = one.nb;
+        *c = GemmChoice{kGemmSkinny, one.tblk, nb};
+        return 2;
+    }
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
-    if (plan->T <= kSkinnyMaxRows && descs[0]->dtype == LORA_DTYPE_BF16 && ctx->opt_gemm_variant < 0) return false;  // decode-sized
-    return c->variant != kGemmSkinny && !(c->variant >= kGemmPipe256x256w8 && c->variant <= kGemmPipe128x128w4);
+    if (c->variant == kGemmSkinny || (c->variant >= kGemmPipe256x256w8 && c->variant <= kGemmPipe128x128w4)) return 0;
+    return 1;
 }
 
 int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, const GemmChoice &c,
@@ -643,6 +657,12 @@ int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc
         if (rc != LORA_OK) return rc;
     }
     if (e.n_sets > 0) LORA_HIP(launch_expand(e, descs[0]->dtype, stream, nullptr));  // one launch for every projection that takes it
+    if (c.variant == kGemmSkinny) {  // (reads the copy of X the shrink launch left in the first projection's workspace)
+        const WorkspaceLayout w = workspace_layout(plan->T, descs[0]->K, descs[0]->N, plan->r_max, descs[0]->dtype);
+        a.Xpack = static_cast<unsigned char *>(descs[0]->workspace) + w.xpack_off;
+        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
+        return LORA_OK;
+    }
     LORA_HIP(launch_gemm_tile(a, descs[0]->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
 }
@@ -855,7 +875,8 @@ int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_
     if (guard.err != hipSuccess) return hip_fail(guard.err);
     hipStream_t s = static_cast<hipStream_t>(stream);
     GemmChoice c;
-    if (n == 1 || !multi_takes_tiled(ctx, plan, descs, n, &c)) {  // one after the other
+    const int kind = n == 1 ? 0 : multi_kind(ctx, plan, descs, n, &c);
+    if (kind == 0) {  // one after the other
         for (int i = 0; i < n; ++i) {
             int rc = do_shrink(ctx, plan, descs[i], s);
             if (rc == LORA_OK) rc = do_gemm(ctx, plan, descs[i], s);
@@ -863,7 +884,7 @@ int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_
         }
         return LORA_OK;
     }
-    const int rc = do_shrink(ctx, plan, descs[0], s, descs, n);  // one launch: the single projection's grid once per projection
+    const int rc = do_shrink(ctx, plan, descs[0], s, descs, n, kind == 2);  // one launch: the single projection's grid once per projection
     if (rc != LORA_OK) return rc;
     return do_gemm_multi(ctx, plan, descs, n, c, s);
 }
