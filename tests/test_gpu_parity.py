@@ -194,6 +194,14 @@ def test_linear_multi_projections_of_the_same_activations(dtype):
                     assert float(np.abs(got - single).max()) <= TOL[dtype] * rms
         print(f"{wl.name}: T={wl.T} err/rms {e:.2e}", flush=True)
         reset_options()
+        # one of the projections without an adapter table: the backbone product alone for that one
+        outs = rt.linear_multi(c, pl, X, [(up[0][1], up[0][2]), (up[1][1], None), (up[2][1], up[2][2])])
+        torch.cuda.synchronize()
+        base = to_f64(rt.bits_from_tensor(rt.linear(c, pl, X, up[1][1], None)))
+        torch.cuda.synchronize()
+        assert float(np.abs(to_f64(rt.bits_from_tensor(outs[1])) - base).max()) <= TOL[dtype] * float(np.sqrt((base ** 2).mean()))
+        check_against_oracle(wl, to_f64(rt.bits_from_tensor(outs[0])), p=0)
+        check_against_oracle(wl, to_f64(rt.bits_from_tensor(outs[2])), p=2)
         # argument errors: more projections than the limit, projections of different activations, one output twice
         ws = [rt.workspace(pl.T, 200, u[1].shape[0], pl.r_max, X.dtype, dev) for u in up]
         Ys = [torch.empty((pl.T, (u[1].shape[0] + 7) // 8 * 8), dtype=X.dtype, device=dev)[:, :u[1].shape[0]] for u in up]
