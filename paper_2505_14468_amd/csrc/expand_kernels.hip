@@ -8,7 +8,7 @@
 // than W0 in such a batch -- arrive through a two-deep, latency-bound pipeline.  Here the same work
 // is a weight-streaming problem laid out like the shrink:
 //
-//   * a workgroup = one work unit of the plan's list (<= 64 rows of one segment) x 1024 output columns
+//   * a workgroup = one work unit of the plan's list (<= 64 rows of one segment, <= 16 in small plans) x 1024 output columns
 //     (long enough a stream of B_a to pay for the unit's set-up: work list, row map, V);
 //   * the unit's rows of V (<= 64 x r, a few KB) are staged in LDS once; as MFMA operand they are
 //     read from there, so global loads carry B_a only;
@@ -20,7 +20,9 @@
 //   * every (row, column) with an adapter belongs to exactly one unit, so D is stored, not accumulated;
 //     rows without an adapter are never written and never read.  D costs 8 bytes of traffic per output
 //     element with an adapter, against the B_a bytes streamed at HBM speed instead of through a
-//     latency-bound pipeline; the host picks this path for batches of many small segments only.
+//     latency-bound pipeline; the host picks this path for batches of many small segments only;
+//   * units of long segments (flagged in the work list) are skipped when the GEMM computes those itself;
+//   * one launch can cover several projections of the same batch (ExpandSet), grid after grid.
 #include "kernels.h"
 
 namespace lora {

@@ -24,6 +24,12 @@
 // stores (8 lanes per row) and the MFMA operand reads (32 rows, one chunk column) spread
 // over all banks.
 //
+// The extension columns of a tile are described by a table in LDS, packed to the columns in use; its first
+// stage is requested in front of the last base stage.  When the adapter term of the short segments comes
+// from the expand kernel (GemmSet::D, long_rows > 0), only segments of long_rows rows and more are
+// extension columns here, and only the rows of the shorter ones add D in the epilogue.  One launch can
+// cover several projections of the same X (GemmSet): their column tiles follow each other in the grid.
+//
 // Workgroup -> tile mapping is XCD-aware: consecutive workgroup ids go round-robin to the 8
 // XCDs, so id % 8 picks the XCD and each XCD walks a contiguous, M-grouped range of tiles
 // that share W0 / X panels in its own L2.
