@@ -8,7 +8,8 @@ Consecutive steps rotate over several independent weight sets (backbone + adapte
 activations), as the layers of a model would, so that decode-sized runs stream their
 weights from HBM instead of re-reading one set from the caches.
 
-Prints ONE JSON line (see README for the fields).  Inputs are seeded and
+Prints ONE JSON line: metric, value (whole-step throughput), the roofline of the dominant kernel from live HIP event
+timings, per-kernel microseconds, and the CPU oracle timed beside it.  Inputs are seeded and
 synthetic (``workloads``), shaped like LoRA-on-Llama2 serving; nothing is read from disk
 except the optional ``profiles/hbm_traffic.json`` produced from rocprofv3 counter runs.
 """
