@@ -397,6 +397,32 @@ def test_strided_inputs_and_adapter_eviction():
     assert status == B.LORA_ERR_ADAPTER_NOT_RESIDENT
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_worked_example_derived_by_hand_is_exact(dtype):
+    """tests/golden/worked_example.json: three rows, one adapter, every number exactly representable -- the GPU's
+    output equals the hand-derived Y exactly, through the decode-sized kernel (bf16) and the tiled one (fp32, and
+    bf16 when forced)."""
+    import json
+    import os
+    import torch
+    from workloads.bits import bf16_bits_from_f32
+    from gpu_common import rt, ctx, reset_options
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.json")))
+    conv = (lambda a: bf16_bits_from_f32(np.asarray(a, np.float32))) if dtype == "bf16" else (lambda a: np.asarray(a, np.float32))
+    c = ctx()
+    dev = c.device
+    X, W0 = rt.tensor_from_bits(conv(fx["X"]), dev), rt.tensor_from_bits(conv(fx["W0"]), dev)
+    table = rt.AdapterTable([rt.tensor_from_bits(conv(fx["A0"]), dev)], [rt.tensor_from_bits(conv(fx["B0"]), dev)],
+                            np.asarray(fx["scale"], np.float32), dev)
+    pl = rt.plan(c, np.asarray(fx["req_adapter"], np.int32), np.asarray(fx["req_ntok"], np.int32), np.asarray(fx["rank"], np.int32), 8)
+    for variant in (None, "tile_64x64", "tile_128x192"):
+        c.set_option("gemm_variant", VARIANTS[variant] if variant else -1)
+        Y = rt.linear(c, pl, X, W0, table)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_f64(rt.bits_from_tensor(Y)), np.asarray(fx["Y"], np.float64)), variant
+    reset_options()
+
+
 def test_empty_batch_is_a_noop():
     import torch
     from gpu_common import ctx, rt

@@ -12,6 +12,7 @@ exact or a re-association bound:
   P7 rank-one          closed form with unit-vector adapters
   P8 output RMS        closed form of the benchmark distributions
   P9 library           fp64 matmul of the same three products
+  P10 worked example   a three-row layer derived by hand (tests/golden/worked_example.json)
 """
 import itertools
 
@@ -185,6 +186,23 @@ def test_p9_library_matmul(dtype):
         assert np.all(V[m, wl.ranks[a]:] == 0)
     rms = np.sqrt((want ** 2).mean())
     assert np.abs(Y - want).max() <= 1e-12 * rms
+
+
+def _worked_example(dtype):
+    import json
+    import os
+    from workloads.bits import bf16_bits_from_f32
+    fx = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.json")))
+    conv = (lambda a: bf16_bits_from_f32(np.asarray(a, np.float32))) if dtype == "bf16" else (lambda a: np.asarray(a, np.float32))
+    return fx, conv
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_p10_worked_example_derived_by_hand(dtype):
+    fx, conv = _worked_example(dtype)
+    Y = oracle_linear(conv(fx["X"]), conv(fx["W0"]), fx["req_adapter"], fx["req_ntok"], [conv(fx["A0"])], [conv(fx["B0"])],
+                      np.asarray(fx["rank"], np.int32), np.asarray(fx["scale"], np.float32))
+    assert np.array_equal(Y, np.asarray(fx["Y"], np.float64))
 
 
 def test_row_subset_matches_full_and_errors():
