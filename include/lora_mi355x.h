@@ -11,7 +11,8 @@
  *     Y[t,:] = X[t,:] W0                            for requests with adapter -1
  *
  * Conventions
- *   - Plain C, no exceptions, no global state.  Every function returns an int:
+ *   - Plain C, no exceptions, no mutable global state (the one file-scope
+ *     object is the scratch array of lora_linear_static()).  Every function returns an int:
  *     LORA_OK (0) or a negative lora_status; lora_strerror() names it.
  *   - "host" / "device" is stated for every pointer.  The library never
  *     allocates device memory and never synchronises the stream unless a
@@ -70,6 +71,7 @@ typedef enum lora_status {
 #define LORA_MAX_REQUESTS 65536   /* requests per batch                                  */
 #define LORA_MAX_ADAPTERS 65536   /* adapter slots in a table                            */
 #define LORA_MAX_RANK 512         /* rank of one adapter; ranks are multiples of 8       */
+#define LORA_STATIC_SCRATCH_BYTES (32u << 20) /* workspace limit of lora_linear_static()     */
 
 /*
  * Adapter pointer table.  A table, not one packed tensor, because adapters are
@@ -79,6 +81,11 @@ typedef enum lora_status {
  * DEVICE arrays of n_adapters entries; A[a] / B[a] are DEVICE pointers to that
  * adapter's weights (16-byte aligned), or NULL for a slot that is not resident.
  * The caller owns everything and may edit entries between calls (stream-ordered).
+ * The ranks are not part of the table: a rank belongs to the adapter, not to one
+ * projection's weights, so the rank array (and r_max, the row stride of the
+ * intermediate) is an argument of lora_plan*(), which fixes them for every
+ * projection and layer that uses the plan; a table entry must then point at
+ * weights of that rank.
  */
 typedef struct lora_adapter_table_t {
     int32_t n_adapters;
@@ -117,7 +124,7 @@ typedef struct lora_plan_t {
     const int32_t *unit_rec;    /* device [(T/16+seg_cap+8)*4] work units: adapter, rank (| 1<<16: segment of >= 64 rows), first slot, rows */
     const int32_t *ext_rec;     /* device [ext_cap*4] per 8 ranks: adapter, rank<<16|j0, slot_lo, slot_hi */
     const int32_t *tok_off;     /* device [n_req+1]  first row of every request             */
-    int32_t *scalars;           /* device [8]: n_seg, status, ext_total, n_units, ...       */
+    int32_t *scalars;           /* device [8]: n_seg, build status, ext_total, n_units, T, evicted flag */
 } lora_plan_t;
 
 typedef struct lora_linear_desc {
@@ -139,22 +146,27 @@ typedef struct lora_linear_desc {
 /* ---- context ----------------------------------------------------------- */
 
 /* Creates a context on device `device_ordinal` (host int).  It caches device
- * properties and owns a small pinned host staging ring used by lora_plan();
- * nothing else.  *out is set to NULL on failure.  Errors: INVALID_ARG, HIP. */
+ * properties, owns a small pinned host staging ring used by lora_plan(), and
+ * does the per-device set-up of the kernels (dynamic-LDS grants; the address
+ * of lora_linear_static()'s scratch on that device), so that no later call
+ * has to: create contexts outside stream capture.  *out is set to NULL on
+ * failure.  Errors: INVALID_ARG, HIP. */
 int lora_ctx_create(lora_ctx **out, int device_ordinal);
 int lora_ctx_destroy(lora_ctx *ctx);
 
-/* Tuning overrides for experiments ("gemm_variant" = 0 tile 128x128,
- * 1 256x128, 2 256x256 on 8 waves, 3 64x64, 4 the decode-sized kernel (up to
- * 128 rows, bf16), 5 256x256 on 4 waves, 6 / 7 / 8 the direct-to-LDS pipeline
- * 256x256 on 8 / on 4 waves / 128x128, 9 128x192, 10 256x192, 11 256x224; "skinny_nb",
- * "skinny_max_rows", "plan_fused_rows", "plan_variant" = 1: never the
- * one-lane-per-request plan kernels, "expand_split" = 0 / 1: adapter term always
- * computed inside the GEMM / by the separate expand kernel whenever the
- * workspace has room for it, "shrink_rank_block" = 8 / 16 / 32 / 64);
- * value < 0 restores the built-in heuristic.  Results never depend on them
- * beyond fp32 summation order.  Errors: INVALID_ARG for an unknown name or a
- * value the option does not take. */
+/* Overrides of the built-in kernel choices, for tests and measurements:
+ * "gemm_variant" (0 tile 128x128, 1 256x128, 2 256x256 on 8 waves, 3 64x64,
+ * 4 the decode-sized kernel (bf16, up to 128 rows), 5 256x256 on 4 waves,
+ * 9 128x192, 10 256x192, 11 256x224), "skinny_nb" (16-column blocks per
+ * workgroup of the decode-sized kernel: 1, 2, 4), "skinny_max_rows" (0: never
+ * the decode-sized kernel), "plan_variant" (1: never the one-lane-per-request
+ * plan kernels), "plan_fused_rows" (most rows for which one workgroup builds
+ * the whole plan), "expand_split" (0 / 1: adapter term always computed inside
+ * the GEMM / by the separate expand kernel whenever the workspace has room
+ * for it), "shrink_rank_block" (8 / 16 / 32 / 64).  value < 0 restores the
+ * built-in choice.  Results never depend on them beyond fp32 summation order.
+ * Not thread-safe against concurrent calls on the same ctx.  Errors:
+ * INVALID_ARG for an unknown name or a value the option does not take. */
 int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value);
 
 /* ---- step a1: segment / indptr builder ---------------------------------- */
@@ -195,10 +207,14 @@ int lora_plan_device(lora_ctx *ctx, const int32_t *req_adapter, const int32_t *r
                      const int32_t *adapter_rank, int32_t n_adapters, int32_t r_max, int64_t T_expected,
                      void *plan_buf, size_t plan_buf_bytes, lora_stream_t stream, lora_plan_t *out);
 
-/* Synchronises `stream` and returns the plan's device-side status (LORA_OK or
- * the negative lora_status recorded by the build or by a later kernel, e.g.
- * ADAPTER_NOT_RESIDENT for a NULL table entry); *n_seg_out (HOST, may be NULL)
- * receives the number of segments. */
+/* Synchronises `stream` and returns the plan's device-side status: the
+ * negative lora_status recorded by the build if it failed (every kernel given
+ * such a plan does nothing); else ADAPTER_NOT_RESIDENT if a layer kernel since
+ * the build met a NULL table entry of an adapter the batch uses (that call
+ * left the adapter term of those rows out -- their Y is the backbone product
+ * or undefined -- and every other row, projection and later call is
+ * unaffected; the flag stays set until the plan is rebuilt); else LORA_OK.
+ * *n_seg_out (HOST, may be NULL) receives the number of segments. */
 int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t stream, int32_t *n_seg_out);
 
 /* ---- steps a2-a4: the layer --------------------------------------------- */
@@ -228,16 +244,37 @@ size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, in
  * Asynchronous on `stream`.  No-op when T == 0. */
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
-/* a3 + a4, base GEMM with the expand fused before the single store of Y:
- * Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V (and the copy of X) taken from
- * the workspace as lora_shrink() left them for the same plan, desc->X and K.  The expand runs as extra K-steps of the
- * same MFMA loop, so each Y element is written exactly once. */
+/* a3 + a4, base GEMM with the adapter term added before the single rounding and
+ * store of Y: Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V (and the copy of
+ * X) taken from the workspace as lora_shrink() left them for the same plan,
+ * desc->X and K.  Two forms, same result up to fp32 summation order: the expand
+ * as extra K-steps of the GEMM's own MFMA loop (always, with a workspace of the
+ * minimal size; and for segments of 64 rows and more up to rank 64), or -- with
+ * a workspace of the preferred size and many small segments -- a
+ * weight-streaming kernel of its own that leaves the term in fp32 in the
+ * workspace ([T, N], written and read once), which the GEMM's epilogue adds to
+ * its fp32 accumulators.  Either way every element of Y is rounded and written
+ * exactly once. */
 int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* The whole layer: lora_shrink() then lora_gemm_expand() on `stream`.  Returns
  * after enqueueing.  Errors (all found before the first launch): INVALID_ARG,
  * PLAN, SHAPE, ALIGNMENT, WORKSPACE_TOO_SMALL; HIP if a launch fails. */
 int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
+
+/* lora_linear() for callers that cannot allocate or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): desc->workspace must be NULL and desc->workspace_bytes 0; the
+ * kernels use a static device array of LORA_STATIC_SCRATCH_BYTES that the
+ * library's code object holds on every GPU it runs on until the process ends.
+ * No allocation, no memset, no synchronisation: launches only.  Problems whose
+ * lora_linear_workspace_bytes() exceeds LORA_STATIC_SCRATCH_BYTES are rejected
+ * with WORKSPACE_TOO_SMALL.  All calls on one GPU share that array (it keeps
+ * the last call's contents; nothing in it needs to start at zero): calls that
+ * overlap in time on one GPU race -- order them on one stream.  Same result as
+ * lora_linear() with a workspace of LORA_STATIC_SCRATCH_BYTES.  Other errors:
+ * as lora_linear(). */
+int lora_linear_static(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* Several projections of the SAME activations in one call -- fused QKV, gate + up
  * of a decoder layer (all seven of which carry LoRA here): descs (HOST array
@@ -258,10 +295,14 @@ int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_
  * lora_profile_end() every kernel the library launches through `ctx` is
  * bracketed by its own pair of HIP events (at most max_launches per kernel
  * kind; later launches run untimed).  lora_profile_end() synchronises `stream`
- * and writes, for the four kernel kinds in the order {plan segments, plan
- * fill, shrink, GEMM+expand}, the average execution time in microseconds into
- * avg_us[4] (HOST) and the number of timed launches into counts[4] (HOST).
- * Errors: INVALID_ARG, HIP. */
+ * and writes, for the LORA_PROFILE_KINDS kernel kinds in the order {plan
+ * segments, plan fill, first layer kernel (shrink; for decode-sized batches
+ * the weight-streaming kernel), second layer kernel (GEMM with the fused
+ * expand; for decode-sized batches the reduction + expand), separate expand
+ * kernel}, the average execution time in microseconds into
+ * avg_us[LORA_PROFILE_KINDS] (HOST) and the number of timed launches into
+ * counts[LORA_PROFILE_KINDS] (HOST).  Errors: INVALID_ARG, HIP. */
+#define LORA_PROFILE_KINDS 5
 int lora_profile_begin(lora_ctx *ctx, int max_launches);
 int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_t *counts);
 

@@ -35,7 +35,7 @@ EXPORTS = [
     "lora_ctx_create", "lora_ctx_destroy", "lora_ctx_set_option",
     "lora_plan_validate", "lora_plan_bytes", "lora_plan", "lora_plan_device", "lora_plan_status",
     "lora_linear_workspace_bytes", "lora_linear_workspace_bytes_preferred", "lora_shrink", "lora_gemm_expand", "lora_linear",
-    "lora_linear_multi",
+    "lora_linear_multi", "lora_linear_static",
     "lora_profile_begin", "lora_profile_end",
     "lora_gemm_kernel_name", "lora_strerror", "lora_last_hip_error",
 ]
@@ -98,7 +98,7 @@ def lib():
         L.lora_linear_workspace_bytes.restype = C.c_size_t
         L.lora_linear_workspace_bytes_preferred.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.lora_linear_workspace_bytes_preferred.restype = C.c_size_t
-        for name in ("lora_shrink", "lora_gemm_expand", "lora_linear"):
+        for name in ("lora_shrink", "lora_gemm_expand", "lora_linear", "lora_linear_static"):
             getattr(L, name).argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(lora_linear_desc), C.c_void_p]
         L.lora_linear_multi.argtypes = [C.c_void_p, C.POINTER(lora_plan_t), C.POINTER(C.POINTER(lora_linear_desc)), C.c_int32,
                                         C.c_void_p]
@@ -241,7 +241,13 @@ def lora_linear(ctx, plan, desc, stream: int, *, raw: bool = False):
     return _stage("lora_linear", ctx, plan, desc, stream, raw)
 
 
+def lora_linear_static(ctx, plan, desc, stream: int, *, raw: bool = False):
+    """desc.workspace must be NULL / 0: the library's static scratch is the workspace."""
+    return _stage("lora_linear_static", ctx, plan, desc, stream, raw)
+
+
 LORA_MAX_MULTI = 4
+LORA_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 def lora_linear_multi(ctx, plan, descs, stream: int, *, raw: bool = False):
@@ -255,7 +261,7 @@ def lora_linear_multi(ctx, plan, descs, stream: int, *, raw: bool = False):
     return None
 
 
-PROFILE_KINDS = ("plan_segments", "plan_fill", "shrink", "gemm_expand")
+PROFILE_KINDS = ("plan_segments", "plan_fill", "shrink", "gemm_expand", "expand")
 
 
 def lora_profile_begin(ctx, max_launches: int) -> None:
@@ -263,9 +269,9 @@ def lora_profile_begin(ctx, max_launches: int) -> None:
 
 
 def lora_profile_end(ctx, stream: int) -> dict:
-    """{kind: (average microseconds, timed launches)} for the four kernel kinds."""
-    avg = (C.c_double * 4)()
-    cnt = (C.c_int32 * 4)()
+    """{kind: (average microseconds, timed launches)} for every kernel kind."""
+    avg = (C.c_double * len(PROFILE_KINDS))()
+    cnt = (C.c_int32 * len(PROFILE_KINDS))()
     _check(lib().lora_profile_end(C.c_void_p(ctx), C.c_void_p(stream), avg, cnt), "lora_profile_end")
     return {k: (float(avg[i]), int(cnt[i])) for i, k in enumerate(PROFILE_KINDS)}
 

@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kExWaves * 64, SMALL ? 4 : 2) void expand_kernel(Ex
     const E *Ba = static_cast<const E *>(p.B[a]);
     LORA_TS(p.trace, 1);  // work-list record read
     if (Ba == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
-        if (threadIdx.x == 0) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+        if (threadIdx.x == 0) atomicMin(&p.plan.scalars[kScEvicted], kErrNotResident);
         const int n_lo = cg * kExCols, n_hi = min(n_lo + kExCols, p.N);
         for (int e = threadIdx.x; e < nrows * (n_hi - n_lo); e += kExWaves * 64) {
             const int t = e / (n_hi - n_lo), n = n_lo + e - t * (n_hi - n_lo);
@@ -310,6 +310,18 @@ size_t expand_smem_bytes(int r_max, int dtype) {
     return (size_t)kShrinkRows * (size_t)(r_max / ce + kExPad) * 16;
 }
 
+// (ranks above ~480 need more than the default 64 KB of dynamic LDS: granted per kernel and device before the first launch)
+hipError_t init_expand_kernels() {
+    const void *fns[4] = {reinterpret_cast<const void *>(expand_kernel<__bf16, true>), reinterpret_cast<const void *>(expand_kernel<__bf16, false>),
+                          reinterpret_cast<const void *>(expand_kernel<float, true>), reinterpret_cast<const void *>(expand_kernel<float, false>)};
+    for (int i = 0; i < 4; ++i) {
+        const size_t smem = expand_smem_bytes(kMaxRank, i < 2 ? 1 : 0);
+        hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, const KernelTimer *timer) {
     if (a0.max_units <= 0 || (a0.n_sets == 0 && a0.N <= 0)) return hipSuccess;
     ExpandArgs a = a0;
@@ -327,17 +339,6 @@ hipError_t launch_expand(const ExpandArgs &a0, int dtype, hipStream_t stream, co
     if (grid <= 0) return hipSuccess;
     const size_t smem = expand_smem_bytes(a.r_max, dtype);
     const bool small = a.unit_rows <= kShrinkRowsSmall;
-    const void *fn = dtype == 1 ? (small ? reinterpret_cast<const void *>(expand_kernel<__bf16, true>)
-                                         : reinterpret_cast<const void *>(expand_kernel<__bf16, false>))
-                                : (small ? reinterpret_cast<const void *>(expand_kernel<float, true>)
-                                         : reinterpret_cast<const void *>(expand_kernel<float, false>));
-    static size_t attr_bytes[4] = {0, 0, 0, 0};  // more than the default 64 KB of dynamic LDS (ranks above ~480)
-    size_t &have = attr_bytes[(dtype == 1 ? 2 : 0) + (small ? 1 : 0)];
-    if (smem > 64 * 1024 && smem > have) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        have = smem;
-    }
     auto launch = [&](const ExpandArgs &b) {
         const dim3 g((unsigned)grid), t(kExWaves * 64);
         if (dtype == 1)

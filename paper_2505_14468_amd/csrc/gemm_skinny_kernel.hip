@@ -182,7 +182,7 @@ __global__ __launch_bounds__(kSkThreads) void gemm_skinny_kernel(GemmArgs p0) {
         for (int u = 0; u < 2; ++u) {
             const int a = rec[u].x, r = rec[u].y >> 16, j = rec[u].y & 0xffff;
             const bool wok = bp[u] != nullptr;
-            if (a >= 0 && !wok) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);  // slot emptied after the plan
+            if (a >= 0 && !wok) atomicMin(&p.plan.scalars[kScEvicted], kErrNotResident);  // slot emptied after the plan
             const E *bsrc = wok ? static_cast<const E *>(bp[u]) + j : W;  // W: some in-bounds address for the dropped loads
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
@@ -328,13 +328,6 @@ hipError_t launch_sk(const GemmArgs &a0, hipStream_t stream, const KernelTimer *
     if (n_tiles <= 0) return hipSuccess;
     const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t);
     auto kern = gemm_skinny_kernel<TBLK, NB>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
 #ifdef LORA_TRACE
     return trace_launch("gemm_skinny", n_tiles, [&](long long *buf) {
         GemmArgs b = a;
@@ -346,7 +339,28 @@ hipError_t launch_sk(const GemmArgs &a0, hipStream_t stream, const KernelTimer *
 #endif
 }
 
+template <int TBLK, int NB>
+hipError_t init_sk() {
+    const size_t smem = (size_t)kSkWaves * NB * TBLK * 256 * sizeof(float) + (size_t)kSkWaves * NB * 16 * 8 * sizeof(chunk_t);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_skinny_kernel<TBLK, NB>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+}
+
 }  // namespace
+
+hipError_t init_gemm_skinny_kernels() {
+    hipError_t e = init_sk<1, 1>();
+    if (e == hipSuccess) e = init_sk<1, 2>();
+    if (e == hipSuccess) e = init_sk<1, 4>();
+    if (e == hipSuccess) e = init_sk<2, 1>();
+    if (e == hipSuccess) e = init_sk<2, 2>();
+    if (e == hipSuccess) e = init_sk<2, 4>();
+    if (e == hipSuccess) e = init_sk<4, 1>();
+    if (e == hipSuccess) e = init_sk<4, 2>();
+    if (e == hipSuccess) e = init_sk<6, 1>();
+    if (e == hipSuccess) e = init_sk<8, 1>();
+    return e;
+}
 
 // tblk: 16-row blocks (1, 2, 4, 6, 8); nb: 16-column blocks per workgroup (1, 2, 4; nb * tblk <= 8).
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer) {

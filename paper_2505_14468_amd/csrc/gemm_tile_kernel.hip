@@ -166,7 +166,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                     e_hi[it] = min(rec.w - m0, BM);
                     e_ptr[it] = b + e_j[it];
                 } else {
-                    atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+                    atomicMin(&p.plan.scalars[kScEvicted], kErrNotResident);
                 }
             }
             const unsigned long long used = __builtin_amdgcn_ballot_w64(e_ptr[it] != nullptr);
@@ -549,16 +549,29 @@ hipError_t launch_tile(const GemmArgs &a0, hipStream_t stream, const KernelTimer
     if (total <= 0) return hipSuccess;
     const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);
     auto kern = gemm_tile_kernel<E, BM, BN, WM, WN>;
-    static bool attr_set = false;  // per instantiation
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const long grid = ((total + 7) / 8) * 8;
     const int group_m = 8;
     return launch_kernel(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, timer, a, tiles_m, tiles_n, group_m);
+}
+
+// Dynamic LDS above the default 64 KB has to be granted per kernel and device before the first launch.
+template <typename E, int BM, int BN, int WM, int WN>
+hipError_t init_tile() {
+    const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tile_kernel<E, BM, BN, WM, WN>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+}
+template <typename E>
+hipError_t init_tiles() {
+    hipError_t e = init_tile<E, 64, 64, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 128, 128, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 128, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 256, 4, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 256, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 128, 192, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 192, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 224, 4, 1>();
+    return e;
 }
 
 template <typename E>
@@ -586,6 +599,12 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
 }
 
 }  // namespace
+
+hipError_t init_gemm_tile_kernels() {
+    hipError_t e = init_tiles<__bf16>();
+    if (e == hipSuccess) e = init_tiles<float>();
+    return e;
+}
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer) {
     return dtype == 1 ? launch_variant<__bf16>(a, variant, stream, timer) : launch_variant<float>(a, variant, stream, timer);

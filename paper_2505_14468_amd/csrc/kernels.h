@@ -4,10 +4,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <stdio.h>
-#include <stdlib.h>
-#include <string.h>
-
 #include "common.hiph"
 
 namespace lora {
@@ -46,49 +42,10 @@ struct KernelTimer {
     hipEvent_t start, stop;
 };
 
-// ---- optional phase trace: builds with -DLORA_TRACE only (a development aid) -------------------------------
-// Thread 0 of every workgroup stamps the constant 100 MHz clock into trace[blockIdx.x * 8 + slot]; with the
-// environment variable LORA_TRACE set to a kernel's name, that kernel's 30th launch prints the stamps in
-// microseconds relative to the earliest one (the launches are synchronous then).
 #ifdef LORA_TRACE
-#define LORA_TS(buf, i)                                                                     \
-    do {                                                                                    \
-        if ((buf) != nullptr && threadIdx.x == 0) (buf)[blockIdx.x * 8 + (i)] = wall_clock64(); \
-    } while (0)
-// the same from the first thread of wave `w` (how far apart the waves of a workgroup finish a phase)
-#define LORA_TS_WAVE(buf, i, w)                                                                              \
-    do {                                                                                                     \
-        if ((buf) != nullptr && (int)threadIdx.x == (w) * 64) (buf)[blockIdx.x * 8 + (i)] = wall_clock64(); \
-    } while (0)
-template <typename Launch>
-inline hipError_t trace_launch(const char *name, long grid, Launch launch) {
-    const char *want = getenv("LORA_TRACE");
-    if (want == nullptr || strcmp(want, name) != 0) return launch(nullptr);
-    constexpr long kMaxWgs = 8192;
-    static long long *dbuf = nullptr;
-    static int calls = 0;
-    if (dbuf == nullptr && hipMalloc(&dbuf, 8 * 8 * kMaxWgs) != hipSuccess) return hipErrorOutOfMemory;
-    (void)hipMemset(dbuf, 0, 8 * 8 * kMaxWgs);
-    (void)hipDeviceSynchronize();
-    hipError_t e = grid <= kMaxWgs ? launch(dbuf) : launch(nullptr);
-    (void)hipDeviceSynchronize();
-    if (++calls == 30 && grid <= kMaxWgs) {
-        static long long h[8 * kMaxWgs];
-        (void)hipMemcpy(h, dbuf, sizeof(long long) * 8 * grid, hipMemcpyDeviceToHost);
-        long long t0 = -1;
-        for (long g = 0; g < grid; ++g)
-            if (h[g * 8] && (t0 < 0 || h[g * 8] < t0)) t0 = h[g * 8];
-        const long stride = getenv("LORA_TRACE_ALL") ? 1 : (grid > 48 ? grid / 24 : 1);  // a sample of the workgroups, or all
-        for (long g = 0; g < grid; g += stride) {
-            if (!h[g * 8]) continue;
-            printf("trace %s wg %ld:", name, g);
-            for (int i = 0; i < 8; ++i) printf(" %6.2f", h[g * 8 + i] ? (h[g * 8 + i] - t0) * 0.01 : -1.0);
-            printf("\n");
-        }
-        fflush(stdout);
-    }
-    return e;
-}
+}  // namespace lora
+#include "trace_build.h"  // phase stamps: trace builds only
+namespace lora {
 #else
 #define LORA_TS(buf, i) \
     do {                \
@@ -229,9 +186,7 @@ enum GemmVariant {
     kGemmTile64x64 = 3,
     kGemmSkinny = 4,
     kGemmTile256x256w4 = 5,  // 256x256 tile on 4 waves (128x128 per wave)
-    kGemmPipe256x256w8 = 6,  // direct-to-LDS software pipeline, 256x256 tile on 8 waves
-    kGemmPipe256x256w4 = 7,  // same on 4 waves (128x128 per wave)
-    kGemmPipe128x128w4 = 8,  // 128x128 tile on 4 waves
+    // (6, 7, 8: not in use)
     kGemmTile128x192 = 9,    // 128 rows x 192 columns on 4 waves (fills the chip where 256x128 leaves CUs idle)
     kGemmTile256x192 = 10,   // 256 x 192 on 4 waves (a tile count just below a whole number of rounds where 256x256 is just above)
     kGemmTile256x224 = 11,   // 256 x 224 on 4 waves of 64 x 224 (likewise)
@@ -239,8 +194,13 @@ enum GemmVariant {
 };
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
-hipError_t launch_gemm_pipe(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
 hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer);
+
+// Dynamic-LDS grants of every kernel instantiation, for the current device (context creation).
+hipError_t init_gemm_tile_kernels();
+hipError_t init_shrink_kernels();
+hipError_t init_expand_kernels();
+hipError_t init_gemm_skinny_kernels();
 
 // Geometry of the skinny kernel shared with the host (workspace sizing).
 constexpr int kSkinnyMaxRows = 128;  // rows it accepts

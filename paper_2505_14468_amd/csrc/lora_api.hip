@@ -19,6 +19,11 @@ static_assert(LORA_ERR_ADAPTER_NOT_RESIDENT == kErrNotResident, "status codes ou
 static_assert(LORA_ERR_RANK_TOO_LARGE == kErrRankTooLarge, "status codes out of sync");
 static_assert(LORA_ERR_SHAPE == kErrShape, "status codes out of sync");
 static_assert(LORA_MAX_MULTI == kMaxGemmSets, "projection limit out of sync");
+static_assert(LORA_MAX_RANK == kMaxRank, "rank limit out of sync");
+
+// Scratch of lora_linear_static(): the layer's workspace for callers that cannot bring or allocate one.  One copy
+// per GPU, at its own address (looked up once per context, on that context's device), held until the process ends.
+static __device__ __align__(256) unsigned char scratch[LORA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -35,7 +40,8 @@ int hip_fail(hipError_t e) {
         if (e_ != hipSuccess) return hip_fail(e_); \
     } while (0)
 
-enum ProfKind { kProfPlanSegments = 0, kProfPlanFill = 1, kProfShrink = 2, kProfGemm = 3, kProfKinds = 4 };
+enum ProfKind { kProfPlanSegments = 0, kProfPlanFill = 1, kProfShrink = 2, kProfGemm = 3, kProfExpand = 4, kProfKinds = 5 };
+static_assert(kProfKinds == LORA_PROFILE_KINDS, "profile kinds out of sync");
 
 constexpr int kRingSlots = 4;
 constexpr size_t kRingSlotInts = 2 * (size_t)LORA_MAX_REQUESTS + LORA_MAX_ADAPTERS;
@@ -47,6 +53,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct lora_ctx {
     int device = 0;
     int num_cu = 256;
+    unsigned char *static_scratch = nullptr;  // this device's copy of `scratch`
     // pinned staging ring for lora_plan's small host arrays
     int32_t *ring = nullptr;
     hipEvent_t ring_event[kRingSlots] = {};
@@ -379,7 +386,8 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     return w;
 }
 
-int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, bool need_ctx = true) {
+// (check_ws = false: the entry point that brings its own workspace; d->workspace is then not looked at)
+int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, bool need_ctx = true, bool check_ws = true) {
     if (!plan || !d) return LORA_ERR_INVALID_ARG;
     if (plan->magic != kPlanMagic || plan->T < 0 || !plan->scalars) return LORA_ERR_PLAN;
     if (plan->unit_rows != kShrinkRows && plan->unit_rows != kShrinkRowsSmall) return LORA_ERR_PLAN;
@@ -395,14 +403,22 @@ int check_linear(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
     if (plan->T > 0) {
         if (!d->X || !d->W0 || !d->Y) return LORA_ERR_INVALID_ARG;
         if (((uintptr_t)d->X | (uintptr_t)d->W0 | (uintptr_t)d->Y) & 15u) return LORA_ERR_ALIGNMENT;
-        if (d->Y == d->X || d->Y == d->W0) return LORA_ERR_INVALID_ARG;
+        // Y must not overlap X, W0 or the workspace (extents from the leading dimensions)
+        const uintptr_t y0 = (uintptr_t)d->Y, y1 = y0 + (uintptr_t)(((plan->T - 1) * d->ldy + d->N) * es);
+        const uintptr_t x0 = (uintptr_t)d->X, x1 = x0 + (uintptr_t)(((plan->T - 1) * d->ldx + d->K) * es);
+        const uintptr_t w0 = (uintptr_t)d->W0, w1 = w0 + (uintptr_t)(((int64_t)(d->N - 1) * d->ldw + d->K) * es);
+        if ((y0 < x1 && x0 < y1) || (y0 < w1 && w0 < y1)) return LORA_ERR_INVALID_ARG;
+        if (check_ws && d->workspace) {
+            const uintptr_t s0 = (uintptr_t)d->workspace, s1 = s0 + d->workspace_bytes;
+            if ((s0 < y1 && y0 < s1) || (s0 < x1 && x0 < s1) || (s0 < w1 && w0 < s1)) return LORA_ERR_INVALID_ARG;
+        }
     }
     if (d->tbl) {
         if (d->tbl->n_adapters < plan->n_adapters) return LORA_ERR_INVALID_ARG;
         if (plan->n_adapters > 0 && (!d->tbl->A || !d->tbl->B || !d->tbl->scale)) return LORA_ERR_INVALID_ARG;
     }
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
-    if (plan->T > 0) {
+    if (plan->T > 0 && check_ws) {
         if (!d->workspace) return LORA_ERR_INVALID_ARG;
         if ((uintptr_t)d->workspace & 255u) return LORA_ERR_ALIGNMENT;
         if (d->workspace_bytes < w.total) return LORA_ERR_WORKSPACE_TOO_SMALL;
@@ -533,7 +549,7 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
         // of an M tile, ~2 us each, against 8 bytes of D traffic per element and the units' reads of B_a saved: worth
         // it up to rank 64 -- C3 gate_proj 150 -> 140 us; at rank 128, C4, 428 -> 434 us) and takes the short
         // segments' from D; the other kernels take all of it from D.
-        const bool tiled = !(variant >= kGemmPipe256x256w8 && variant <= kGemmPipe128x128w4) && plan->r_max <= 64;
+        const bool tiled = plan->r_max <= 64;
         e.skip_long = tiled ? 1 : 0;
         if (collect != nullptr) {
             const int i = collect->n_sets;
@@ -542,7 +558,9 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
             collect->set[i] = ExpandSet{e.V, e.B, e.D, e.ldd, e.N, e.skip_long, 0, 0};
             collect->n_sets = i + 1;
         } else {
-            LORA_HIP(launch_expand(e, d->dtype, stream, expand_timer));
+            KernelTimer et;
+            const bool etimed = expand_timer != nullptr && next_timer(ctx, kProfExpand, &et);
+            LORA_HIP(launch_expand(e, d->dtype, stream, etimed ? &et : nullptr));
         }
         if (tiled) {
             g.long_rows = kLongSegRows;
@@ -562,19 +580,11 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
-    if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4) {  // these address W0 / X with 31-bit byte offsets
-        const int64_t es = d->dtype == LORA_DTYPE_BF16 ? 2 : 4;
-        if ((int64_t)d->N * d->ldw * es >= (1ll << 31) || plan->T * d->ldx * es >= (1ll << 31)) c.variant = kGemmTile256x256;
-    }
-    KernelTimer timer;
+    KernelTimer timer, etimer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
-    // (with a separate expand kernel one event pair brackets both kernels: start with the first, stop with the second)
-    KernelTimer first = timer, second = timer;
-    first.stop = nullptr;
-    second.start = nullptr;
     GemmSet g;
     bool split = false;
-    const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &first : nullptr, &g, &split);
+    const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &etimer : nullptr, &g, &split);
     if (rc != LORA_OK) return rc;
     GemmArgs a;
     a.plan = view_of(plan);
@@ -594,11 +604,9 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.T = (int32_t)plan->T;
     a.K = d->K;
     a.N = d->N;
-    const KernelTimer *tg = !timed ? nullptr : (split ? &second : &timer);
+    const KernelTimer *tg = timed ? &timer : nullptr;
     if (c.variant == kGemmSkinny)
         LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, tg));
-    else if (c.variant >= kGemmPipe256x256w8 && c.variant <= kGemmPipe128x128w4)
-        LORA_HIP(launch_gemm_pipe(a, d->dtype, c.variant, stream, tg));
     else
         LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
     return LORA_OK;
@@ -623,7 +631,7 @@ int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
         return 2;
     }
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
-    if (c->variant == kGemmSkinny || (c->variant >= kGemmPipe256x256w8 && c->variant <= kGemmPipe128x128w4)) return 0;
+    if (c->variant == kGemmSkinny) return 0;
     return 1;
 }
 
@@ -648,7 +656,7 @@ int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc
     a.N = 0;
     a.n_sets = n;
     KernelTimer timer;
-    const bool timed = next_timer(ctx, kProfGemm, &timer);  // (the GEMM alone: the expand launches are not bracketed)
+    const bool timed = next_timer(ctx, kProfGemm, &timer);
     ExpandArgs e;
     e.n_sets = 0;
     for (int i = 0; i < n; ++i) {
@@ -656,7 +664,11 @@ int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc
         const int rc = prepare_set(ctx, plan, descs[i], c.variant, stream, nullptr, &a.set[i], &split, &e);
         if (rc != LORA_OK) return rc;
     }
-    if (e.n_sets > 0) LORA_HIP(launch_expand(e, descs[0]->dtype, stream, nullptr));  // one launch for every projection that takes it
+    if (e.n_sets > 0) {  // one launch for every projection that takes it
+        KernelTimer et;
+        const bool etimed = timed && next_timer(ctx, kProfExpand, &et);
+        LORA_HIP(launch_expand(e, descs[0]->dtype, stream, etimed ? &et : nullptr));
+    }
     if (c.variant == kGemmSkinny) {  // (reads the copy of X the shrink launch left in the first projection's workspace)
         const WorkspaceLayout w = workspace_layout(plan->T, descs[0]->K, descs[0]->N, plan->r_max, descs[0]->dtype);
         a.Xpack = static_cast<unsigned char *>(descs[0]->workspace) + w.xpack_off;
@@ -691,6 +703,13 @@ int lora_ctx_create(lora_ctx **out, int device_ordinal) {
         e = hipHostMalloc(reinterpret_cast<void **>(&ctx->ring), kRingSlots * kRingSlotInts * sizeof(int32_t), hipHostMallocDefault);
     }
     for (int i = 0; i < kRingSlots && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ctx->ring_event[i], hipEventDisableTiming);
+    // per-device set-up of the kernels: dynamic-LDS grants of every instantiation (so that no launch has to make one,
+    // under stream capture or from two threads at once), and this device's address of the static scratch array
+    if (e == hipSuccess) e = init_gemm_tile_kernels();
+    if (e == hipSuccess) e = init_gemm_skinny_kernels();
+    if (e == hipSuccess) e = init_shrink_kernels();
+    if (e == hipSuccess) e = init_expand_kernels();
+    if (e == hipSuccess) e = hipGetSymbolAddress(reinterpret_cast<void **>(&ctx->static_scratch), HIP_SYMBOL(scratch));
     if (e != hipSuccess) {
         for (int i = 0; i < kRingSlots; ++i)
             if (ctx->ring_event[i]) (void)hipEventDestroy(ctx->ring_event[i]);
@@ -720,7 +739,7 @@ int lora_ctx_destroy(lora_ctx *ctx) {
 int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     if (!ctx || !name) return LORA_ERR_INVALID_ARG;
     if (!strcmp(name, "gemm_variant")) {
-        if (value >= kGemmVariantCount) return LORA_ERR_INVALID_ARG;
+        if (value >= kGemmVariantCount || (value >= 6 && value <= 8)) return LORA_ERR_INVALID_ARG;
         ctx->opt_gemm_variant = value;
     } else if (!strcmp(name, "skinny_nb")) {
         ctx->opt_skinny_nb = value;
@@ -812,7 +831,7 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
     int32_t sc[8];
     LORA_HIP(hipMemcpy(sc, plan->scalars, sizeof sc, hipMemcpyDeviceToHost));
     if (n_seg_out) *n_seg_out = sc[kScNSeg];
-    return sc[kScStatus];
+    return sc[kScStatus] != 0 ? sc[kScStatus] : sc[kScEvicted];
 }
 
 size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
@@ -854,6 +873,29 @@ int lora_linear(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
     rc = do_shrink(ctx, plan, desc, s);
     if (rc != LORA_OK) return rc;
     return do_gemm(ctx, plan, desc, s);
+}
+
+int lora_linear_static(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream) {
+    if (!desc) return LORA_ERR_INVALID_ARG;
+    if (desc->workspace != nullptr || desc->workspace_bytes != 0) return LORA_ERR_INVALID_ARG;
+    if (!plan) return LORA_ERR_INVALID_ARG;
+    // (sizes first, so that an oversized problem is reported as such whatever else is wrong with it)
+    if (plan->T >= 0 && desc->K > 0 && desc->N > 0 && plan->r_max >= 0 &&
+        (desc->dtype == LORA_DTYPE_BF16 || desc->dtype == LORA_DTYPE_F32) &&
+        workspace_layout(plan->T, desc->K, desc->N, plan->r_max, desc->dtype).total > (size_t)LORA_STATIC_SCRATCH_BYTES)
+        return LORA_ERR_WORKSPACE_TOO_SMALL;
+    int rc = check_linear(ctx, plan, desc, true, false);
+    if (rc != LORA_OK) return rc;
+    lora_linear_desc d = *desc;
+    d.workspace = ctx->static_scratch;
+    d.workspace_bytes = LORA_STATIC_SCRATCH_BYTES;
+    if (plan->T == 0) return LORA_OK;
+    DeviceGuard guard(ctx->device);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = do_shrink(ctx, plan, &d, s);
+    if (rc != LORA_OK) return rc;
+    return do_gemm(ctx, plan, &d, s);
 }
 
 int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int32_t n,
@@ -955,12 +997,6 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
         case kGemmTile256x256w4:
             snprintf(buf, sizeof buf, "tile_256x256w4");
             break;
-        case kGemmPipe256x256w8:
-            snprintf(buf, sizeof buf, "pipe_256x256_w8");
-            break;
-        case kGemmPipe256x256w4:
-            snprintf(buf, sizeof buf, "pipe_256x256_w4");
-            break;
         case kGemmTile128x192:
             snprintf(buf, sizeof buf, "tile_128x192");
             break;
@@ -969,9 +1005,6 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
             break;
         case kGemmTile256x224:
             snprintf(buf, sizeof buf, "tile_256x224");
-            break;
-        case kGemmPipe128x128w4:
-            snprintf(buf, sizeof buf, "pipe_128x128_w4");
             break;
         default:
             snprintf(buf, sizeof buf, "unknown");

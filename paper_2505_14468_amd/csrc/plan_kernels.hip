@@ -173,6 +173,7 @@ __device__ void fill_units(const PlanBuildArgs &p, int start, int stride) {
 __device__ void write_failed(const PlanBuildArgs &p, int status) {
     p.scalars[kScNSeg] = 0;
     p.scalars[kScStatus] = status;
+    p.scalars[kScEvicted] = 0;
     p.scalars[kScExtTotal] = 0;
     p.scalars[kScNUnits] = 0;
     p.scalars[kScT] = 0;
@@ -292,6 +293,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_segments_kernel(PlanBuildAr
         p.seg_unit[c_seg] = c_unit;
         p.scalars[kScNSeg] = c_seg;
         p.scalars[kScStatus] = 0;
+        p.scalars[kScEvicted] = 0;
         p.scalars[kScExtTotal] = c_ext;
         p.scalars[kScNUnits] = c_unit;
         p.scalars[kScT] = c_row;
@@ -469,6 +471,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         s_sun[c_seg] = c_unit;
         p.scalars[kScNSeg] = c_seg;
         p.scalars[kScStatus] = 0;
+        p.scalars[kScEvicted] = 0;
         p.scalars[kScExtTotal] = c_ext;
         p.scalars[kScNUnits] = c_unit;
         p.scalars[kScT] = c_row;
@@ -764,6 +767,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
             p.seg_unit[c_seg] = c_unit;
             p.scalars[kScNSeg] = c_seg;
             p.scalars[kScStatus] = 0;
+            p.scalars[kScEvicted] = 0;
             p.scalars[kScExtTotal] = c_ext;
             p.scalars[kScNUnits] = c_unit;
             p.scalars[kScT] = p.T;
@@ -1052,6 +1056,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p)
             p.seg_unit[c_seg] = c_unit;
             p.scalars[kScNSeg] = c_seg;
             p.scalars[kScStatus] = 0;
+            p.scalars[kScEvicted] = 0;
             p.scalars[kScExtTotal] = c_ext;
             p.scalars[kScNUnits] = c_unit;
             p.scalars[kScT] = p.T;

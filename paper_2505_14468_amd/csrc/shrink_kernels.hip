@@ -415,7 +415,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
 
     if (Aa == nullptr) {  // slot emptied after the plan was built: flag it, contribute nothing
         E *V = static_cast<E *>(p.V);
-        if (tid == 0) atomicMin(&p.plan.scalars[kScStatus], kErrNotResident);
+        if (tid == 0) atomicMin(&p.plan.scalars[kScEvicted], kErrNotResident);
         for (int e = tid; e < nrows * nj; e += kShWaves * 64) {
             const int t = e / nj, j = e - t * nj;
             V[(int64_t)p.plan.perm[slot0 + t] * p.r_max + j0 + j] = Elem<E>::from_f32(0.f);
@@ -446,21 +446,21 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
 
 }  // namespace
 
+// (more than the default 64 KB of dynamic LDS: granted per kernel and device before the first launch)
+hipError_t init_shrink_kernels() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<__bf16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kShSmemBase + kStageBytes + kXldsBytes);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<float>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kShSmemBase + kStageBytes + kXldsBytes);
+    return e;
+}
+
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
     const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups * (a.n_sets > 0 ? a.n_sets : 1) + a.pack_wgs;
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
     const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;
-    static bool attr_set = false;  // more than the default 64 KB of dynamic LDS
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<__bf16>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kShSmemBase + kStageBytes + kXldsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(shrink_kernel<float>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kShSmemBase + kStageBytes + kXldsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
 #ifdef LORA_TRACE
     return trace_launch("shrink", grid, [&](long long *buf) {
         ShrinkArgs b = a;
