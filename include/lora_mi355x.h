@@ -27,9 +27,10 @@
  *         A_a [r_a, K]   A_a[k,j] of the formula at A_a[j*K + k]
  *         B_a [N, r_a]   B_a[j,n] of the formula at B_a[n*r_a + j]
  *         Y   [T, ldy]
- *   - dtype LORA_DTYPE_BF16: all five tensors bf16, fp32 accumulation; the
- *     intermediate s_a (X A_a) is rounded once to bf16 before the second
- *     product.  dtype LORA_DTYPE_F32: everything fp32.
+ *   - dtype LORA_DTYPE_BF16: all five tensors bf16, fp32 accumulation; above
+ *     128 rows the intermediate s_a (X A_a) is rounded once to bf16 before the
+ *     second product (up to 128 rows it stays fp32).  dtype LORA_DTYPE_F32:
+ *     everything fp32.
  *   - Run-to-run results are bitwise reproducible (no floating-point atomics).
  *   - Thread safety: a ctx may be shared by threads as long as calls that use
  *     the same plan_buf / workspace / Y are ordered by the caller; lora_plan()
@@ -116,6 +117,7 @@ typedef struct lora_plan_t {
     const int32_t *perm;        /* device [T]        slot -> row index of X / Y             */
     const int32_t *row_seg;     /* device [T]        slot -> segment                        */
     const int32_t *row_adapter; /* device [T]        row (original order) -> adapter id     */
+    const int32_t *row_ext;     /* device [T]        row -> (first column of its adapter on the concatenated rank axis / 8) << 7 | rank / 8 */
     const int32_t *seg_adapter; /* device [seg_cap]  adapter id of the segment (-1 = none)  */
     const int32_t *seg_indptr;  /* device [seg_cap+1] first slot of the segment             */
     const int32_t *seg_rank;    /* device [seg_cap]  rank (0 for the no-adapter segment)    */
@@ -156,10 +158,10 @@ int lora_ctx_destroy(lora_ctx *ctx);
 
 /* Overrides of the built-in kernel choices, for tests and measurements:
  * "gemm_variant" (0 tile 128x128, 1 256x128, 2 256x256 on 8 waves, 3 64x64,
- * 4 the decode-sized kernel (bf16, up to 128 rows), 5 256x256 on 4 waves,
- * 9 128x192, 10 256x192, 11 256x224), "skinny_nb" (16-column blocks per
- * workgroup of the decode-sized kernel: 1, 2, 4), "skinny_max_rows" (0: never
- * the decode-sized kernel), "plan_variant" (1: never the one-lane-per-request
+ * 4 the decode path (bf16, up to 128 rows), 5 256x256 on 4 waves,
+ * 9 128x192, 10 256x192, 11 256x224), "decode_waves" (waves per workgroup of
+ * the decode path's streaming kernel: 8..12), "decode_max_rows" (0: never
+ * the decode path), "plan_variant" (1: never the one-lane-per-request
  * plan kernels), "plan_fused_rows" (most rows for which one workgroup builds
  * the whole plan), "expand_split" (0 / 1: adapter term always computed inside
  * the GEMM / by the separate expand kernel whenever the workspace has room
@@ -221,10 +223,12 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 
 /* Device bytes lora_linear needs in desc->workspace for T rows, K inputs, N
  * outputs and V row stride r_max.  It holds the intermediate V = s_a X A_a
- * ([T, r_max]) and, for decode-sized bf16 batches, a copy of X re-ordered into
- * matrix-core operand order.  One workspace may serve calls of different
- * shapes as long as it is big enough for each and the calls do not overlap in
- * time.  Returns 0 for invalid arguments. */
+ * ([T, r_max]) and, for decode-sized bf16 batches (T <= 128), the fp32 partial
+ * sums of the slices the contraction axis is cut into (about
+ * ceil(K / 512) * (N + T * r_max) * 4 bytes per 16 rows of the batch).  One
+ * workspace may serve calls of different shapes as long as it is big enough
+ * for each and the calls do not overlap in time.  Returns 0 for invalid
+ * arguments. */
 size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
 
 /* The workspace size that lets every batch take its fastest path: the size
@@ -238,16 +242,20 @@ size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, in
 
 /* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an
  * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).
- * The same launch prepares whatever else lora_gemm_expand() expects to find in
- * the workspace (the re-ordered copy of X for decode-sized batches), so it is
- * the first half of the layer even when desc->tbl is NULL.
+ * It is the first of the layer's two stages whatever the batch: for
+ * decode-sized bf16 batches (T <= 128) the launch streams W0 and the used A_a
+ * against X once, slice by slice of the contraction axis, and leaves fp32
+ * partial sums of both X W0 and X A_a in the workspace (V is then never
+ * rounded), so call it even when desc->tbl is NULL.
  * Asynchronous on `stream`.  No-op when T == 0. */
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* a3 + a4, base GEMM with the adapter term added before the single rounding and
  * store of Y: Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V (and the copy of
  * X) taken from the workspace as lora_shrink() left them for the same plan,
- * desc->X and K.  Two forms, same result up to fp32 summation order: the expand
+ * desc->X and K (decode-sized bf16 batches: sums the partial sums lora_shrink()
+ * left, adds V B_a in fp32 and stores Y).  Otherwise two forms, same result up
+ * to fp32 summation order: the expand
  * as extra K-steps of the GEMM's own MFMA loop (always, with a workspace of the
  * minimal size; and for segments of 64 rows and more up to rank 64), or -- with
  * a workspace of the preferred size and many small segments -- a
@@ -307,7 +315,7 @@ int lora_profile_begin(lora_ctx *ctx, int max_launches);
 int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_t *counts);
 
 /* Name of the GEMM kernel variant lora_gemm_expand() would launch for this
- * problem ("skinny_tb4_nb1", "tile_128x128", ...), for reports.  Host only. */
+ * problem ("decode_tb4", "tile_128x128", ...), for reports.  Host only. */
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype);
 
 /* ---- errors ------------------------------------------------------------- */

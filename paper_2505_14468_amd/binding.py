@@ -49,7 +49,7 @@ class lora_adapter_table_t(C.Structure):
 class lora_plan_t(C.Structure):
     _fields_ = [("T", C.c_int64), ("n_req", C.c_int32), ("n_adapters", C.c_int32), ("r_max", C.c_int32),
                 ("seg_cap", C.c_int32), ("ext_cap", C.c_int32), ("magic", C.c_int32), ("unit_rows", C.c_int32),
-                ("perm", C.c_void_p), ("row_seg", C.c_void_p), ("row_adapter", C.c_void_p), ("seg_adapter", C.c_void_p),
+                ("perm", C.c_void_p), ("row_seg", C.c_void_p), ("row_adapter", C.c_void_p), ("row_ext", C.c_void_p), ("seg_adapter", C.c_void_p),
                 ("seg_indptr", C.c_void_p), ("seg_rank", C.c_void_p), ("seg_ext", C.c_void_p),
                 ("seg_unit", C.c_void_p), ("unit_rec", C.c_void_p), ("ext_rec", C.c_void_p), ("tok_off", C.c_void_p),
                 ("scalars", C.c_void_p)]

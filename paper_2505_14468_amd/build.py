@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "liblora_mi355x.so")
 
 SOURCES = ["lora_api.hip", "plan_kernels.hip", "shrink_kernels.hip", "expand_kernels.hip", "gemm_tile_kernel.hip",
-           "gemm_skinny_kernel.hip"]
+           "decode_kernels.hip"]
 
 # packed fp32 VALU forms stay off (they are not needed by these kernels)
 HIPCC_FLAGS = [

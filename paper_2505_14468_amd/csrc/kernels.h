@@ -25,6 +25,7 @@ struct PlanBuildArgs {
     int32_t *perm;         // [T]
     int32_t *row_seg;      // [T]
     int32_t *row_adapter;  // [T]  adapter of every row, original order
+    int32_t *row_ext;      // [T]  pack_row_ext(first extension column of the row's adapter, its rank), original order
     int32_t *seg_adapter;  // [seg_cap]
     int32_t *seg_indptr;   // [seg_cap+1]
     int32_t *seg_rank;     // [seg_cap]
@@ -184,7 +185,7 @@ enum GemmVariant {
     kGemmTile256x128 = 1,
     kGemmTile256x256 = 2,
     kGemmTile64x64 = 3,
-    kGemmSkinny = 4,
+    kGemmDecode = 4,         // not a tile shape: the decode-sized path (decode_kernels.hip)
     kGemmTile256x256w4 = 5,  // 256x256 tile on 4 waves (128x128 per wave)
     // (6, 7, 8: not in use)
     kGemmTile128x192 = 9,    // 128 rows x 192 columns on 4 waves (fills the chip where 256x128 leaves CUs idle)
@@ -194,15 +195,39 @@ enum GemmVariant {
 };
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
-hipError_t launch_gemm_skinny(const GemmArgs &a, int tblk, int nb, hipStream_t stream, const KernelTimer *timer);
+
+// Decode-sized batches (bf16, at most kDecodeMaxRows rows): two launches, see decode_kernels.hip.
+struct DecodeArgs {
+    PlanView plan;
+    const void *X;
+    int64_t ldx;
+    const void *W;
+    int64_t ldw;
+    const void *const *A;  // device tables (all three null when the call has no adapters)
+    const void *const *B;
+    const float *scale;
+    void *Y;
+    int64_t ldy;
+    float *P;              // workspace: fp32 partial tiles, [nbe_cap + nbw][ks][tblk][64 lanes][4]
+    int32_t T, K, N;
+    int32_t r_max;         // the plan's largest rank
+    int32_t n_adapters;    // entries of the A / B / scale tables
+    int32_t nbw;           // blocks of 16 rows of W0: ceil(N / 16)
+    int32_t nbe_cap;       // upper bound of the blocks of 16 extension rows (rows of the used A_a), which come first
+    int32_t ks;            // slices of 512 along K
+    int32_t waves;         // waves (= 16-row blocks) per workgroup of the streaming kernel
+    long long *trace = nullptr;  // phase stamps (trace builds only)
+};
+constexpr int kDecodeMaxRows = 128;
+constexpr int kDecodeMinWaves = 8, kDecodeMaxWaves = 12;
+hipError_t init_decode_kernels();
+hipError_t launch_decode_stream(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
+hipError_t launch_decode_reduce(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
 
 // Dynamic-LDS grants of every kernel instantiation, for the current device (context creation).
 hipError_t init_gemm_tile_kernels();
 hipError_t init_shrink_kernels();
 hipError_t init_expand_kernels();
-hipError_t init_gemm_skinny_kernels();
 
-// Geometry of the skinny kernel shared with the host (workspace sizing).
-constexpr int kSkinnyMaxRows = 128;  // rows it accepts
 
 }  // namespace lora

@@ -62,8 +62,8 @@ struct lora_ctx {
     std::mutex ring_mutex;
     // tuning overrides (-1 = heuristic)
     int opt_gemm_variant = -1;
-    int opt_skinny_nb = -1;
-    int opt_skinny_max_rows = -1;
+    int opt_decode_waves = -1;
+    int opt_decode_max_rows = -1;
     int opt_plan_fused_rows = -1;
     int opt_shrink_rank_block = -1;
     int opt_plan_variant = -1;
@@ -121,7 +121,7 @@ void free_profiler(lora_ctx *ctx) {
 
 // ---- plan storage layout ------------------------------------------------------------------------
 struct PlanLayout {
-    size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, row_adapter, seg_adapter, seg_indptr, seg_rank, seg_ext,
+    size_t staged, tok_off, req_dst, hist, cursor, key_seg, perm, row_seg, row_adapter, row_ext, seg_adapter, seg_indptr, seg_rank, seg_ext,
         seg_unit, unit_rec, ext_rec, scalars, total_bytes;
     int32_t seg_cap, ext_cap;
 };
@@ -152,6 +152,7 @@ PlanLayout plan_layout(int32_t n_req, int64_t T, int32_t n_adapters, int32_t r_m
     L.perm = take((size_t)T);
     L.row_seg = take((size_t)T);
     L.row_adapter = take((size_t)T);
+    L.row_ext = take((size_t)T);
     L.seg_adapter = take((size_t)L.seg_cap);
     L.seg_indptr = take((size_t)L.seg_cap + 1);
     L.seg_rank = take((size_t)L.seg_cap);
@@ -240,6 +241,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     a.perm = base + L.perm;
     a.row_seg = base + L.row_seg;
     a.row_adapter = base + L.row_adapter;
+    a.row_ext = base + L.row_ext;
     a.seg_adapter = base + L.seg_adapter;
     a.seg_indptr = base + L.seg_indptr;
     a.seg_rank = base + L.seg_rank;
@@ -268,6 +270,7 @@ int build_plan(lora_ctx *ctx, const int32_t *req_adapter_dev, const int32_t *req
     out->perm = a.perm;
     out->row_seg = a.row_seg;
     out->row_adapter = a.row_adapter;
+    out->row_ext = a.row_ext;
     out->seg_adapter = a.seg_adapter;
     out->seg_indptr = a.seg_indptr;
     out->seg_rank = a.seg_rank;
@@ -289,41 +292,50 @@ int check_plan_buf(const void *plan_buf, size_t plan_buf_bytes, const PlanLayout
 }
 
 // ---- kernel selection ---------------------------------------------------------------------------------
-int skinny_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : T <= 96 ? 6 : 8; }
+int decode_tblk(int64_t T) { return T <= 16 ? 1 : T <= 32 ? 2 : T <= 64 ? 4 : T <= 96 ? 6 : 8; }
 
 struct GemmChoice {
     int variant;
-    int tblk;  // skinny only: 16-row blocks
-    int nb;    // skinny only: 16-column blocks per workgroup
+    int tblk;   // decode path only: 16-row blocks of the batch
+    int waves;  // decode path only: waves (16-row weight blocks) per workgroup of the streaming kernel
 };
 
-// (ns / n_sets: the output widths of the projections one launch covers; the decode-sized kernel takes one)
+// Geometry of the decode path's launches and workspace: blocks of 16 weight rows (extension rows first, by an upper
+// bound of how many ranks the batch can use), slices of 512 along K.
+struct DecodeGeom {
+    int tblk, nbw, nbe_cap, ks;
+    size_t p_bytes;
+};
+DecodeGeom decode_geom(int64_t T, int32_t K, int32_t N, int64_t ext_rows_bound) {
+    DecodeGeom g;
+    g.tblk = decode_tblk(T);
+    g.nbw = (N + 15) / 16;
+    g.nbe_cap = (int)((ext_rows_bound + 15) / 16);
+    g.ks = (K / 8 + 63) / 64;
+    g.p_bytes = (size_t)(g.nbe_cap + g.nbw) * (size_t)g.ks * (size_t)g.tblk * 1024;
+    return g;
+}
+
+// (ns / n_sets: the output widths of the projections one launch covers; the decode path takes one)
 GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int32_t *ns, int n_sets, int32_t dtype) {
     const int32_t N = ns[0];
-    GemmChoice c{kGemmTile128x128, 0, 1};
-    (void)K;
-    const int cus = ctx ? ctx->num_cu : 256;
-    const int max_rows = ctx && ctx->opt_skinny_max_rows >= 0 ? ctx->opt_skinny_max_rows : kSkinnyMaxRows;
+    GemmChoice c{kGemmTile128x128, 0, kDecodeMinWaves};
+    const int max_rows = ctx && ctx->opt_decode_max_rows >= 0 ? ctx->opt_decode_max_rows : kDecodeMaxRows;
     int forced = ctx ? ctx->opt_gemm_variant : -1;
-    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kSkinnyMaxRows && n_sets == 1;
-    if (forced == kGemmSkinny && !fits) forced = -1;
-    const bool skinny = forced == kGemmSkinny || (forced < 0 && fits && T <= max_rows);
-    if (skinny) {
-        c.variant = kGemmSkinny;
-        c.tblk = skinny_tblk(T);
-        // widest column block that still gives every CU a workgroup (fewer re-reads of X)
-        int nb = 8 / c.tblk > 4 ? 4 : 8 / c.tblk;
-        while (nb > 1 && (N + 16 * nb - 1) / (16 * nb) < cus) nb >>= 1;
-        if (ctx && ctx->opt_skinny_nb >= 1 && ctx->opt_skinny_nb * c.tblk <= 8 && ctx->opt_skinny_nb <= 4 &&
-            (ctx->opt_skinny_nb & (ctx->opt_skinny_nb - 1)) == 0)
-            nb = ctx->opt_skinny_nb;
-        c.nb = nb;
+    const bool fits = dtype == LORA_DTYPE_BF16 && T <= kDecodeMaxRows && n_sets == 1;
+    if (forced == kGemmDecode && !fits) forced = -1;
+    const bool decode = forced == kGemmDecode || (forced < 0 && fits && T <= max_rows);
+    if (decode) {
+        c.variant = kGemmDecode;
+        c.tblk = decode_tblk(T);
+        // (waves per workgroup of the streaming kernel: chosen at launch, when the plan's bound of extension rows is known)
         return c;
     }
-    if (forced >= 0 && forced != kGemmSkinny) {
+    if (forced >= 0 && forced != kGemmDecode) {
         c.variant = forced;
         return c;
     }
+    const int cus = ctx ? ctx->num_cu : 256;
     // Time model: rounds of one tile per CU, a tile costing its area over its MFMA efficiency (measured per
     // round at K = 4096: 256x256 104 us, 256x224 100 us, 256x192 88 us, 256x128 64 us, 128x192 51 us, 128x128 34 us, all on 4 waves).
     struct Cand {
@@ -359,29 +371,23 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 }
 
 struct WorkspaceLayout {
-    size_t v_off, xpack_off, xpack_bytes, total;  // total: what every call needs
+    size_t v_off, p_off, p_bytes, total;          // total: what every call needs
     size_t d_off, d_bytes, ldd, total_preferred;  // fp32 adapter term of the separate expand kernel (optional)
 };
 
-// Bytes of the fragment-major copy of X the decode-sized GEMM reads (whole 64-k stages, 16-row blocks).
-size_t xpack_bytes_for(int64_t T, int32_t K) {
-    const size_t stages = ((size_t)K / 8 + 7) / 8;
-    return stages * 2 * (size_t)skinny_tblk(T) * 64 * 16;
-}
-
 WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
     WorkspaceLayout w;
-    (void)N;
     const size_t es = dtype == LORA_DTYPE_BF16 ? 2 : 4;
     w.v_off = 0;
     size_t off = align_up((size_t)T * (size_t)r_max * es, 256);
-    w.xpack_off = off;
-    w.xpack_bytes = (dtype == LORA_DTYPE_BF16 && T > 0 && T <= kSkinnyMaxRows) ? xpack_bytes_for(T, K) : 0;
-    off = align_up(off + w.xpack_bytes, 256);
+    // decode-sized bf16 batches: the partial tiles of the K slices (any batch of T rows uses at most T * r_max ranks)
+    w.p_off = off;
+    w.p_bytes = (dtype == LORA_DTYPE_BF16 && T > 0 && T <= kDecodeMaxRows) ? decode_geom(T, K, N, T * (int64_t)r_max).p_bytes : 0;
+    off = align_up(off + w.p_bytes, 256);
     w.total = off < 256 ? 256 : off;
     w.ldd = align_up((size_t)N, 8);  // (the GEMM's epilogue reads whole 8-column pieces of a row)
     w.d_off = w.total;
-    w.d_bytes = T > kSkinnyMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
+    w.d_bytes = T > kDecodeMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
     w.total_preferred = align_up(w.d_off + w.d_bytes, 256);
     return w;
 }
@@ -432,6 +438,7 @@ PlanView view_of(const lora_plan_t *plan) {
     v.perm = plan->perm;
     v.row_seg = plan->row_seg;
     v.row_adapter = plan->row_adapter;
+    v.row_ext = plan->row_ext;
     v.seg_adapter = plan->seg_adapter;
     v.seg_indptr = plan->seg_indptr;
     v.seg_rank = plan->seg_rank;
@@ -447,14 +454,66 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
 }
 
+// The two launches of the decode path share one argument block.
+DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, const GemmChoice &c) {
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
+    const bool ad = has_adapters(plan, d);
+    // ranks the batch can use at most: one adapter per request, per slot, per row
+    const int64_t segs = std::min<int64_t>(std::min<int64_t>(plan->n_req, plan->n_adapters), plan->T);
+    const DecodeGeom g = decode_geom(plan->T, d->K, d->N, ad ? segs * plan->r_max : 0);
+    DecodeArgs a;
+    a.plan = view_of(plan);
+    a.X = d->X;
+    a.ldx = d->ldx;
+    a.W = d->W0;
+    a.ldw = d->ldw;
+    a.A = ad ? d->tbl->A : nullptr;
+    a.B = ad ? d->tbl->B : nullptr;
+    a.scale = ad ? d->tbl->scale : nullptr;
+    a.Y = d->Y;
+    a.ldy = d->ldy;
+    a.P = reinterpret_cast<float *>(static_cast<unsigned char *>(d->workspace) + w.p_off);
+    a.T = (int32_t)plan->T;
+    a.K = d->K;
+    a.N = d->N;
+    a.r_max = plan->r_max;
+    a.n_adapters = ad ? d->tbl->n_adapters : 0;
+    a.nbw = g.nbw;
+    a.nbe_cap = g.nbe_cap;
+    a.ks = g.ks;
+    // waves per workgroup: whole rounds of one workgroup per CU, as little of the last round idle as possible
+    const int maxw = c.tblk <= 4 ? kDecodeMaxWaves : kDecodeMinWaves;
+    const long nblk = (long)g.nbe_cap + g.nbw;
+    long best = -1;
+    a.waves = kDecodeMinWaves;
+    for (int w = maxw; w >= kDecodeMinWaves; --w) {
+        const long wgs = ((nblk + w - 1) / w) * g.ks;
+        const long cost = ((wgs + ctx->num_cu - 1) / ctx->num_cu) * w;
+        if (best < 0 || cost < best) {
+            best = cost;
+            a.waves = w;
+        }
+    }
+    if (ctx->opt_decode_waves >= kDecodeMinWaves && ctx->opt_decode_waves <= maxw) a.waves = ctx->opt_decode_waves;
+    return a;
+}
+
 // (multi: several projections of the same X that go through one launch)
 int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream,
               const lora_linear_desc *const *multi = nullptr, int n_multi = 0, bool multi_pack = false) {
+    if (n_multi == 0) {
+        const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
+        if (c.variant == kGemmDecode) {  // decode-sized: the first launch streams W0 and the used A_a against X
+            KernelTimer timer;
+            const bool timed = next_timer(ctx, kProfShrink, &timer);
+            LORA_HIP(launch_decode_stream(decode_args(ctx, plan, d, c), c.tblk, stream, timed ? &timer : nullptr));
+            return LORA_OK;
+        }
+    }
     bool ad = has_adapters(plan, d);
     for (int i = 0; i < n_multi; ++i) ad = ad || has_adapters(plan, multi[i]);
-    // (several projections: one copy of the X they share, in the first one's workspace)
-    const bool pack = n_multi == 0 ? choose_gemm(ctx, plan->T, d->K, d->N, d->dtype).variant == kGemmSkinny : multi_pack;
-    if (!ad && !pack) return LORA_OK;
+    (void)multi_pack;
+    if (!ad) return LORA_OK;
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     ShrinkArgs a;
@@ -498,9 +557,9 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.rank_block = rank_block;
     a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
     a.xlds_bytes = ad && plan->T <= 256 ? 64 * 1024 : 0;  // small batches: units of a few rows, one workgroup per CU is plenty
-    a.xpack = pack ? ws + w.xpack_off : nullptr;
-    a.pack_tblk = pack ? skinny_tblk(plan->T) : 0;
-    a.pack_wgs = pack ? (int32_t)((w.xpack_bytes / 16 + 2047) / 2048) : 0;  // 4 chunks per thread
+    a.xpack = nullptr;
+    a.pack_tblk = 0;
+    a.pack_wgs = 0;
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfShrink, &timer);
     LORA_HIP(launch_shrink(a, d->dtype, stream, timed ? &timer : nullptr));
@@ -526,7 +585,7 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
     g.B = ad ? d->tbl->B : nullptr;
     g.N = d->N;
     bool split = false;
-    if (ad && variant != kGemmSkinny && w.d_bytes > 0 && d->workspace_bytes >= w.total_preferred) {
+    if (ad && w.d_bytes > 0 && d->workspace_bytes >= w.total_preferred) {
         const int64_t segs = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;  // upper bound
         split = segs > 0 && plan->T / segs < 64;
         if (ctx->opt_expand_split >= 0) split = ctx->opt_expand_split == 1;
@@ -582,6 +641,10 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
     KernelTimer timer, etimer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
+    if (c.variant == kGemmDecode) {  // decode-sized: the second launch sums the slices, adds V B_a, stores Y
+        LORA_HIP(launch_decode_reduce(decode_args(ctx, plan, d, c), c.tblk, stream, timed ? &timer : nullptr));
+        return LORA_OK;
+    }
     GemmSet g;
     bool split = false;
     const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &etimer : nullptr, &g, &split);
@@ -595,7 +658,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.Y = g.Y;
     a.ldy = g.ldy;
     a.V = g.V;
-    a.Xpack = w.xpack_bytes ? ws + w.xpack_off : nullptr;
+    a.Xpack = nullptr;
     a.B = g.B;
     a.D = g.D;
     a.ldd = g.ldd;
@@ -605,10 +668,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.K = d->K;
     a.N = d->N;
     const KernelTimer *tg = timed ? &timer : nullptr;
-    if (c.variant == kGemmSkinny)
-        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, tg));
-    else
-        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
+    LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, tg));
     return LORA_OK;
 }
 
@@ -622,16 +682,10 @@ int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
         ns[i] = descs[i]->N;
         n_total += descs[i]->N;
     }
-    const GemmChoice one = choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype);
-    if (one.variant == kGemmSkinny) {  // decode-sized: the widest column block that still gives every CU a workgroup
-        int nb = 8 / one.tblk > 4 ? 4 : 8 / one.tblk;
-        while (nb > 1 && (n_total + 16 * nb - 1) / (16 * nb) < ctx->num_cu) nb >>= 1;
-        if (ctx->opt_skinny_nb >= 1) nb = one.nb;
-        *c = GemmChoice{kGemmSkinny, one.tblk, nb};
-        return 2;
-    }
+    // decode-sized batches take the projections one after the other (two short launches each)
+    if (choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype).variant == kGemmDecode) return 0;
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
-    if (c->variant == kGemmSkinny) return 0;
+    if (c->variant == kGemmDecode) return 0;
     return 1;
 }
 
@@ -669,12 +723,6 @@ int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc
         const bool etimed = timed && next_timer(ctx, kProfExpand, &et);
         LORA_HIP(launch_expand(e, descs[0]->dtype, stream, etimed ? &et : nullptr));
     }
-    if (c.variant == kGemmSkinny) {  // (reads the copy of X the shrink launch left in the first projection's workspace)
-        const WorkspaceLayout w = workspace_layout(plan->T, descs[0]->K, descs[0]->N, plan->r_max, descs[0]->dtype);
-        a.Xpack = static_cast<unsigned char *>(descs[0]->workspace) + w.xpack_off;
-        LORA_HIP(launch_gemm_skinny(a, c.tblk, c.nb, stream, timed ? &timer : nullptr));
-        return LORA_OK;
-    }
     LORA_HIP(launch_gemm_tile(a, descs[0]->dtype, c.variant, stream, timed ? &timer : nullptr));
     return LORA_OK;
 }
@@ -706,7 +754,7 @@ int lora_ctx_create(lora_ctx **out, int device_ordinal) {
     // per-device set-up of the kernels: dynamic-LDS grants of every instantiation (so that no launch has to make one,
     // under stream capture or from two threads at once), and this device's address of the static scratch array
     if (e == hipSuccess) e = init_gemm_tile_kernels();
-    if (e == hipSuccess) e = init_gemm_skinny_kernels();
+    if (e == hipSuccess) e = init_decode_kernels();
     if (e == hipSuccess) e = init_shrink_kernels();
     if (e == hipSuccess) e = init_expand_kernels();
     if (e == hipSuccess) e = hipGetSymbolAddress(reinterpret_cast<void **>(&ctx->static_scratch), HIP_SYMBOL(scratch));
@@ -741,10 +789,11 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     if (!strcmp(name, "gemm_variant")) {
         if (value >= kGemmVariantCount || (value >= 6 && value <= 8)) return LORA_ERR_INVALID_ARG;
         ctx->opt_gemm_variant = value;
-    } else if (!strcmp(name, "skinny_nb")) {
-        ctx->opt_skinny_nb = value;
-    } else if (!strcmp(name, "skinny_max_rows")) {
-        ctx->opt_skinny_max_rows = value;
+    } else if (!strcmp(name, "decode_waves")) {
+        if (value >= 0 && (value < kDecodeMinWaves || value > kDecodeMaxWaves)) return LORA_ERR_INVALID_ARG;
+        ctx->opt_decode_waves = value;
+    } else if (!strcmp(name, "decode_max_rows")) {
+        ctx->opt_decode_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
         ctx->opt_plan_fused_rows = value;
     } else if (!strcmp(name, "expand_split")) {
@@ -979,8 +1028,8 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
     static thread_local char buf[64];
     const GemmChoice c = choose_gemm(ctx, T, K, N, dtype);
     switch (c.variant) {
-        case kGemmSkinny:
-            snprintf(buf, sizeof buf, "skinny_tb%d_nb%d", c.tblk, c.nb);
+        case kGemmDecode:
+            snprintf(buf, sizeof buf, "decode_tb%d", c.tblk);
             break;
         case kGemmTile64x64:
             snprintf(buf, sizeof buf, "tile_64x64");

@@ -116,9 +116,11 @@ __device__ void fill_rows(const PlanBuildArgs &p, int start, int stride) {
         const int a = p.req_adapter[i];
         const int key = a < 0 ? p.n_adapters : a;
         const int slot = p.req_dst[i] + (t - p.tok_off[i]);
+        const int sg = p.key_seg[key];
         p.perm[slot] = t;
-        p.row_seg[slot] = p.key_seg[key];
+        p.row_seg[slot] = sg;
         p.row_adapter[t] = a;
+        p.row_ext[t] = pack_row_ext(p.seg_ext[sg], p.seg_rank[sg]);
     }
 }
 
@@ -550,9 +552,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_small_kernel(PlanBuildArgs 
         }
         const int a = s_a[lo];
         const int slot = s_dst[lo] + (t - s_tok[lo]);
+        const int sg = s_kseg[a < 0 ? n_ad : a];
         p.perm[slot] = t;
-        p.row_seg[slot] = s_kseg[a < 0 ? n_ad : a];
+        p.row_seg[slot] = sg;
         p.row_adapter[t] = a;
+        p.row_ext[t] = pack_row_ext(s_sex[sg], s_srk[sg]);
     }
     LORA_TS(p.trace, 6);  // row scatter
     // 6. one record per 8 ranks of the extension axis, one per shrink work unit
@@ -793,6 +797,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_tiny_kernel(PlanBuildArgs p
         p.perm[slot] = t;
         p.row_seg[slot] = s_rseg[lo];
         p.row_adapter[t] = s_a[lo];
+        p.row_ext[t] = pack_row_ext(s_sex[s_rseg[lo]], s_srk[s_rseg[lo]]);
     }
     for (int q = tid; q < (c_ext >> 3); q += kPlanThreads) {
         const int pel = q << 3;
@@ -1082,6 +1087,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_mid_kernel(PlanBuildArgs p)
         p.perm[slot] = t;
         p.row_seg[slot] = s_rseg[lo];
         p.row_adapter[t] = s_a[lo];
+        p.row_ext[t] = pack_row_ext(s_sex[s_rseg[lo]], s_srk[s_rseg[lo]]);
     }
     for (int u = tid; u < (c_ext >> 3); u += kPlanThreads) {
         const int pel = u << 3;

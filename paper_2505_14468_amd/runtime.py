@@ -129,7 +129,7 @@ class Plan:
             return out
         T = self.T
         sc = self._arr("scalars", 8)
-        out.update(perm=self._arr("perm", T), row_seg=self._arr("row_seg", T), row_adapter=self._arr("row_adapter", T),
+        out.update(perm=self._arr("perm", T), row_seg=self._arr("row_seg", T), row_adapter=self._arr("row_adapter", T), row_ext=self._arr("row_ext", T),
                    seg_adapter=self._arr("seg_adapter", n_seg), seg_indptr=self._arr("seg_indptr", n_seg + 1),
                    seg_rank=self._arr("seg_rank", n_seg), seg_ext=self._arr("seg_ext", n_seg + 1),
                    seg_unit=self._arr("seg_unit", n_seg + 1), ext_total=int(sc[2]), n_units=int(sc[3]),

@@ -38,7 +38,7 @@ def test_status_codes_match_header():
 def test_struct_layouts_match_c():
     # sizes as a C compiler lays the header's structs out on x86-64
     assert C.sizeof(B.lora_adapter_table_t) == 32
-    assert C.sizeof(B.lora_plan_t) == 8 + 7 * 4 + 4 + 12 * 8  # (4 bytes of padding before the pointers)
+    assert C.sizeof(B.lora_plan_t) == 8 + 7 * 4 + 4 + 13 * 8  # (4 bytes of padding before the pointers)
     assert C.sizeof(B.lora_linear_desc) == 16 + 6 * 8 + 8 + 8 + 8
 
 
@@ -141,7 +141,7 @@ def test_lora_linear_validates_before_touching_the_gpu():
 
 
 def test_kernel_selection_is_host_side():
-    assert B.lora_gemm_kernel_name(None, 64, 4096, 4096, B.LORA_DTYPE_BF16).startswith("skinny_tb4")
-    assert B.lora_gemm_kernel_name(None, 16, 4096, 4096, B.LORA_DTYPE_BF16).startswith("skinny_tb1")
+    assert B.lora_gemm_kernel_name(None, 64, 4096, 4096, B.LORA_DTYPE_BF16).startswith("decode_tb4")
+    assert B.lora_gemm_kernel_name(None, 16, 4096, 4096, B.LORA_DTYPE_BF16).startswith("decode_tb1")
     assert B.lora_gemm_kernel_name(None, 9000, 4096, 11008, B.LORA_DTYPE_BF16).startswith("tile_")
     assert B.lora_gemm_kernel_name(None, 64, 256, 256, B.LORA_DTYPE_F32).startswith("tile_")

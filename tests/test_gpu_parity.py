@@ -8,7 +8,7 @@ from workloads import make_custom, make_workload, same_adapter_decode, to_f64
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = {"tile_128x128": 0, "tile_256x128": 1, "tile_256x256": 2, "tile_64x64": 3, "skinny": 4, "tile_256x256w4": 5,
+VARIANTS = {"tile_128x128": 0, "tile_256x128": 1, "tile_256x256": 2, "tile_64x64": 3, "decode": 4, "tile_256x256w4": 5,
             "tile_128x192": 9, "tile_256x192": 10, "tile_256x224": 11}
 
 
@@ -211,26 +211,28 @@ def test_linear_multi_projections_of_the_same_activations(dtype):
         X2 = X.clone()
         d_other = rt.linear_desc(pl, X2, up[1][1], Ys[1], up[1][2], ws[1])
         assert B.lora_linear_multi(c.handle, pl.struct, [d[0], d_other], st, raw=True) == B.LORA_ERR_INVALID_ARG
-        d_same_y = rt.linear_desc(pl, X, up[0][1], Ys[0], up[0][2], ws[1])
+        d_same_y = rt.linear_desc(pl, X, up[0][1], Ys[0], up[0][2], torch.empty_like(ws[0]))
         assert B.lora_linear_multi(c.handle, pl.struct, [d[0], d_same_y], st, raw=True) == B.LORA_ERR_INVALID_ARG
         assert B.lora_linear_multi(c.handle, pl.struct, d, st, raw=True) == B.LORA_OK
         torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
-def test_skinny_kernel_row_counts(T):
-    """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128)."""
+def test_decode_path_row_counts(T):
+    """Decode-sized batches of one-token requests (1, ..., 73 = the paper's peak batch, ..., 128): every
+    instantiation of the two decode kernels, ragged N (200 = 12.5 blocks of 16 columns) and K (520 = one whole slice
+    of 512 and a slice of one chunk), workgroups of 8 to 12 waves."""
     from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, B
     rng = np.random.default_rng(T)
     n_ad = 12
     ids = rng.integers(-1, n_ad, size=T)
     wl = make_custom(seed=40 + T, dtype="bf16", K=520, N=200, ranks=rng.choice([8, 16, 32], size=n_ad),
                      scales=rng.choice([0.5, 1.0, 2.0], size=n_ad), req_adapter=ids, req_ntok=np.ones(T, int),
-                     name=f"skinny_T{T}")
-    assert B.lora_gemm_kernel_name(ctx().handle, T, 520, 200, B.LORA_DTYPE_BF16).startswith("skinny")
-    for nb in (1, 2, 4, -1):
-        ctx().set_option("skinny_nb", nb)
-        Y = gpu_linear(wl, device_plan=(nb == 2))
+                     name=f"decode_T{T}")
+    assert B.lora_gemm_kernel_name(ctx().handle, T, 520, 200, B.LORA_DTYPE_BF16).startswith("decode")
+    for nb in (8, 10, 12, -1):
+        ctx().set_option("decode_waves", nb if T <= 64 else -1)  # (more than 64 rows: always 8 waves)
+        Y = gpu_linear(wl, device_plan=(nb == 10))
         e = check_against_oracle(wl, Y)
     print(f"{wl.name}: err/rms {e:.2e}", flush=True)
     reset_options()
@@ -270,13 +272,13 @@ def test_adapter_dominated_output_at_the_default_distributions(K):
     reset_options()
 
 
-def test_skinny_equals_tile_path_within_tolerance_and_tile_handles_small_T():
+def test_decode_path_equals_tile_path_within_tolerance_and_tile_handles_small_T():
     from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options
     ids, L = _mixed_batch(8, R=20, n_ad=5, max_len=6)
     wl = make_custom(seed=77, dtype="bf16", K=1024, N=512, ranks=(16, 8, 32, 16, 64), scales=(1.0, 2.0, 0.5, 1.0, 1.0),
                      req_adapter=ids, req_ntok=L, name="small_T_both_paths")
     assert wl.T <= 128
-    ctx().set_option("skinny_max_rows", 0)  # force the tiled kernel
+    ctx().set_option("decode_max_rows", 0)  # force the tiled kernel
     check_against_oracle(wl, gpu_linear(wl))
     reset_options()
     check_against_oracle(wl, gpu_linear(wl))

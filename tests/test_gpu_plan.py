@@ -55,6 +55,11 @@ def _check_plan(ids, L, ranks, device_plan, fused_rows=-1, plan_variant=-1):
             q += 1
     assert q == rec.shape[0]
     assert np.array_equal(got["tok_off"], np.concatenate([[0], np.cumsum(L)]))
+    # per row (original order): first extension column of its adapter and its rank, packed
+    seg_of_row = np.empty(len(ref["perm"]), np.int64)
+    seg_of_row[ref["perm"]] = ref["row_seg"]
+    want = ((ref["seg_ext"][:-1][seg_of_row] >> 3) << 7) | (ref["seg_rank"][seg_of_row] >> 3)
+    assert np.array_equal(got["row_ext"], want.astype(np.int32))
 
 
 @pytest.mark.parametrize("device_plan", [False, True])
