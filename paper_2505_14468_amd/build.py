@@ -13,7 +13,7 @@ LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "liblora_mi355x.so")
 
 SOURCES = ["lora_api.hip", "plan_kernels.hip", "shrink_kernels.hip", "expand_kernels.hip", "gemm_tile_kernel.hip",
-           "decode_kernels.hip"]
+           "decode_kernels.hip", "sched_batching.cpp", "sched_residency.cpp"]
 
 # packed fp32 VALU forms stay off (they are not needed by these kernels)
 HIPCC_FLAGS = [
@@ -42,10 +42,13 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     os.makedirs(LIB_DIR, exist_ok=True)
     hipcc = _hipcc()
-    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
 
     def compile_one(pair):
         src, obj = pair
+        if src.endswith(".cpp"):  # host-only schedulers: plain C++, products rounded before they are added
+            return _run([hipcc, "-O2", "-std=c++17", "-fPIC", "-Wall", "-ffp-contract=off", *extra_flags, "-c",
+                         os.path.join(CSRC, src), "-o", obj])
         return _run([hipcc, *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj])
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:

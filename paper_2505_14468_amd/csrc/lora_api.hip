@@ -318,7 +318,6 @@ DecodeGeom decode_geom(int64_t T, int32_t K, int32_t N, int64_t ext_rows_bound) 
 
 // (ns / n_sets: the output widths of the projections one launch covers; the decode path takes one)
 GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int32_t *ns, int n_sets, int32_t dtype) {
-    const int32_t N = ns[0];
     GemmChoice c{kGemmTile128x128, 0, kDecodeMinWaves};
     const int max_rows = ctx && ctx->opt_decode_max_rows >= 0 ? ctx->opt_decode_max_rows : kDecodeMaxRows;
     int forced = ctx ? ctx->opt_gemm_variant : -1;
@@ -636,8 +635,6 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
 }
 
 int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream) {
-    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
-    unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
     KernelTimer timer, etimer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
@@ -677,11 +674,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
 // 1: the tiled kernel; 2: the decode-sized kernel.
 int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
     int32_t ns[kMaxGemmSets];
-    int64_t n_total = 0;
-    for (int i = 0; i < n; ++i) {
-        ns[i] = descs[i]->N;
-        n_total += descs[i]->N;
-    }
+    for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
     // decode-sized batches take the projections one after the other (two short launches each)
     if (choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype).variant == kGemmDecode) return 0;
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);

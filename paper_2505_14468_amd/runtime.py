@@ -242,3 +242,93 @@ def upload_workload(wl, p: int, device, only_used: bool = False):
             A.append(tensor_from_bits(wl.A(a, p), device))
             Bw.append(tensor_from_bits(wl.B(a, p), device))
     return X, W0, AdapterTable(A, Bw, wl.scales, device)
+
+
+class AdapterPool:
+    """Adapters of many functions on one GPU with room for only some of them: host copies (pinned) of every
+    adapter, a byte budget on the GPU, and the greedy value-density policy of ``sched`` deciding what is
+    pre-loaded and what is offloaded when a batch needs adapters that are not resident.  Uploads run on a side
+    stream (default priority) and the pointer table is edited in stream order, so the layer's kernels never see a
+    half-loaded adapter.  Decisions are the library's (``lora_preload_greedy`` / ``lora_offload_greedy``); this
+    class only moves bytes and edits ``AdapterTable`` slots."""
+
+    def __init__(self, ctx: Context, host_A: Sequence[np.ndarray], host_B: Sequence[np.ndarray], scales, gpu_bytes: float,
+                 rates: Sequence[float], load_ms: Optional[Sequence[float]] = None):
+        from . import sched
+        self._sched = sched
+        self.ctx, self.device = ctx, ctx.device
+        self.n = len(host_A)
+
+        def pin(a):
+            t = tensor_from_bits(a, "cpu")
+            p = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+            p.copy_(t)
+            return p
+        self.host_A = [pin(a) for a in host_A]
+        self.host_B = [pin(b) for b in host_B]
+        self.bytes = [float(a.numel() * a.element_size() + b.numel() * b.element_size()) for a, b in zip(self.host_A, self.host_B)]
+        self.rates = [float(r) for r in rates]
+        # loading delay of an adapter: its bytes over the host link, plus a fixed cost (overridable per adapter)
+        self.load_ms = [float(x) for x in load_ms] if load_ms is not None else [b / 25.0e6 + 0.05 for b in self.bytes]
+        self.gpu_bytes = float(gpu_bytes)
+        self.table = AdapterTable([None] * self.n, [None] * self.n, scales, self.device)
+        self.resident = [False] * self.n
+        self.side = torch.cuda.Stream(device=self.device)
+        self.log: List[tuple] = []
+
+    def _artifacts(self, pinned=()):
+        pinned = set(int(a) for a in pinned)
+        return [dict(function=a, kind=2, share_id=0, pinned=int(a in pinned), bytes=self.bytes[a],
+                     value=self.load_ms[a] * self.rates[a]) for a in range(self.n)]
+
+    def used_bytes(self) -> float:
+        return sum(b for b, r in zip(self.bytes, self.resident) if r)
+
+    def _upload(self, adapters):
+        if not adapters:
+            return
+        main = torch.cuda.current_stream(self.device)
+        fresh = []
+        for a in adapters:  # allocate in the main stream's order, copy on the side stream
+            A = torch.empty(self.host_A[a].shape, dtype=self.host_A[a].dtype, device=self.device)
+            Bw = torch.empty(self.host_B[a].shape, dtype=self.host_B[a].dtype, device=self.device)
+            fresh.append((a, A, Bw))
+        self.side.wait_stream(main)
+        with torch.cuda.stream(self.side):
+            for a, A, Bw in fresh:
+                A.copy_(self.host_A[a], non_blocking=True)
+                Bw.copy_(self.host_B[a], non_blocking=True)
+                A.record_stream(self.side)
+                Bw.record_stream(self.side)
+        main.wait_stream(self.side)
+        for a, A, Bw in fresh:
+            self.table.set_slot(a, A, Bw)
+            self.resident[a] = True
+            self.log.append(("load", a))
+
+    def _evict(self, adapters):
+        for a in adapters:
+            self.table.set_slot(a, None, None)  # stream-ordered edit; the tensors are released in stream order too
+            self.resident[a] = False
+            self.log.append(("evict", a))
+
+    def preload(self):
+        """Section 4.1: fill the GPU budget in order of value density."""
+        place, _ = self._sched.lora_preload_greedy(self._artifacts(), 0.0, self.gpu_bytes)
+        self._upload([a for a in range(self.n) if (place[a] & 2) and not self.resident[a]])
+
+    def ensure(self, needed: Sequence[int]) -> dict:
+        """Make every adapter of ``needed`` resident before the next batch (section 4.3): offload the least valuable
+        adapters that the batch does not use until the missing ones fit, then upload those."""
+        needed = sorted(set(int(a) for a in needed if a >= 0))
+        missing = [a for a in needed if not self.resident[a]]
+        need = self.used_bytes() + sum(self.bytes[a] for a in missing) - self.gpu_bytes
+        evicted = []
+        if need > 0:
+            ev, _, _, enough = self._sched.lora_offload_greedy(self._artifacts(pinned=needed), [int(r) for r in self.resident], need)
+            if not enough:
+                raise RuntimeError("the batch's adapters do not fit the GPU budget")
+            evicted = [a for a in range(self.n) if ev[a]]
+            self._evict(evicted)
+        self._upload(missing)
+        return dict(uploaded=missing, evicted=evicted)
