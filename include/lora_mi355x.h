@@ -318,6 +318,25 @@ int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_
  * problem ("decode_tb4", "tile_128x128", ...), for reports.  Host only. */
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype);
 
+/* ---- the shared backbone across processes (section 4.4, section 5) -------- */
+
+/* The backbone's tensors live in ONE process (the "backbone function") and every LoRA function
+ * process maps them read-only, zero-copy, through an inter-process memory handle; W0 of
+ * lora_linear_desc is such a mapped pointer.  These four calls are that plumbing (the paper's
+ * IPC-handle plugin): the holder allocates a region of its own (a whole device allocation, which
+ * is what a handle names; keep each below 2 GiB), fills it, exports the handle as
+ * LORA_IPC_HANDLE_BYTES opaque bytes that it passes to the other processes by any means; they
+ * open it, use the returned DEVICE pointer as W0 for as long as they like, and close it.  The
+ * mapping costs no copy and no device memory beyond the driver's bookkeeping.  The library never
+ * writes through W0.  All four: device `device_ordinal` of the calling process; errors
+ * INVALID_ARG, HIP. */
+#define LORA_IPC_HANDLE_BYTES 64
+int lora_backbone_alloc(int device_ordinal, size_t bytes, void **dev_ptr_out);
+int lora_backbone_free(int device_ordinal, void *dev_ptr);
+int lora_backbone_export(int device_ordinal, const void *dev_ptr, unsigned char handle_out[LORA_IPC_HANDLE_BYTES]);
+int lora_backbone_open(int device_ordinal, const unsigned char handle[LORA_IPC_HANDLE_BYTES], void **dev_ptr_out);
+int lora_backbone_close(int device_ordinal, void *dev_ptr);
+
 /* ---- errors ------------------------------------------------------------- */
 const char *lora_strerror(int status);
 /* The hipError_t (as int) of the last failing HIP call on this thread, 0 if none. */

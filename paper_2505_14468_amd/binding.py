@@ -38,6 +38,7 @@ EXPORTS = [
     "lora_linear_multi", "lora_linear_static",
     "lora_profile_begin", "lora_profile_end",
     "lora_gemm_kernel_name", "lora_strerror", "lora_last_hip_error",
+    "lora_backbone_alloc", "lora_backbone_free", "lora_backbone_export", "lora_backbone_open", "lora_backbone_close",
 ]
 
 
@@ -106,6 +107,11 @@ def lib():
         L.lora_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_double), i32p]
         L.lora_gemm_kernel_name.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
         L.lora_gemm_kernel_name.restype = C.c_char_p
+        L.lora_backbone_alloc.argtypes = [C.c_int, C.c_size_t, C.POINTER(C.c_void_p)]
+        L.lora_backbone_free.argtypes = [C.c_int, C.c_void_p]
+        L.lora_backbone_export.argtypes = [C.c_int, C.c_void_p, C.c_char_p]
+        L.lora_backbone_open.argtypes = [C.c_int, C.c_char_p, C.POINTER(C.c_void_p)]
+        L.lora_backbone_close.argtypes = [C.c_int, C.c_void_p]
         L.lora_strerror.argtypes = [C.c_int]
         L.lora_strerror.restype = C.c_char_p
         L.lora_last_hip_error.restype = C.c_int
@@ -274,6 +280,37 @@ def lora_profile_end(ctx, stream: int) -> dict:
     cnt = (C.c_int32 * len(PROFILE_KINDS))()
     _check(lib().lora_profile_end(C.c_void_p(ctx), C.c_void_p(stream), avg, cnt), "lora_profile_end")
     return {k: (float(avg[i]), int(cnt[i])) for i, k in enumerate(PROFILE_KINDS)}
+
+
+LORA_IPC_HANDLE_BYTES = 64
+
+
+def lora_backbone_alloc(device_ordinal: int, nbytes: int) -> int:
+    p = C.c_void_p()
+    _check(lib().lora_backbone_alloc(int(device_ordinal), int(nbytes), C.byref(p)), "lora_backbone_alloc")
+    return int(p.value)
+
+
+def lora_backbone_free(device_ordinal: int, ptr: int) -> None:
+    _check(lib().lora_backbone_free(int(device_ordinal), C.c_void_p(ptr)), "lora_backbone_free")
+
+
+def lora_backbone_export(device_ordinal: int, ptr: int) -> bytes:
+    buf = C.create_string_buffer(LORA_IPC_HANDLE_BYTES)
+    _check(lib().lora_backbone_export(int(device_ordinal), C.c_void_p(ptr), buf), "lora_backbone_export")
+    return buf.raw
+
+
+def lora_backbone_open(device_ordinal: int, handle: bytes) -> int:
+    assert len(handle) == LORA_IPC_HANDLE_BYTES
+    p = C.c_void_p()
+    _check(lib().lora_backbone_open(int(device_ordinal), C.create_string_buffer(handle, LORA_IPC_HANDLE_BYTES), C.byref(p)),
+           "lora_backbone_open")
+    return int(p.value)
+
+
+def lora_backbone_close(device_ordinal: int, ptr: int) -> None:
+    _check(lib().lora_backbone_close(int(device_ordinal), C.c_void_p(ptr)), "lora_backbone_close")
 
 
 def lora_gemm_kernel_name(ctx, T: int, K: int, N: int, dtype: int) -> str:

@@ -1017,6 +1017,54 @@ int lora_profile_end(lora_ctx *ctx, lora_stream_t stream, double *avg_us, int32_
     return LORA_OK;
 }
 
+static_assert(sizeof(hipIpcMemHandle_t) == LORA_IPC_HANDLE_BYTES, "IPC handle size out of sync");
+
+int lora_backbone_alloc(int device_ordinal, size_t bytes, void **dev_ptr_out) {
+    if (!dev_ptr_out || bytes == 0 || device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    *dev_ptr_out = nullptr;
+    DeviceGuard guard(device_ordinal);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    LORA_HIP(hipMalloc(dev_ptr_out, bytes));
+    return LORA_OK;
+}
+
+int lora_backbone_free(int device_ordinal, void *dev_ptr) {
+    if (!dev_ptr || device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(device_ordinal);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    LORA_HIP(hipFree(dev_ptr));
+    return LORA_OK;
+}
+
+int lora_backbone_export(int device_ordinal, const void *dev_ptr, unsigned char handle_out[LORA_IPC_HANDLE_BYTES]) {
+    if (!dev_ptr || !handle_out || device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(device_ordinal);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipIpcMemHandle_t h;
+    LORA_HIP(hipIpcGetMemHandle(&h, const_cast<void *>(dev_ptr)));
+    memcpy(handle_out, &h, sizeof h);
+    return LORA_OK;
+}
+
+int lora_backbone_open(int device_ordinal, const unsigned char handle[LORA_IPC_HANDLE_BYTES], void **dev_ptr_out) {
+    if (!handle || !dev_ptr_out || device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    *dev_ptr_out = nullptr;
+    DeviceGuard guard(device_ordinal);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    hipIpcMemHandle_t h;
+    memcpy(&h, handle, sizeof h);
+    LORA_HIP(hipIpcOpenMemHandle(dev_ptr_out, h, hipIpcMemLazyEnablePeerAccess));
+    return LORA_OK;
+}
+
+int lora_backbone_close(int device_ordinal, void *dev_ptr) {
+    if (!dev_ptr || device_ordinal < 0) return LORA_ERR_INVALID_ARG;
+    DeviceGuard guard(device_ordinal);
+    if (guard.err != hipSuccess) return hip_fail(guard.err);
+    LORA_HIP(hipIpcCloseMemHandle(dev_ptr));
+    return LORA_OK;
+}
+
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
     static thread_local char buf[64];
     const GemmChoice c = choose_gemm(ctx, T, K, N, dtype);
