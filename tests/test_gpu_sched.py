@@ -68,7 +68,7 @@ def test_adapter_pool_keeps_the_batches_adapters_resident_within_its_budget():
     scales = tuple(float(s) for s in rng.choice([0.5, 1.0, 2.0], size=n_ad))
     base = make_custom(seed=6100, dtype="bf16", K=K, N=N, ranks=ranks, scales=scales, req_adapter=[0], req_ntok=[1])
     sizes = [2.0 * r * (K + N) for r in ranks]
-    budget = sum(sorted(sizes)[-5:])  # room for the five largest, not for all twelve
+    budget = sum(sorted(sizes)[-6:])  # room for the six largest (any batch below fits), not for all twelve
     rates = [float(x) for x in rng.integers(1, 20, size=n_ad)]
     pool = rt.AdapterPool(c, [base.A(a) for a in range(n_ad)], [base.B(a) for a in range(n_ad)], scales, budget, rates)
     pool.preload()
@@ -79,7 +79,7 @@ def test_adapter_pool_keeps_the_batches_adapters_resident_within_its_budget():
     X = rt.tensor_from_bits(base.X(0)[:0], c.device)  # (dtype only)
     W0 = rt.tensor_from_bits(base.W0(0), c.device)
     for step in range(8):
-        R = int(rng.integers(3, 9))
+        R = int(rng.integers(3, 8))  # at most six distinct adapters per batch
         ids = rng.choice(n_ad, size=R, replace=True)
         ids[0] = -1
         L = rng.integers(1, 6 if step % 2 else 60, size=R)
