@@ -146,21 +146,22 @@ def run_projection(ctx, mods, wl, cfg_index, p, steps, warmup, cpu_seconds, opti
     sec_per_step = _timed(torch, step, steps)
     # ---- the same steps again with every kernel bracketed by its own HIP event pair (the events cost host time
     #      per launch, so this pass is not the one `value` comes from) -----------------------------------------
-    B.lora_profile_begin(h, steps)
+    B.lora_profile_begin(h, 2 * steps)
     sec_profiled = _timed(torch, step, steps)
     prof = B.lora_profile_end(h, stream)
     # ---- side measurements (not part of `value`) ------------------------------------------------------------
     k2 = max(10, steps // 4)
     sec_layer = _timed(torch, lambda i: B.lora_linear(h, plan0.struct, descs[i % n_sets], stream), k2)
-    B.lora_profile_begin(h, k2)
+    B.lora_profile_begin(h, 2 * k2)
     _timed(torch, lambda i: B.lora_linear(h, plan0.struct, descs_base[i % n_sets], stream), k2)
     prof_base = B.lora_profile_end(h, stream)
-    base_us = prof_base["shrink"][0] + prof_base["gemm_expand"][0]  # (decode-sized batches: both kernels carry the base product)
+    base_us = (prof_base["shrink"][0] * prof_base["shrink"][1] + prof_base["gemm_expand"][0] * prof_base["gemm_expand"][1]) / k2  # (decode-sized batches: both kernels carry the base product)
     sec_hot = _timed(torch, lambda i: B.lora_linear(h, plan0.struct, descs[0], stream), k2)  # one weight set: cache-resident
 
     flops = wl.useful_flops(p)
-    k1_us, k2_us, ex_us = prof["shrink"][0], prof["gemm_expand"][0], prof["expand"][0]
-    plan_us = prof["plan_segments"][0] + prof["plan_fill"][0]
+    per_step = lambda pr_, kind, n: pr_[kind][0] * pr_[kind][1] / n  # (a kind may be more than one launch per step)
+    k1_us, k2_us, ex_us = per_step(prof, "shrink", steps), per_step(prof, "gemm_expand", steps), per_step(prof, "expand", steps)
+    plan_us = per_step(prof, "plan_segments", steps) + per_step(prof, "plan_fill", steps)
     ra_rows = wl.row_adapter()
     rows_by_ad = dict(zip(*np.unique(ra_rows[ra_rows >= 0], return_counts=True)))
     v_elems = int(sum(int(wl.ranks[a]) * int(n) for a, n in rows_by_ad.items()))  # sum over rows of their rank
