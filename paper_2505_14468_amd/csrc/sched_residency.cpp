@@ -131,20 +131,41 @@ int lora_preload_greedy(const lora_artifact *artifacts, int32_t n, double contai
     });
     std::vector<uint8_t> placed(m.objects.size(), 0);
     double used_container = 0.0, used_gpu = 0.0, value = 0.0;
-    for (bool progress = true; progress;) {
-        progress = false;
-        for (const Cand &c : cands) {
-            const Object &o = m.objects[(size_t)c.obj];
-            if (placed[(size_t)c.obj] & c.bit) continue;
-            double &used = c.bit == kContainerBit ? used_container : used_gpu;
-            const double cap = c.bit == kContainerBit ? container_bytes : gpu_bytes;
-            if (used + o.bytes > cap || !precedence_ok(m, placed, c.obj, c.bit)) continue;
-            placed[(size_t)c.obj] |= (uint8_t)c.bit;
-            used += o.bytes;
-            value += o.value;
-            progress = true;
-            break;  // a placement may unlock denser candidates: scan again from the top
+    // "Place the first candidate in density order that fits, then scan again from the top" -- without the rescans: a
+    // candidate that failed on capacity fails for good (capacity only shrinks), so after a placement only the
+    // candidates passed over for PRECEDENCE can have become placeable; they are kept in order in `waiting`.
+    auto try_place = [&](const Cand &c) -> int {  // 1 placed, 0 no room / already there, -1 precedence not met yet
+        const Object &o = m.objects[(size_t)c.obj];
+        if (placed[(size_t)c.obj] & c.bit) return 0;
+        double &used = c.bit == kContainerBit ? used_container : used_gpu;
+        const double cap = c.bit == kContainerBit ? container_bytes : gpu_bytes;
+        if (used + o.bytes > cap) return 0;
+        if (!precedence_ok(m, placed, c.obj, c.bit)) return -1;
+        placed[(size_t)c.obj] |= (uint8_t)c.bit;
+        used += o.bytes;
+        value += o.value;
+        return 1;
+    };
+    std::vector<size_t> waiting;  // indices into cands, increasing
+    auto drain_waiting = [&]() {  // place waiting candidates, densest first, until none of them can go
+        for (bool again = true; again;) {
+            again = false;
+            for (size_t w = 0; w < waiting.size(); ++w) {
+                const int r = try_place(cands[waiting[w]]);
+                if (r == -1) continue;
+                waiting.erase(waiting.begin() + (long)w);  // placed, or out of room for good
+                if (r == 1) {
+                    again = true;
+                    break;
+                }
+                --w;
+            }
         }
+    };
+    for (size_t i = 0; i < cands.size(); ++i) {
+        const int r = try_place(cands[i]);
+        if (r == -1) waiting.push_back(i);
+        if (r == 1) drain_waiting();
     }
     for (int32_t i = 0; i < n; ++i) place_out[i] = placed[(size_t)m.object_of[(size_t)i]];
     if (value_out) *value_out = value;

@@ -158,7 +158,10 @@ class Batcher:
         return math.inf if out.value == math.inf else float(out.value)
 
 
-def _artifacts(arts: Sequence[dict]):
+def artifacts_array(arts):
+    """A ctypes array of lora_artifact from a sequence of dicts (or such an array, passed through)."""
+    if isinstance(arts, C.Array):
+        return arts
     arr = (lora_artifact * max(len(arts), 1))()
     for i, a in enumerate(arts):
         arr[i] = lora_artifact(int(a["function"]), int(a["kind"]), int(a.get("share_id", 0)), int(a.get("pinned", 0)),
@@ -170,7 +173,7 @@ def lora_preload_greedy(arts: Sequence[dict], container_bytes: float, gpu_bytes:
     """Returns (mask per artifact: bit 0 container, bit 1 GPU; objective value)."""
     place = np.zeros(max(len(arts), 1), np.uint8)
     value = C.c_double()
-    st = lib().lora_preload_greedy(_artifacts(arts), len(arts), float(container_bytes), float(gpu_bytes),
+    st = lib().lora_preload_greedy(artifacts_array(arts), len(arts), float(container_bytes), float(gpu_bytes),
                                    place.ctypes.data_as(C.c_void_p), C.byref(value))
     if raw:
         return st
@@ -185,7 +188,7 @@ def lora_offload_greedy(arts: Sequence[dict], on_gpu: Sequence[int], need_bytes:
         flags = np.zeros(1, np.uint8)
     evict = np.zeros(max(len(arts), 1), np.uint8)
     freed, lost = C.c_double(), C.c_double()
-    st = lib().lora_offload_greedy(_artifacts(arts), len(arts), flags.ctypes.data_as(C.c_void_p), float(need_bytes),
+    st = lib().lora_offload_greedy(artifacts_array(arts), len(arts), flags.ctypes.data_as(C.c_void_p), float(need_bytes),
                                    evict.ctypes.data_as(C.c_void_p), C.byref(freed), C.byref(lost))
     if st not in (LORA_SCHED_OK, LORA_SCHED_ERR_CAPACITY):
         raise SchedError(st, "lora_offload_greedy")
