@@ -98,13 +98,7 @@ struct ShrinkArgs {
     int32_t rank_groups;   // ceil(r_max / rank_block)
     int32_t max_units;     // upper bound of work units (shrink grid = max_units * rank_groups)
     int32_t xlds_bytes;    // LDS for staging the X rows of small units: 0 or 64 KiB (decode-sized batches)
-    // Fragment-major copy of X for the decode-sized GEMM (null = not needed): for MFMA step s
-    // (32 k) and 16-row block tb, the 64 lanes' 16-byte operands are stored contiguously at
-    // xpack[(s * pack_tblk + tb) * 64 + lane], lane = 16 * kgroup + row, zero past T and K.
-    void *xpack;
-    int32_t pack_tblk;
     long long *trace = nullptr;  // phase stamps (trace builds only)
-    int32_t pack_wgs;      // extra workgroups in front of the shrink units that write the copy
     int32_t n_sets = 0;    // > 0: the projections of the launch (A, scale, V, n_adapters above are then unused)
     ShrinkSet set[kMaxGemmSets];
 };
@@ -136,7 +130,6 @@ struct GemmArgs {
     void *Y;
     int64_t ldy;
     const void *V;         // [T, r_max] of E, original row order (null when no adapters)
-    const void *Xpack;     // fragment-major copy of X (decode-sized kernel only)
     const void *const *B;  // device table (null when no adapters, or when all of the adapter term comes in D)
     const float *D;        // adapter term in fp32, [T, ldd], original row order, rows with an adapter only (null = none)
     int64_t ldd;

@@ -499,7 +499,7 @@ DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_
 
 // (multi: several projections of the same X that go through one launch)
 int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream,
-              const lora_linear_desc *const *multi = nullptr, int n_multi = 0, bool multi_pack = false) {
+              const lora_linear_desc *const *multi = nullptr, int n_multi = 0) {
     if (n_multi == 0) {
         const GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
         if (c.variant == kGemmDecode) {  // decode-sized: the first launch streams W0 and the used A_a against X
@@ -511,7 +511,6 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     }
     bool ad = has_adapters(plan, d);
     for (int i = 0; i < n_multi; ++i) ad = ad || has_adapters(plan, multi[i]);
-    (void)multi_pack;
     if (!ad) return LORA_OK;
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
@@ -556,9 +555,6 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
     a.rank_block = rank_block;
     a.rank_groups = ad ? (plan->r_max + rank_block - 1) / rank_block : 1;
     a.xlds_bytes = ad && plan->T <= 256 ? 64 * 1024 : 0;  // small batches: units of a few rows, one workgroup per CU is plenty
-    a.xpack = nullptr;
-    a.pack_tblk = 0;
-    a.pack_wgs = 0;
     KernelTimer timer;
     const bool timed = next_timer(ctx, kProfShrink, &timer);
     LORA_HIP(launch_shrink(a, d->dtype, stream, timed ? &timer : nullptr));
@@ -655,7 +651,6 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     a.Y = g.Y;
     a.ldy = g.ldy;
     a.V = g.V;
-    a.Xpack = nullptr;
     a.B = g.B;
     a.D = g.D;
     a.ldd = g.ldd;
@@ -671,7 +666,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
 
 // Several projections of the same X in one GEMM launch (their column tiles side by side in one grid: one ramp, one
 // set of whole rounds of tiles for all of them).  0: this batch / these options take the projections one by one;
-// 1: the tiled kernel; 2: the decode-sized kernel.
+// 1: the tiled kernel (one launch of each kernel for all of them).
 int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
     int32_t ns[kMaxGemmSets];
     for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
@@ -693,7 +688,6 @@ int do_gemm_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc
     a.Y = nullptr;
     a.ldy = 0;
     a.V = nullptr;
-    a.Xpack = nullptr;
     a.B = nullptr;
     a.D = nullptr;
     a.ldd = 0;
@@ -968,7 +962,7 @@ int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_
         }
         return LORA_OK;
     }
-    const int rc = do_shrink(ctx, plan, descs[0], s, descs, n, kind == 2);  // one launch: the single projection's grid once per projection
+    const int rc = do_shrink(ctx, plan, descs[0], s, descs, n);  // one launch: the single projection's grid once per projection
     if (rc != LORA_OK) return rc;
     return do_gemm_multi(ctx, plan, descs, n, c, s);
 }

@@ -306,37 +306,15 @@ __device__ __forceinline__ void shrink_unit(const ShrinkArgs &p, const E *Aa, fl
     }
 }
 
-// Fragment-major copy of X for the decode-sized GEMM: output-ordered, so the writes are contiguous.
-template <typename E>
-__device__ __forceinline__ void pack_x(const ShrinkArgs &p, int wg) {
-    constexpr int CE = Elem<E>::CE;
-    const int kchunks = p.K / CE;
-    const int steps = ((kchunks + 7) >> 3) * 2;  // whole 64-k stages
-    const int64_t total = (int64_t)steps * p.pack_tblk * 64;
-    chunk_t *dst = static_cast<chunk_t *>(p.xpack);
-    for (int64_t idx = (int64_t)wg * (kShWaves * 64) + threadIdx.x; idx < total; idx += (int64_t)p.pack_wgs * (kShWaves * 64)) {
-        const int lane = (int)(idx & 63);
-        const int64_t blk = idx >> 6;
-        const int tb = (int)(blk % p.pack_tblk), s = (int)(blk / p.pack_tblk);
-        const int t = tb * 16 + (lane & 15), kc = s * 4 + (lane >> 4);
-        dst[idx] = (t < p.T && kc < kchunks) ? load_chunk(static_cast<const E *>(p.X) + (int64_t)t * p.ldx + kc * CE) : zero_chunk();
-    }
-}
-
 template <typename E>
 __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x;
     LORA_TS(p0.trace, 0);
 
-    if ((int)blockIdx.x < p0.pack_wgs) {
-        if (p0.plan.scalars[kScStatus] != 0) return;
-        pack_x<E>(p0, blockIdx.x);
-        return;
-    }
     // several projections of the same X: the single-projection grid once per projection
     ShrinkArgs p = p0;
-    int bid = blockIdx.x - p.pack_wgs;
+    int bid = blockIdx.x;
     if (p0.n_sets > 0) {
         const int per = (p.max_units + 7) / 8 * 8 * p.rank_groups;
         const int si = bid / per;
@@ -457,7 +435,7 @@ hipError_t init_shrink_kernels() {
 }
 
 hipError_t launch_shrink(const ShrinkArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
-    const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups * (a.n_sets > 0 ? a.n_sets : 1) + a.pack_wgs;
+    const long grid = (long)((a.max_units + 7) / 8 * 8) * a.rank_groups * (a.n_sets > 0 ? a.n_sets : 1);
     if (grid <= 0) return hipSuccess;
     if (a.xlds_bytes != 0 && a.xlds_bytes != kXldsBytes) return hipErrorInvalidValue;
     const size_t smem = (size_t)kShSmemBase + kStageBytes + (size_t)a.xlds_bytes;
