@@ -338,6 +338,66 @@ def run_layer(ctx, mods, wl, steps, warmup, fuse, n_layers=1):
                     (")" if n_layers > 1 else "")}
 
 
+def run_fused_copies(ctx, mods, wl, n_proj, steps, warmup):
+    """n_proj projections of projection 0's shape on the same activations (own weights and adapters each: q/k/v of a
+    model with as many KV heads as query heads), one plan per step: one lora_linear each against one lora_linear_multi."""
+    np, torch, B, rt = mods
+    dev, T, r_max = ctx.device, wl.T, wl.r_max
+    tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    req_adapter = torch.from_numpy(np.ascontiguousarray(wl.req_adapter)).to(dev)
+    req_ntok = torch.from_numpy(np.ascontiguousarray(wl.req_ntok)).to(dev)
+    ranks = torch.from_numpy(np.ascontiguousarray(wl.ranks)).to(dev)
+    plan_bytes = B.lora_plan_bytes(wl.n_req, T, wl.n_adapters, r_max)
+    plan_buf = torch.empty(plan_bytes, dtype=torch.uint8, device=dev)
+    plan0 = rt.plan_device(ctx, req_adapter, req_ntok, ranks, r_max, T, buf=plan_buf)
+    pr = wl.projections[0]
+    X, W0, table = _upload(rt, wl, 0, dev)
+    wl.drop_cache()
+    keep, descs, outs = [], [], []
+    for q in range(n_proj):
+        copies = {}
+
+        def own(t):
+            if t is None:
+                return None
+            if id(t) not in copies:
+                copies[id(t)] = t.clone()
+            return copies[id(t)]
+        tq = table if q == 0 else rt.AdapterTable([own(t) for t in table.A], [own(t) for t in table.B],
+                                                  table.scales.cpu().numpy(), dev)
+        Wq = W0 if q == 0 else W0.clone()
+        ws = rt.workspace(T, pr.K, pr.N, r_max, tdtype, dev)
+        for fused in (0, 1):
+            Y = torch.zeros((T, pr.N), dtype=tdtype, device=dev)
+            outs.append((q, fused, Y))
+            descs.append(rt.linear_desc(plan0, X, Wq, Y, tq, ws))
+        keep.append((Wq, tq, ws))
+    seq = [d for d, (q, f, _) in zip(descs, outs) if f == 0]
+    fus = [d for d, (q, f, _) in zip(descs, outs) if f == 1]
+    h, stream = ctx.handle, int(torch.cuda.current_stream().cuda_stream)
+    ra_p, rn_p, rk_p, pb_p = req_adapter.data_ptr(), req_ntok.data_ptr(), ranks.data_ptr(), plan_buf.data_ptr()
+
+    def step_seq(_):
+        plan = B.lora_plan_device(h, ra_p, rn_p, wl.n_req, rk_p, wl.n_adapters, r_max, T, pb_p, plan_bytes, stream)
+        for d in seq:
+            B.lora_linear(h, plan, d, stream)
+
+    def step_fused(_):
+        plan = B.lora_plan_device(h, ra_p, rn_p, wl.n_req, rk_p, wl.n_adapters, r_max, T, pb_p, plan_bytes, stream)
+        B.lora_linear_multi(h, plan, fus, stream)
+
+    res = {}
+    for name, fn in (("one_call_each", step_seq), ("lora_linear_multi", step_fused)):
+        for i in range(warmup):
+            fn(i)
+        res[name + "_ms_per_step"] = round(_timed(torch, fn, steps) * 1e3, 5)
+    ys = {(q, f): Y for q, f, Y in outs}
+    res["outputs_equal"] = bool(all(torch.equal(ys[(q, 0)], ys[(q, 1)]) for q in range(n_proj)))
+    res["projections"] = n_proj
+    res["steps"], res["warmup"] = steps, warmup
+    return res
+
+
 def run_schedulers(np):
     """Decision latency of the two host-side schedulers at the scale of the paper's deployment (hundreds of functions
     on a GPU; configuration 4's pool of 512 adapters): microseconds per call, single host thread."""
@@ -445,6 +505,8 @@ def main():
             steps, warmup = {0: (200, 40), 1: (400, 40), 3: (60, 15), 4: (60, 15)}[idx]
         if idx != 3:
             r = run_projection(ctx, mods, wl, idx, 0, steps, warmup, cpu_s, options)
+            if idx == 1:
+                r["three_projections_of_the_same_activations"] = run_fused_copies(ctx, mods, wl, 3, 200, 40)
             per_config.append(dict(index=idx, **r))
             sys.stderr.write(f"bench: config {idx} done at {time.perf_counter() - t_start:.0f} s\n")
             continue

@@ -40,8 +40,28 @@ __device__ __forceinline__ float lane_entry(float mine, int idx) {
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// The projection a block of weight rows (streaming kernel) or a column block (reduction) belongs to, and the index
+// inside it: the launch's fields are overwritten with that projection's.
+__device__ __forceinline__ void select_set(DecodeArgs &p, const DecodeArgs &p0, int &idx, bool by_column) {
+    if (p0.n_sets <= 0) return;
+    int si = 0;
+    while (si + 1 < p0.n_sets && idx >= (by_column ? p0.set[si + 1].cb0 : p0.set[si + 1].blk0)) ++si;
+    idx -= by_column ? p0.set[si].cb0 : p0.set[si].blk0;
+    p.W = p0.set[si].W;
+    p.ldw = p0.set[si].ldw;
+    p.A = p0.set[si].A;
+    p.B = p0.set[si].B;
+    p.scale = p0.set[si].scale;
+    p.Y = p0.set[si].Y;
+    p.ldy = p0.set[si].ldy;
+    p.P = p0.set[si].P;
+    p.N = p0.set[si].N;
+    p.nbw = p0.set[si].nbw;
+    p.n_adapters = p0.set[si].n_adapters;
+}
+
 template <int TBLK, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void decode_stream_kernel(DecodeArgs p) {
+__global__ __launch_bounds__(MAXW * 64) void decode_stream_kernel(DecodeArgs p0) {
     typedef __bf16 E;
     constexpr int CE = 8;
     constexpr int XROWS = TBLK * 16;
@@ -54,8 +74,10 @@ __global__ __launch_bounds__(MAXW * 64) void decode_stream_kernel(DecodeArgs p) 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = blockDim.x, nw = nthreads >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    const int slice = blockIdx.x % p.ks, grp = blockIdx.x / p.ks;
-    const int blk = grp * nw + wave;
+    const int slice = blockIdx.x % p0.ks, grp = blockIdx.x / p0.ks;
+    int blk = grp * nw + wave;
+    DecodeArgs p = p0;
+    select_set(p, p0, blk, false);  // (a workgroup's waves may belong to two projections: the X slice is the same)
     // (the plan's status is wanted only before anything is stored: nothing requested until then depends on a valid
     // plan -- a failed build leaves an extension axis of length 0 -- so its round trip is not waited for here)
     const int status = p.plan.scalars[kScStatus];
@@ -188,13 +210,15 @@ constexpr int kVsStride = 68;  // floats per row of the staged rank tile (64 + p
 // RQ: quads of ranks a lane gathers per 64-rank tile of V (1, 2 or 4: enough for the plan's largest rank, so that the
 // gather needs no per-lane branch -- loads behind a branch would each be waited for on their own).
 template <int TBLK, int RQ>
-__global__ __launch_bounds__(TBLK * 64) void decode_reduce_kernel(DecodeArgs p) {
+__global__ __launch_bounds__(TBLK * 64) void decode_reduce_kernel(DecodeArgs p0) {
     typedef __bf16 E;
     __shared__ __attribute__((aligned(16))) float vs[TBLK * 16 * kVsStride];
     const int tid = threadIdx.x, lane = tid & 63, tb = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 15, lg = lane >> 4;
-    LORA_TS(p.trace, 0);
-    const int cb = blockIdx.x;
+    LORA_TS(p0.trace, 0);
+    int cb = blockIdx.x;
+    DecodeArgs p = p0;
+    select_set(p, p0, cb, true);
     const int n = cb * 16 + lg * 4;
     const int t = tb * 16 + li;
     const bool tv = t < p.T;
@@ -336,10 +360,31 @@ hipError_t init_stream() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)stream_smem<TBLK, MAXW>(MAXW));
 }
 
+// Lays the projections of a launch out in the two grids; returns the totals.
+void layout_sets(DecodeArgs &a, long *blocks_out, long *cols_out) {
+    if (a.n_sets <= 0) {
+        *blocks_out = (long)a.nbe_cap + a.nbw;
+        *cols_out = a.nbw;
+        return;
+    }
+    long blk = 0, cb = 0;
+    for (int i = 0; i < a.n_sets; ++i) {
+        a.set[i].blk0 = (int32_t)blk;
+        a.set[i].cb0 = (int32_t)cb;
+        blk += (long)a.nbe_cap + a.set[i].nbw;
+        cb += a.set[i].nbw;
+    }
+    *blocks_out = blk;
+    *cols_out = cb;
+}
+
 template <int TBLK, int MAXW>
-hipError_t launch_stream_t(const DecodeArgs &a, hipStream_t stream, const KernelTimer *timer) {
-    if (a.waves < kDecodeMinWaves || a.waves > MAXW) return hipErrorInvalidValue;
-    const long groups = ((long)a.nbe_cap + a.nbw + a.waves - 1) / a.waves;
+hipError_t launch_stream_t(const DecodeArgs &a0, hipStream_t stream, const KernelTimer *timer) {
+    if (a0.waves < kDecodeMinWaves || a0.waves > MAXW) return hipErrorInvalidValue;
+    DecodeArgs a = a0;
+    long blocks = 0, cols = 0;
+    layout_sets(a, &blocks, &cols);
+    const long groups = (blocks + a.waves - 1) / a.waves;
     const long grid = groups * a.ks;
     if (grid <= 0) return hipSuccess;
 #ifdef LORA_TRACE
@@ -356,15 +401,19 @@ hipError_t launch_stream_t(const DecodeArgs &a, hipStream_t stream, const Kernel
 }
 
 template <int TBLK, int RQ>
-hipError_t launch_reduce_q(const DecodeArgs &a, hipStream_t stream, const KernelTimer *timer) {
+hipError_t launch_reduce_q(const DecodeArgs &a0, hipStream_t stream, const KernelTimer *timer) {
+    DecodeArgs a = a0;
+    long blocks = 0, cols = 0;
+    layout_sets(a, &blocks, &cols);
+    if (cols <= 0) return hipSuccess;
 #ifdef LORA_TRACE
-    return trace_launch("decode_reduce", a.nbw, [&](long long *buf) {
+    return trace_launch("decode_reduce", cols, [&](long long *buf) {
         DecodeArgs b = a;
         b.trace = buf;
-        return launch_kernel(decode_reduce_kernel<TBLK, RQ>, dim3((unsigned)a.nbw), dim3(TBLK * 64), 0, stream, timer, b);
+        return launch_kernel(decode_reduce_kernel<TBLK, RQ>, dim3((unsigned)cols), dim3(TBLK * 64), 0, stream, timer, b);
     });
 #else
-    return launch_kernel(decode_reduce_kernel<TBLK, RQ>, dim3((unsigned)a.nbw), dim3(TBLK * 64), 0, stream, timer, a);
+    return launch_kernel(decode_reduce_kernel<TBLK, RQ>, dim3((unsigned)cols), dim3(TBLK * 64), 0, stream, timer, a);
 #endif
 }
 
@@ -376,9 +425,15 @@ hipError_t launch_reduce_t(const DecodeArgs &a, hipStream_t stream, const Kernel
 }
 
 bool decode_args_ok(const DecodeArgs &a, int tblk) {
-    return a.T > 0 && a.T <= tblk * 16 && a.K > 0 && (a.K & 7) == 0 && a.N > 0 && a.nbw == (a.N + 15) / 16 && a.nbe_cap >= 0 &&
-           a.ks == (a.K / 8 + kDsSliceChunks - 1) / kDsSliceChunks && a.P != nullptr && a.X != nullptr && a.W != nullptr &&
-           a.Y != nullptr;
+    if (!(a.T > 0 && a.T <= tblk * 16 && a.K > 0 && (a.K & 7) == 0 && a.nbe_cap >= 0 && a.X != nullptr &&
+          a.ks == (a.K / 8 + kDsSliceChunks - 1) / kDsSliceChunks && a.n_sets >= 0 && a.n_sets <= kMaxGemmSets))
+        return false;
+    if (a.n_sets == 0) return a.N > 0 && a.nbw == (a.N + 15) / 16 && a.P != nullptr && a.W != nullptr && a.Y != nullptr;
+    for (int i = 0; i < a.n_sets; ++i) {
+        const DecodeSet &s = a.set[i];
+        if (!(s.N > 0 && s.nbw == (s.N + 15) / 16 && s.P != nullptr && s.W != nullptr && s.Y != nullptr)) return false;
+    }
+    return true;
 }
 
 }  // namespace

@@ -189,6 +189,25 @@ enum GemmVariant {
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
 
+// One projection of a decode launch that covers several projections of the same X (fused QKV, gate + up): its blocks of
+// weight rows follow the previous projection's in the streaming kernel's grid, its column blocks in the reduction's.
+struct DecodeSet {
+    const void *W;
+    int64_t ldw;
+    const void *const *A;
+    const void *const *B;
+    const float *scale;
+    void *Y;
+    int64_t ldy;
+    float *P;
+    int32_t N;
+    int32_t nbw;
+    int32_t n_adapters;
+    int32_t blk0;  // first block of weight rows (set by the launcher)
+    int32_t cb0;   // first column block of the reduction's grid (set by the launcher)
+    int32_t pad_;
+};
+
 // Decode-sized batches (bf16, at most kDecodeMaxRows rows): two launches, see decode_kernels.hip.
 struct DecodeArgs {
     PlanView plan;
@@ -210,6 +229,8 @@ struct DecodeArgs {
     int32_t ks;            // slices of 512 along K
     int32_t waves;         // waves (= 16-row blocks) per workgroup of the streaming kernel
     long long *trace = nullptr;  // phase stamps (trace builds only)
+    int32_t n_sets = 0;    // > 0: the projections of the launch (W .. P, N, nbw, n_adapters above are then unused)
+    DecodeSet set[kMaxGemmSets];
 };
 constexpr int kDecodeMaxRows = 128;
 constexpr int kDecodeMinWaves = 8, kDecodeMaxWaves = 12;

@@ -453,40 +453,63 @@ bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
 }
 
-// The two launches of the decode path share one argument block.
-DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, const GemmChoice &c) {
-    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
-    const bool ad = has_adapters(plan, d);
+// The two launches of the decode path share one argument block.  n > 1: several projections of the same X, their
+// blocks of weight rows side by side in the first launch's grid and their column blocks in the second's.
+DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, const GemmChoice &c) {
+    const lora_linear_desc *d = descs[0];
+    bool any_ad = false;
+    for (int i = 0; i < n; ++i) any_ad = any_ad || has_adapters(plan, descs[i]);
     // ranks the batch can use at most: one adapter per request, per slot, per row
     const int64_t segs = std::min<int64_t>(std::min<int64_t>(plan->n_req, plan->n_adapters), plan->T);
-    const DecodeGeom g = decode_geom(plan->T, d->K, d->N, ad ? segs * plan->r_max : 0);
     DecodeArgs a;
     a.plan = view_of(plan);
     a.X = d->X;
     a.ldx = d->ldx;
-    a.W = d->W0;
-    a.ldw = d->ldw;
-    a.A = ad ? d->tbl->A : nullptr;
-    a.B = ad ? d->tbl->B : nullptr;
-    a.scale = ad ? d->tbl->scale : nullptr;
-    a.Y = d->Y;
-    a.ldy = d->ldy;
-    a.P = reinterpret_cast<float *>(static_cast<unsigned char *>(d->workspace) + w.p_off);
     a.T = (int32_t)plan->T;
     a.K = d->K;
-    a.N = d->N;
     a.r_max = plan->r_max;
-    a.n_adapters = ad ? d->tbl->n_adapters : 0;
-    a.nbw = g.nbw;
-    a.nbe_cap = g.nbe_cap;
-    a.ks = g.ks;
+    a.n_sets = n > 1 ? n : 0;
+    long nblk = 0;
+    for (int i = 0; i < n; ++i) {
+        const lora_linear_desc *di = descs[i];
+        const WorkspaceLayout w = workspace_layout(plan->T, di->K, di->N, plan->r_max, di->dtype);
+        const DecodeGeom g = decode_geom(plan->T, di->K, di->N, any_ad ? segs * plan->r_max : 0);
+        const bool ad = has_adapters(plan, di);
+        DecodeSet &st = a.set[i];
+        st.W = di->W0;
+        st.ldw = di->ldw;
+        st.A = ad ? di->tbl->A : nullptr;
+        st.B = ad ? di->tbl->B : nullptr;
+        st.scale = ad ? di->tbl->scale : nullptr;
+        st.Y = di->Y;
+        st.ldy = di->ldy;
+        st.P = reinterpret_cast<float *>(static_cast<unsigned char *>(di->workspace) + w.p_off);
+        st.N = di->N;
+        st.nbw = g.nbw;
+        st.n_adapters = ad ? di->tbl->n_adapters : 0;
+        st.blk0 = st.cb0 = st.pad_ = 0;
+        a.nbe_cap = g.nbe_cap;
+        a.ks = g.ks;
+        nblk += (long)g.nbe_cap + g.nbw;
+    }
+    const DecodeSet &s0 = a.set[0];  // (one projection: the launch's own fields)
+    a.W = s0.W;
+    a.ldw = s0.ldw;
+    a.A = s0.A;
+    a.B = s0.B;
+    a.scale = s0.scale;
+    a.Y = s0.Y;
+    a.ldy = s0.ldy;
+    a.P = s0.P;
+    a.N = s0.N;
+    a.nbw = s0.nbw;
+    a.n_adapters = s0.n_adapters;
     // waves per workgroup: whole rounds of one workgroup per CU, as little of the last round idle as possible
     const int maxw = c.tblk <= 4 ? kDecodeMaxWaves : kDecodeMinWaves;
-    const long nblk = (long)g.nbe_cap + g.nbw;
     long best = -1;
     a.waves = kDecodeMinWaves;
     for (int w = maxw; w >= kDecodeMinWaves; --w) {
-        const long wgs = ((nblk + w - 1) / w) * g.ks;
+        const long wgs = ((nblk + w - 1) / w) * a.ks;
         const long cost = ((wgs + ctx->num_cu - 1) / ctx->num_cu) * w;
         if (best < 0 || cost < best) {
             best = cost;
@@ -497,6 +520,17 @@ DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_
     return a;
 }
 
+int do_decode(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, const GemmChoice &c,
+              hipStream_t stream) {
+    const DecodeArgs a = decode_args(ctx, plan, descs, n, c);
+    KernelTimer t1, t2;
+    const bool timed1 = next_timer(ctx, kProfShrink, &t1);
+    LORA_HIP(launch_decode_stream(a, c.tblk, stream, timed1 ? &t1 : nullptr));  // streams W0 and the used A_a against X
+    const bool timed2 = next_timer(ctx, kProfGemm, &t2);
+    LORA_HIP(launch_decode_reduce(a, c.tblk, stream, timed2 ? &t2 : nullptr));  // sums the slices, adds V B_a, stores Y
+    return LORA_OK;
+}
+
 // (multi: several projections of the same X that go through one launch)
 int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, hipStream_t stream,
               const lora_linear_desc *const *multi = nullptr, int n_multi = 0) {
@@ -505,7 +539,7 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
         if (c.variant == kGemmDecode) {  // decode-sized: the first launch streams W0 and the used A_a against X
             KernelTimer timer;
             const bool timed = next_timer(ctx, kProfShrink, &timer);
-            LORA_HIP(launch_decode_stream(decode_args(ctx, plan, d, c), c.tblk, stream, timed ? &timer : nullptr));
+            LORA_HIP(launch_decode_stream(decode_args(ctx, plan, &d, 1, c), c.tblk, stream, timed ? &timer : nullptr));
             return LORA_OK;
         }
     }
@@ -635,7 +669,7 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     KernelTimer timer, etimer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
     if (c.variant == kGemmDecode) {  // decode-sized: the second launch sums the slices, adds V B_a, stores Y
-        LORA_HIP(launch_decode_reduce(decode_args(ctx, plan, d, c), c.tblk, stream, timed ? &timer : nullptr));
+        LORA_HIP(launch_decode_reduce(decode_args(ctx, plan, &d, 1, c), c.tblk, stream, timed ? &timer : nullptr));
         return LORA_OK;
     }
     GemmSet g;
@@ -666,12 +700,12 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
 
 // Several projections of the same X in one GEMM launch (their column tiles side by side in one grid: one ramp, one
 // set of whole rounds of tiles for all of them).  0: this batch / these options take the projections one by one;
-// 1: the tiled kernel (one launch of each kernel for all of them).
+// 1: the tiled kernel (one launch of each kernel for all of them); 2: the decode path's two launches for all of them.
 int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *const *descs, int n, GemmChoice *c) {
     int32_t ns[kMaxGemmSets];
     for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
-    // decode-sized batches take the projections one after the other (two short launches each)
-    if (choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype).variant == kGemmDecode) return 0;
+    *c = choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype);
+    if (c->variant == kGemmDecode) return 2;
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
     if (c->variant == kGemmDecode) return 0;
     return 1;
@@ -962,6 +996,7 @@ int lora_linear_multi(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_
         }
         return LORA_OK;
     }
+    if (kind == 2) return do_decode(ctx, plan, descs, n, c, s);
     const int rc = do_shrink(ctx, plan, descs[0], s, descs, n);  // one launch: the single projection's grid once per projection
     if (rc != LORA_OK) return rc;
     return do_gemm_multi(ctx, plan, descs, n, c, s);

@@ -156,7 +156,7 @@ def test_random_segment_mixes_fused_and_separate(seed):
 def test_linear_multi_projections_of_the_same_activations(dtype):
     """lora_linear_multi: three projections of one X (different widths, one ragged) in one call -- every output
     against the oracle and against the single-projection call; tile shapes, adapter term fused / separate; a
-    decode-sized batch (taken one projection after the other); argument errors."""
+    decode-sized batch (bf16: the decode path's two launches cover all three); argument errors."""
     import torch
     from workloads.configs import Projection
     from gpu_common import B, rt, ctx, check_against_oracle, reset_options, TOL
@@ -211,6 +211,43 @@ def test_linear_multi_projections_of_the_same_activations(dtype):
         assert B.lora_linear_multi(c.handle, pl.struct, [d[0], d_same_y], st, raw=True) == B.LORA_ERR_INVALID_ARG
         assert B.lora_linear_multi(c.handle, pl.struct, d, st, raw=True) == B.LORA_OK
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("T,n_proj", [(1, 2), (9, 3), (24, 4), (50, 3), (90, 2), (128, 3)])
+def test_decode_sized_multi_projections(T, n_proj):
+    """lora_linear_multi on decode-sized bf16 batches: projections of different widths (one ragged, one without
+    adapters), several K slices with a ragged last one -- each output against the oracle, and bit-equal to the
+    single-projection call (the same partial tiles summed in the same order)."""
+    import torch
+    from workloads.configs import Projection
+    from gpu_common import rt, ctx, check_against_oracle, reset_options
+    from workloads import to_f64
+    c = ctx()
+    reset_options()
+    rng = np.random.default_rng(77 + T)
+    ranks = (8, 16, 64, 40, 8, 24, 32, 48, 128)
+    ids = rng.integers(-1, len(ranks), size=T)
+    wl = make_custom(seed=1200 + T, dtype="bf16", K=1288, N=520, ranks=ranks, scales=tuple(0.5 + 0.25 * i for i in range(len(ranks))),
+                     req_adapter=ids, req_ntok=np.ones(T, np.int64), name=f"decode_multi_{T}")
+    widths = [520, 264, 1100, 48][:n_proj]
+    wl.projections = [Projection(chr(97 + q), 1288, n) for q, n in enumerate(widths)]
+    wl.shared_x = True
+    dev = c.device
+    up = [rt.upload_workload(wl, q, dev) for q in range(n_proj)]
+    X = up[0][0]
+    pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks, wl.r_max)
+    bare = 1  # this projection goes without its adapter table
+    outs = rt.linear_multi(c, pl, X, [(u[1], None if q == bare else u[2]) for q, u in enumerate(up)])
+    torch.cuda.synchronize()
+    for q in range(n_proj):
+        got = rt.bits_from_tensor(outs[q])
+        single = rt.bits_from_tensor(rt.linear(c, pl, X, up[q][1], None if q == bare else up[q][2]))
+        torch.cuda.synchronize()
+        assert np.array_equal(got, single), f"projection {q}"
+        if q != bare:
+            e = check_against_oracle(wl, to_f64(got), p=q)
+    assert pl.status(c)[0] == 0
+    print(f"{wl.name}: T={T} n_proj={n_proj} err/rms {e:.2e}", flush=True)
 
 
 @pytest.mark.parametrize("T", [1, 5, 16, 17, 32, 33, 64, 73, 100, 128])
