@@ -312,13 +312,14 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     const int tid = threadIdx.x;
     LORA_TS(p0.trace, 0);
 
-    // several projections of the same X: the single-projection grid once per projection
+    // several projections of the same X: the single-projection grid with the projections innermost -- the
+    // workgroups that read the same rows of X (one unit, one rank block, every projection) are neighbours in the
+    // grid and run together, so a row of X comes from HBM once and from L2 for the others
     ShrinkArgs p = p0;
     int bid = blockIdx.x;
     if (p0.n_sets > 0) {
-        const int per = (p.max_units + 7) / 8 * 8 * p.rank_groups;
-        const int si = bid / per;
-        bid -= si * per;
+        const int si = bid % p0.n_sets;
+        bid /= p0.n_sets;
         p.A = p0.set[si].A;
         p.scale = p0.set[si].scale;
         p.V = p0.set[si].V;
