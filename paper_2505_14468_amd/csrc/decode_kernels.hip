@@ -442,8 +442,8 @@ hipError_t init_decode_kernels() {
     hipError_t e = init_stream<1, kDecodeMaxWaves>();
     if (e == hipSuccess) e = init_stream<2, kDecodeMaxWaves>();
     if (e == hipSuccess) e = init_stream<4, kDecodeMaxWaves>();
-    if (e == hipSuccess) e = init_stream<6, kDecodeMinWaves>();
-    if (e == hipSuccess) e = init_stream<8, kDecodeMinWaves>();
+    if (e == hipSuccess) e = init_stream<6, kDecodeMaxWaves>();
+    if (e == hipSuccess) e = init_stream<8, kDecodeMaxWaves>();
     return e;
 }
 
@@ -458,9 +458,9 @@ hipError_t launch_decode_stream(const DecodeArgs &a, int tblk, hipStream_t strea
         case 4:
             return launch_stream_t<4, kDecodeMaxWaves>(a, stream, timer);
         case 6:
-            return launch_stream_t<6, kDecodeMinWaves>(a, stream, timer);
+            return launch_stream_t<6, kDecodeMaxWaves>(a, stream, timer);
         case 8:
-            return launch_stream_t<8, kDecodeMinWaves>(a, stream, timer);
+            return launch_stream_t<8, kDecodeMaxWaves>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

@@ -316,7 +316,8 @@ DecodeGeom decode_geom(int64_t T, int32_t K, int32_t N, int64_t ext_rows_bound) 
     return g;
 }
 
-// (ns / n_sets: the output widths of the projections one launch covers; the decode path takes one)
+// (ns / n_sets: the output widths of the projections one tiled launch covers; the decode path is chosen per projection,
+// with n_sets == 1, and covers several projections with its own launches)
 GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int32_t *ns, int n_sets, int32_t dtype) {
     GemmChoice c{kGemmTile128x128, 0, kDecodeMinWaves};
     const int max_rows = ctx && ctx->opt_decode_max_rows >= 0 ? ctx->opt_decode_max_rows : kDecodeMaxRows;
@@ -505,7 +506,7 @@ DecodeArgs decode_args(const lora_ctx *ctx, const lora_plan_t *plan, const lora_
     a.nbw = s0.nbw;
     a.n_adapters = s0.n_adapters;
     // waves per workgroup: whole rounds of one workgroup per CU, as little of the last round idle as possible
-    const int maxw = c.tblk <= 4 ? kDecodeMaxWaves : kDecodeMinWaves;
+    const int maxw = kDecodeMaxWaves;
     long best = -1;
     a.waves = kDecodeMinWaves;
     for (int w = maxw; w >= kDecodeMinWaves; --w) {
