@@ -398,6 +398,21 @@ def run_fused_copies(ctx, mods, wl, n_proj, steps, warmup):
     return res
 
 
+def run_batch_sweep(ctx, mods, options):
+    """Configuration 1's layer (4096 -> 4096, 32 adapters of rank 16, one-token requests, adapter ids uniform) at other
+    batch sizes: the decode path up to 128 rows, the tiled GEMM split along K up to a few hundred, the tiled GEMM."""
+    from workloads import make_custom
+    np = mods[0]
+    rng = np.random.default_rng(11)
+    rows = []
+    for T in (1, 16, 64, 128, 256, 512, 1024):
+        wl = make_custom(seed=900 + T, dtype="bf16", K=4096, N=4096, ranks=[16] * 32, scales=[2.0] * 32,
+                         req_adapter=rng.integers(0, 32, size=T), req_ntok=np.ones(T, np.int64), name=f"decode_shape_T{T}")
+        r = run_projection(ctx, mods, wl, 1, 0, 100, 20, 0.0, options)
+        rows.append({"rows": T, "ms_per_layer": r["ms_per_layer"], "ms_per_step": r["ms_per_step"], "kernel": r["roofline"]["kernel"]})
+    return rows
+
+
 def run_schedulers(np):
     """Decision latency of the two host-side schedulers at the scale of the paper's deployment (hundreds of functions
     on a GPU; configuration 4's pool of 512 adapters): microseconds per call, single host thread."""
@@ -534,6 +549,7 @@ def main():
               "ms_per_step_plan_amortised", "kernel_us", "whole_call", "adapter_path", "parity_max_err_over_rms"):
         out[k] = head[k]
     out["per_config"] = per_config
+    out["batch_size_sweep_config1_shape"] = run_batch_sweep(ctx, mods, options)
     out["schedulers"] = run_schedulers(np)
     out["targets"] = {"prefill (configs 2, 3)": ">= 0.60 of bf16 MFMA peak", "decode / adapter-heavy (configs 1, 4)": ">= 0.70 of HBM peak (whole_call.frac_of_hbm_peak)"}
     print(json.dumps(out))

@@ -165,7 +165,8 @@ int lora_ctx_destroy(lora_ctx *ctx);
  * plan kernels), "plan_fused_rows" (most rows for which one workgroup builds
  * the whole plan), "expand_split" (0 / 1: adapter term always computed inside
  * the GEMM / by the separate expand kernel whenever the workspace has room
- * for it), "shrink_rank_block" (8 / 16 / 32 / 64).  value < 0 restores the
+ * for it), "gemm_split_k" (0: never split the tiled GEMM along K),
+ * "shrink_rank_block" (8 / 16 / 32 / 64).  value < 0 restores the
  * built-in choice.  Results never depend on them beyond fp32 summation order.
  * Not thread-safe against concurrent calls on the same ctx.  Errors:
  * INVALID_ARG for an unknown name or a value the option does not take. */
@@ -236,8 +237,11 @@ size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_ma
  * in fp32 ([T, N]).  Batches of many small segments then compute that term
  * in a weight-streaming kernel of its own and the GEMM adds it before its
  * single rounding of Y; with a smaller workspace the term is computed inside
- * the GEMM (same result within fp32 summation order).  Returns 0 for invalid
- * arguments. */
+ * the GEMM (same result within fp32 summation order).  For batches of 129 to
+ * 1024 rows whose output tiles would leave most of the chip idle it also has
+ * room for the fp32 partial outputs of a GEMM split along K (2 to 8 copies
+ * of [T, N]; a second launch sums them in a fixed order, adds the adapter
+ * term and rounds Y once).  Returns 0 for invalid arguments. */
 size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
 
 /* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an

@@ -54,7 +54,8 @@ struct ExtTable {
     unsigned char use_d[256];  // tile row takes its adapter term from D (the expand kernel's result)
 };
 
-template <typename E, int BM, int BN, int WM, int WN>
+// SPLIT: the launch is split along K (grid y = split index); partial tiles go to GemmArgs::P in fp32.
+template <typename E, int BM, int BN, int WM, int WN, bool SPLIT>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int tiles_m, int tiles_n, int group_m) {
     constexpr int CE = Elem<E>::CE;
     constexpr int NT = WM * WN * 64;
@@ -97,7 +98,13 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     const int wn0 = (wave % WN) * WTN, wm0 = (wave / WN) * WTM;
     const int l31 = lane & 31, lh = lane >> 5;
 
-    const E *W = static_cast<const E *>(g.W);
+    // this workgroup's stretch of the contraction axis
+    int k0 = 0, Kloc = p.K;
+    if constexpr (SPLIT) {
+        k0 = (int)blockIdx.y * p.k_chunk;
+        Kloc = min(p.K - k0, p.k_chunk);
+    }
+    const E *W = static_cast<const E *>(g.W) + k0;
     const E *V = static_cast<const E *>(g.V);
 
     // ---- per-thread load slots ------------------------------------------------------------
@@ -105,8 +112,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // 32-bit byte offsets (row start + this thread's chunk of a stage) against a scalar base that moves along K:
     // a load then needs no vector address arithmetic at all, and one register of address.  X is
     // addressed from its start (the host checks that it is smaller than 4 GiB), W0 from the tile's first row.
-    const BufferDesc Xd = make_buffer_desc(p.X);
-    const BufferDesc Wd = make_buffer_desc(static_cast<const char *>(g.W) + (int64_t)n0 * g.ldw * (int64_t)sizeof(E));
+    const BufferDesc Xd = make_buffer_desc(static_cast<const E *>(p.X) + k0);
+    const BufferDesc Wd = make_buffer_desc(W + (int64_t)n0 * g.ldw);
     unsigned xoff[XL], woff[WL];
     int xrowi[XL];  // original row index of each load slot (V is stored in original row order)
 #pragma unroll
@@ -222,7 +229,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
 #pragma unroll
             for (int i = 0; i < WL; ++i) wr[i] = buffer_load_chunk(Wd, woff[i], kt * 128);
         } else {
-            const bool kv = (kt * 8 + lc) * CE < p.K;
+            const bool kv = (kt * 8 + lc) * CE < Kloc;
             // dropped loads read the start of the row (all of it in the per-lane offset: the scalar one must be uniform)
             const unsigned adj = kv ? (unsigned)kt * 128u : 0u - (unsigned)lc * 16u;
 #pragma unroll
@@ -306,8 +313,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // and barrier, the other half after the barrier, behind the first operand reads of the next
     // stage, whose latency they cover.  Global loads for the stage after next are issued right
     // behind the barrier and have a whole stage to arrive.
-    const int KT = (p.K + 8 * CE - 1) / (8 * CE);
-    const int KT_full = p.K / (8 * CE);  // stages that lie entirely inside K
+    const int KT = (Kloc + 8 * CE - 1) / (8 * CE);
+    const int KT_full = Kloc / (8 * CE);  // stages that lie entirely inside K
     auto read_w = [&](int buf, int kk, int nb) { return sW[buf * BN * 8 + swz(wn0 + nb * 32 + l31, 2 * kk + lh)]; };
     auto read_x = [&](int buf, int kk, int tb) { return sX[buf * BM * 8 + swz(wm0 + tb * 32 + l31, 2 * kk + lh)]; };
     load_base(0, KT_full < 1);
@@ -375,7 +382,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         // the XL + WL load slots of a stage (X slots first), dealt to the four k-steps as evenly as they divide
         constexpr int NS = XL + WL;
         auto gload_q = [&](chunk_t (&xs)[XL], chunk_t (&ws)[WL], int kq, int q, bool partial) {
-            const bool kv = !partial || (kq * 8 + lc) * CE < p.K;
+            const bool kv = !partial || (kq * 8 + lc) * CE < Kloc;
             // (partial stage: all of the offset per lane -- the scalar one must be uniform; dropped loads read the row start)
             const unsigned adj = !partial ? 0u : (kv ? (unsigned)kq * 128u : 0u - (unsigned)lc * 16u);
             const int soff = partial ? 0 : kq * 128;
@@ -495,6 +502,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     }
 
     // ---- single store of Y: acc[nb][tb][g*4+e] = D[n = nb*32 + g*8 + lh*4 + e][t = tb*32 + l31] -------
+    if constexpr (SPLIT) {  // the partial tile, in fp32, to this split's copy of the output
+        float *P = p.P + (int64_t)blockIdx.y * p.T * p.ldp;
+#pragma unroll
+        for (int tb = 0; tb < NBT; ++tb) {
+            const int t = m0 + wm0 + tb * 32 + l31;
+            float *prow = P + (int64_t)p.plan.perm[min(t, p.T - 1)] * p.ldp;
+#pragma unroll
+            for (int nb = 0; nb < NBN; ++nb) store_acc_tile<float>(acc[nb][tb], prow, nullptr, n0 + wn0 + nb * 32, lh, g.N, t < p.T);
+        }
+        return;
+    }
     E *Y = static_cast<E *>(g.Y);
     if (g.D == nullptr) {
 #pragma unroll
@@ -532,7 +550,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     }
 }
 
-template <typename E, int BM, int BN, int WM, int WN>
+template <typename E, int BM, int BN, int WM, int WN, bool CAN_SPLIT = false>
 hipError_t launch_tile(const GemmArgs &a0, hipStream_t stream, const KernelTimer *timer) {
     GemmArgs a = a0;
     if (a.n_sets == 0) {  // a single projection, described by the plain fields
@@ -548,23 +566,42 @@ hipError_t launch_tile(const GemmArgs &a0, hipStream_t stream, const KernelTimer
     const long total = (long)tiles_m * tiles_n;
     if (total <= 0) return hipSuccess;
     const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);
-    auto kern = gemm_tile_kernel<E, BM, BN, WM, WN>;
     const long grid = ((total + 7) / 8) * 8;
     const int group_m = 8;
-    return launch_kernel(kern, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, timer, a, tiles_m, tiles_n, group_m);
+    if (a.split_k > 1) {
+        if constexpr (CAN_SPLIT) {
+            constexpr int stage = 8 * Elem<E>::CE;
+            if (a.n_sets != 1 || a.set[0].B != nullptr || a.set[0].D != nullptr || a.P == nullptr || a.k_chunk <= 0 ||
+                a.k_chunk % stage != 0 || (long)a.k_chunk * (a.split_k - 1) >= a.K || (long)a.k_chunk * a.split_k < a.K ||
+                a.ldp < a.set[0].N || (a.ldp & 7) != 0)
+                return hipErrorInvalidValue;
+            return launch_kernel(gemm_tile_kernel<E, BM, BN, WM, WN, true>, dim3((unsigned)grid, (unsigned)a.split_k), dim3(WM * WN * 64),
+                                 smem, stream, timer, a, tiles_m, tiles_n, group_m);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
+    return launch_kernel(gemm_tile_kernel<E, BM, BN, WM, WN, false>, dim3((unsigned)grid), dim3(WM * WN * 64), smem, stream, timer, a,
+                         tiles_m, tiles_n, group_m);
 }
 
 // Dynamic LDS above the default 64 KB has to be granted per kernel and device before the first launch.
-template <typename E, int BM, int BN, int WM, int WN>
+template <typename E, int BM, int BN, int WM, int WN, bool CAN_SPLIT = false>
 hipError_t init_tile() {
     const size_t smem = (size_t)(BM + BN) * 8 * 16 * 2 + sizeof(ExtTable);
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tile_kernel<E, BM, BN, WM, WN>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tile_kernel<E, BM, BN, WM, WN, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if constexpr (CAN_SPLIT) {
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_tile_kernel<E, BM, BN, WM, WN, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    }
+    return e;
 }
 template <typename E>
 hipError_t init_tiles() {
     hipError_t e = init_tile<E, 64, 64, 2, 2>();
-    if (e == hipSuccess) e = init_tile<E, 128, 128, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 128, 128, 2, 2, true>();
     if (e == hipSuccess) e = init_tile<E, 256, 128, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 256, 4, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 256, 2, 2>();
@@ -580,7 +617,7 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
         case kGemmTile64x64:
             return launch_tile<E, 64, 64, 2, 2>(a, stream, timer);
         case kGemmTile128x128:
-            return launch_tile<E, 128, 128, 2, 2>(a, stream, timer);
+            return launch_tile<E, 128, 128, 2, 2, true>(a, stream, timer);
         case kGemmTile256x128:
             return launch_tile<E, 256, 128, 2, 2>(a, stream, timer);
         case kGemmTile256x256:
@@ -598,6 +635,61 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
     }
 }
 
+// The second launch of a GEMM split along K: one thread = 8 consecutive columns of one row; the splits' partials are
+// requested together and summed in split order, the adapter term of rows with an adapter is added, Y is rounded once.
+template <typename E>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(SplitReduceArgs p) {
+    if (p.plan.scalars[kScStatus] != 0) return;
+    const int n8 = (p.N + 7) >> 3;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)p.T * n8) return;
+    const int row = (int)(idx / n8), n = (int)(idx % n8) * 8;
+    const bool has = p.D != nullptr && p.plan.row_adapter[row] >= 0 && row_ext_rank(p.plan.row_ext[row]) > 0;
+    constexpr int kMaxSplit = 8;
+    chunk_t q[kMaxSplit][2];
+    const float *src = p.P + (int64_t)row * p.ldp + n;  // (rows are ldp >= N rounded up to 8 floats long: whole pieces are readable)
+#pragma unroll
+    for (int s = 0; s < kMaxSplit; ++s) {
+        const float *ps = src + (int64_t)min(s, p.split_k - 1) * p.T * p.ldp;
+        q[s][0] = load_chunk(ps);
+        q[s][1] = load_chunk(ps + 4);
+    }
+    const float *dsrc = has ? p.D + (int64_t)row * p.ldd + n : src;
+    const chunk_t d0 = load_chunk(dsrc), d1 = load_chunk(dsrc + 4);
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < kMaxSplit; ++s) {
+        if (s < p.split_k) {
+            v[0] += __uint_as_float(q[s][0].x);
+            v[1] += __uint_as_float(q[s][0].y);
+            v[2] += __uint_as_float(q[s][0].z);
+            v[3] += __uint_as_float(q[s][0].w);
+            v[4] += __uint_as_float(q[s][1].x);
+            v[5] += __uint_as_float(q[s][1].y);
+            v[6] += __uint_as_float(q[s][1].z);
+            v[7] += __uint_as_float(q[s][1].w);
+        }
+    }
+    if (has) {
+        v[0] += __uint_as_float(d0.x);
+        v[1] += __uint_as_float(d0.y);
+        v[2] += __uint_as_float(d0.z);
+        v[3] += __uint_as_float(d0.w);
+        v[4] += __uint_as_float(d1.x);
+        v[5] += __uint_as_float(d1.y);
+        v[6] += __uint_as_float(d1.z);
+        v[7] += __uint_as_float(d1.w);
+    }
+    E *y = static_cast<E *>(p.Y) + (int64_t)row * p.ldy + n;
+    if (n + 7 < p.N) {
+        store8(y, v);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (n + e < p.N) store1(y + e, v[e]);
+    }
+}
+
 }  // namespace
 
 hipError_t init_gemm_tile_kernels() {
@@ -608,6 +700,17 @@ hipError_t init_gemm_tile_kernels() {
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer) {
     return dtype == 1 ? launch_variant<__bf16>(a, variant, stream, timer) : launch_variant<float>(a, variant, stream, timer);
+}
+
+hipError_t launch_splitk_reduce(const SplitReduceArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer) {
+    if (a.T <= 0 || a.N <= 0) return hipSuccess;
+    if (a.split_k < 1 || a.split_k > 8 || a.P == nullptr || a.Y == nullptr || a.ldp < a.N || (a.ldp & 7) != 0 ||
+        (a.D != nullptr && (a.ldd < a.N || (a.ldd & 7) != 0)))
+        return hipErrorInvalidValue;
+    const long threads = (long)a.T * ((a.N + 7) / 8);
+    const dim3 grid((unsigned)((threads + 255) / 256));
+    if (dtype == 1) return launch_kernel(splitk_reduce_kernel<__bf16>, grid, dim3(256), 0, stream, timer, a);
+    return launch_kernel(splitk_reduce_kernel<float>, grid, dim3(256), 0, stream, timer, a);
 }
 
 }  // namespace lora

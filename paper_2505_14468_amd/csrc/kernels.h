@@ -137,6 +137,14 @@ struct GemmArgs {
                             // the tiled GEMM computes the others' as extension stages
     int32_t r_max;
     int32_t T, K, N;
+    // split along K (mid-sized batches whose tiles would not fill the chip; one projection, no adapter term here):
+    // workgroup (tile, s) multiplies columns [s * k_chunk, (s + 1) * k_chunk) of the contraction axis and stores its
+    // fp32 partial tile to P[s][row][n] (row = original row index, rows ldp floats long); launch_splitk_reduce
+    // sums the partials in order, adds the adapter term and stores Y.
+    int32_t split_k = 0;   // > 1: number of splits
+    int32_t k_chunk = 0;   // columns per split, a multiple of one stage (64 bf16 / 32 fp32 elements)
+    float *P = nullptr;
+    int64_t ldp = 0;
     // tiled kernel only: the projections of the launch (n_sets == 0: one, described by the fields above)
     int32_t n_sets = 0;
     GemmSet set[kMaxGemmSets];
@@ -188,6 +196,20 @@ enum GemmVariant {
 };
 
 hipError_t launch_gemm_tile(const GemmArgs &a, int dtype, int variant, hipStream_t stream, const KernelTimer *timer);
+
+// Y[row, :] = sum over s (in order) of P[s][row, :]  +  D[row, :] for rows with an adapter (D null: none), rounded once.
+struct SplitReduceArgs {
+    PlanView plan;
+    const float *P;
+    int64_t ldp;
+    int32_t split_k;
+    const float *D;
+    int64_t ldd;
+    void *Y;
+    int64_t ldy;
+    int32_t T, N;
+};
+hipError_t launch_splitk_reduce(const SplitReduceArgs &a, int dtype, hipStream_t stream, const KernelTimer *timer);
 
 // One projection of a decode launch that covers several projections of the same X (fused QKV, gate + up): its blocks of
 // weight rows follow the previous projection's in the streaming kernel's grid, its column blocks in the reduction's.

@@ -68,6 +68,7 @@ struct lora_ctx {
     int opt_shrink_rank_block = -1;
     int opt_plan_variant = -1;
     int opt_expand_split = -1;
+    int opt_gemm_split_k = -1;
     // profiling mode: event pairs recorded tightly around each kernel
     bool prof_on = false;
     int prof_cap = 0;
@@ -373,7 +374,32 @@ GemmChoice choose_gemm(const lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int
 struct WorkspaceLayout {
     size_t v_off, p_off, p_bytes, total;          // total: what every call needs
     size_t d_off, d_bytes, ldd, total_preferred;  // fp32 adapter term of the separate expand kernel (optional)
+    size_t sk_off, sk_bytes;                      // partial outputs of a GEMM split along K (optional, inside total_preferred)
 };
+
+// Mid-sized batches whose 128x128 tiles would leave most CUs idle: the tiled GEMM is split along K as well, its
+// fp32 partial outputs summed by a second launch.  Depends on the shape alone (the workspace is sized from it).
+struct SplitK {
+    int s, k_chunk;
+};
+SplitK choose_split_k(int64_t T, int32_t K, int32_t N, int32_t dtype) {
+    SplitK r{1, 0};
+    if (T <= kDecodeMaxRows || T > 1024) return r;  // (up to kDecodeMaxRows rows: the decode path, or a batch too small to matter)
+    const int64_t tiles = ((T + 127) / 128) * (((int64_t)N + 127) / 128);
+    // Worth it while the tiles alone leave most of the chip idle (measured at 4096 -> 4096: 129 rows 46.7 -> 37.8 us per
+    // layer, 256 rows 48.5 -> 42.7, 512 rows no gain; 11008 -> 4096, 512 rows: 126 -> 108 us; at 4096 -> 11008, 172
+    // tiles and more, the partial outputs cost more than the idle CUs: 72 -> 84 us).
+    if (tiles > 128 || (tiles > 96 && K < 8192)) return r;
+    const int stage = dtype == LORA_DTYPE_BF16 ? 64 : 32;
+    int64_t s = (384 + tiles - 1) / tiles;  // about one and a half workgroups per CU (two of them fit one)
+    s = std::min<int64_t>(s, 8);
+    s = std::min<int64_t>(s, K / (16 * stage));  // at least 16 stages per split
+    if (s < 2) return r;
+    r.k_chunk = (int)(((K + s - 1) / s + stage - 1) / stage * stage);
+    r.s = (K + r.k_chunk - 1) / r.k_chunk;
+    if (r.s < 2) r = SplitK{1, 0};
+    return r;
+}
 
 WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype) {
     WorkspaceLayout w;
@@ -388,7 +414,10 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     w.ldd = align_up((size_t)N, 8);  // (the GEMM's epilogue reads whole 8-column pieces of a row)
     w.d_off = w.total;
     w.d_bytes = T > kDecodeMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
-    w.total_preferred = align_up(w.d_off + w.d_bytes, 256);
+    w.sk_off = align_up(w.d_off + w.d_bytes, 256);
+    const SplitK sk = choose_split_k(T, K, N, dtype);
+    w.sk_bytes = sk.s > 1 ? (size_t)sk.s * (size_t)T * w.ldd * sizeof(float) : 0;
+    w.total_preferred = align_up(w.sk_off + w.sk_bytes, 256);
     return w;
 }
 
@@ -601,8 +630,11 @@ int do_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d,
 // kernel of its own into the workspace (fp32), which is launched here, and added by the GEMM to its accumulators;
 // the second only if the caller's workspace has the room.  Describes the projection for the GEMM in *out.
 // (collect: several projections in one launch -- the expand kernel's arguments are gathered there, not launched)
+// (all_in_d: the whole adapter term through the expand kernel -- the caller has checked the workspace -- for a GEMM
+// that adds nothing itself)
 int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, int variant, hipStream_t stream,
-                const KernelTimer *expand_timer, GemmSet *out, bool *split_out, ExpandArgs *collect = nullptr) {
+                const KernelTimer *expand_timer, GemmSet *out, bool *split_out, ExpandArgs *collect = nullptr,
+                bool all_in_d = false) {
     const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     unsigned char *ws = static_cast<unsigned char *>(d->workspace);
     const bool ad = has_adapters(plan, d);
@@ -619,6 +651,7 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
         const int64_t segs = plan->n_adapters < plan->n_req ? plan->n_adapters : plan->n_req;  // upper bound
         split = segs > 0 && plan->T / segs < 64;
         if (ctx->opt_expand_split >= 0) split = ctx->opt_expand_split == 1;
+        if (all_in_d) split = true;
     }
     if (split) {
         ExpandArgs e;
@@ -638,7 +671,7 @@ int prepare_set(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
         // of an M tile, ~2 us each, against 8 bytes of D traffic per element and the units' reads of B_a saved: worth
         // it up to rank 64 -- C3 gate_proj 150 -> 140 us; at rank 128, C4, 428 -> 434 us) and takes the short
         // segments' from D; the other kernels take all of it from D.
-        const bool tiled = plan->r_max <= 64;
+        const bool tiled = plan->r_max <= 64 && !all_in_d;
         e.skip_long = tiled ? 1 : 0;
         if (collect != nullptr) {
             const int i = collect->n_sets;
@@ -673,10 +706,54 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         LORA_HIP(launch_decode_reduce(decode_args(ctx, plan, &d, 1, c), c.tblk, stream, timed ? &timer : nullptr));
         return LORA_OK;
     }
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
+    SplitK sk = choose_split_k(plan->T, d->K, d->N, d->dtype);
+    if (ctx->opt_gemm_split_k == 0 || (ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != kGemmTile128x128) ||
+        d->workspace_bytes < w.total_preferred || (has_adapters(plan, d) && w.d_bytes == 0))
+        sk = SplitK{1, 0};
+    if (sk.s > 1) c.variant = kGemmTile128x128;
     GemmSet g;
     bool split = false;
-    const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &etimer : nullptr, &g, &split);
+    const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &etimer : nullptr, &g, &split, nullptr, sk.s > 1);
     if (rc != LORA_OK) return rc;
+    if (sk.s > 1) {  // partial products per stretch of K, then one launch that sums them, adds the adapter term and rounds
+        GemmArgs a;
+        a.plan = view_of(plan);
+        a.X = d->X;
+        a.ldx = d->ldx;
+        a.W = g.W;
+        a.ldw = g.ldw;
+        a.Y = g.Y;
+        a.ldy = g.ldy;
+        a.V = nullptr;
+        a.B = nullptr;
+        a.D = nullptr;
+        a.ldd = 0;
+        a.r_max = plan->r_max;
+        a.T = (int32_t)plan->T;
+        a.K = d->K;
+        a.N = d->N;
+        a.split_k = sk.s;
+        a.k_chunk = sk.k_chunk;
+        a.P = reinterpret_cast<float *>(static_cast<unsigned char *>(d->workspace) + w.sk_off);
+        a.ldp = (int64_t)w.ldd;
+        LORA_HIP(launch_gemm_tile(a, d->dtype, c.variant, stream, timed ? &timer : nullptr));
+        SplitReduceArgs r;
+        r.plan = a.plan;
+        r.P = a.P;
+        r.ldp = a.ldp;
+        r.split_k = sk.s;
+        r.D = g.D;  // (null when the call has no adapters)
+        r.ldd = g.ldd;
+        r.Y = d->Y;
+        r.ldy = d->ldy;
+        r.T = a.T;
+        r.N = d->N;
+        KernelTimer rtimer;
+        const bool rtimed = timed && next_timer(ctx, kProfGemm, &rtimer);
+        LORA_HIP(launch_splitk_reduce(r, d->dtype, stream, rtimed ? &rtimer : nullptr));
+        return LORA_OK;
+    }
     GemmArgs a;
     a.plan = view_of(plan);
     a.X = d->X;
@@ -818,6 +895,9 @@ int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
         ctx->opt_decode_max_rows = value;
     } else if (!strcmp(name, "plan_fused_rows")) {
         ctx->opt_plan_fused_rows = value;
+    } else if (!strcmp(name, "gemm_split_k")) {
+        if (value > 1) return LORA_ERR_INVALID_ARG;
+        ctx->opt_gemm_split_k = value;
     } else if (!strcmp(name, "expand_split")) {
         if (value > 1) return LORA_ERR_INVALID_ARG;
         ctx->opt_expand_split = value;
@@ -1098,6 +1178,13 @@ int lora_backbone_close(int device_ordinal, void *dev_ptr) {
 const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N, int32_t dtype) {
     static thread_local char buf[64];
     const GemmChoice c = choose_gemm(ctx, T, K, N, dtype);
+    // (with a workspace of the preferred size and an adapter table, or none)
+    const SplitK sk = choose_split_k(T, K, N, dtype);
+    if (c.variant != kGemmDecode && sk.s > 1 && !(ctx && ctx->opt_gemm_split_k == 0) &&
+        !(ctx && ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != kGemmTile128x128)) {
+        snprintf(buf, sizeof buf, "tile_128x128_splitk%d", sk.s);
+        return buf;
+    }
     switch (c.variant) {
         case kGemmDecode:
             snprintf(buf, sizeof buf, "decode_tb%d", c.tblk);

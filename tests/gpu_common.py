@@ -20,7 +20,7 @@ def ctx():
 
 
 def reset_options():
-    for name in ("gemm_variant", "decode_waves", "decode_max_rows", "plan_fused_rows", "plan_variant", "expand_split",
+    for name in ("gemm_variant", "decode_waves", "decode_max_rows", "plan_fused_rows", "plan_variant", "expand_split", "gemm_split_k",
                  "shrink_rank_block"):
         ctx().set_option(name, -1)
 

@@ -213,6 +213,46 @@ def test_linear_multi_projections_of_the_same_activations(dtype):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("dtype,K,N,T", [("bf16", 2312, 520, 129), ("bf16", 2312, 520, 384), ("bf16", 8200, 264, 200),
+                                          ("bf16", 4096, 1100, 300), ("f32", 1032, 264, 150), ("f32", 2056, 520, 140)])
+def test_mid_sized_batches_split_along_k(dtype, K, N, T):
+    """Batches whose 128x128 tiles would not fill the chip go through the GEMM split along K (fp32 partial outputs, a
+    second launch that sums them in order, adds the adapter term and rounds once): ragged N, a last stretch of K
+    that ends in a partial stage, rows without an adapter, short and long segments -- against the oracle, against the
+    unsplit path, with and without an adapter table, and bit-equal from run to run."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, TOL
+    reset_options()
+    rng = np.random.default_rng(T + K)
+    ranks = (8, 16, 64, 40, 8, 24, 128)
+    lens, ids = [], []
+    left = T
+    while left > 0:
+        n = int(min(left, rng.choice([1, 1, 2, 7, 33, 90])))
+        lens.append(n)
+        ids.append(int(rng.integers(-1, len(ranks))))
+        left -= n
+    wl = make_custom(seed=300 + T, dtype=dtype, K=K, N=N, ranks=ranks, scales=(2.0, 0.5, 1.0, 0.25, 1.5, 1.0, 0.75),
+                     req_adapter=np.asarray(ids), req_ntok=np.asarray(lens), name=f"split_k_{dtype}_{K}_{N}_{T}")
+    assert wl.T == T
+    from gpu_common import B
+    code = 1 if dtype == "bf16" else 0
+    out = {}
+    for split in (-1, 0):
+        ctx().set_option("gemm_split_k", split)
+        assert ("splitk" in B.lora_gemm_kernel_name(ctx().handle, T, K, N, code)) == (split == -1)
+        out[split] = gpu_linear(wl, device_plan=bool(T & 1))
+        e = check_against_oracle(wl, out[split])
+    again = gpu_linear(wl, device_plan=bool(T & 1))
+    ctx().set_option("gemm_split_k", -1)
+    again = gpu_linear(wl, device_plan=bool(T & 1))
+    assert np.array_equal(again, out[-1])
+    rms = float(np.sqrt((out[0] ** 2).mean()))
+    assert float(np.abs(out[0] - out[-1]).max()) <= TOL[dtype] * rms
+    assert not np.array_equal(out[0], out[-1]) or dtype == "bf16"  # (fp32: another summation order shows in the last bits)
+    print(f"{wl.name}: err/rms {e:.2e}", flush=True)
+    reset_options()
+
+
 @pytest.mark.parametrize("T,n_proj", [(1, 2), (9, 3), (24, 4), (50, 3), (90, 2), (128, 3)])
 def test_decode_sized_multi_projections(T, n_proj):
     """lora_linear_multi on decode-sized bf16 batches: projections of different widths (one ragged, one without
