@@ -487,6 +487,50 @@ def test_strided_inputs_and_adapter_eviction():
     assert status == B.LORA_ERR_ADAPTER_NOT_RESIDENT
 
 
+@pytest.mark.parametrize("T,K", [(20, 264), (200, 2312), (700, 264)])
+def test_largest_rank_and_eviction_on_every_path(T, K):
+    """Adapters of the largest rank the library takes (512) beside small ones, on the decode path (20 rows), the GEMM
+    split along K (200 rows) and the tiled GEMM (700 rows); then one used adapter is evicted after planning: every
+    path reports it, the rows of the other adapters keep their results."""
+    import torch
+    from gpu_common import ctx, rt, check_against_oracle, B, reset_options
+    from paper_2505_14468_amd.runtime import bits_from_tensor
+    reset_options()
+    c = ctx()
+    rng = np.random.default_rng(T)
+    ranks = (512, 8, 256, 16)
+    lens = [1, 2, 3, 1]  # every adapter in use
+    left = T - sum(lens)
+    while left > 0:
+        n = int(min(left, rng.choice([1, 3, 40])))
+        lens.append(n)
+        left -= n
+    ids = rng.integers(-1, len(ranks), size=len(lens))
+    ids[:4] = (0, 1, 2, 3)
+    wl = make_custom(seed=77 + T, dtype="bf16", K=K, N=328, ranks=ranks, scales=(0.05, 2.0, 0.1, 1.0), req_adapter=ids,
+                     req_ntok=np.asarray(lens), name=f"rank512_T{T}")
+    X, W0, table = rt.upload_workload(wl, 0, c.device)
+    pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks)
+    Y = rt.linear(c, pl, X, W0, table)
+    torch.cuda.synchronize()
+    full = to_f64(bits_from_tensor(Y))
+    e = check_against_oracle(wl, full)
+    assert pl.status(c)[0] == 0
+    table.set_slot(2, None, None)
+    Y2 = rt.linear(c, pl, X, W0, table)
+    torch.cuda.synchronize()
+    assert pl.status(c)[0] == B.LORA_ERR_ADAPTER_NOT_RESIDENT
+    part = to_f64(bits_from_tensor(Y2))
+    row_ad = np.repeat(wl.req_adapter, wl.req_ntok)
+    keep = row_ad != 2
+    assert np.array_equal(part[keep], full[keep]), "rows of resident adapters changed"
+    base = to_f64(bits_from_tensor(rt.linear(c, pl, X, W0, None)))
+    torch.cuda.synchronize()
+    rms = float(np.sqrt((base ** 2).mean()))
+    assert float(np.abs(part[~keep] - base[~keep]).max()) <= 2e-2 * rms, "rows of the evicted adapter: the base product alone"
+    print(f"{wl.name}: {B.lora_gemm_kernel_name(c.handle, T, K, 328, 1)} err/rms {e:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_worked_example_derived_by_hand_is_exact(dtype):
     """tests/golden/worked_example.json: three rows, one adapter, every number exactly representable -- the GPU's
