@@ -410,7 +410,16 @@ def run_batch_sweep(ctx, mods, options):
                          req_adapter=rng.integers(0, 32, size=T), req_ntok=np.ones(T, np.int64), name=f"decode_shape_T{T}")
         r = run_projection(ctx, mods, wl, 1, 0, 100, 20, 0.0, options)
         rows.append({"rows": T, "ms_per_layer": r["ms_per_layer"], "ms_per_step": r["ms_per_step"], "kernel": r["roofline"]["kernel"]})
-    return rows
+    # The batching model of the paper's section 4.2 (equation 2), T(b) = T0 + alpha (b - 1), fitted to the layer's own
+    # times (least squares over the measured batch sizes): what a function profile for the batcher would carry.
+    b = np.array([x["rows"] for x in rows], np.float64)
+    t = np.array([x["ms_per_layer"] * 1e3 for x in rows], np.float64)
+    A = np.stack([np.ones_like(b), b - 1.0], axis=1)
+    (t0, alpha), *_ = np.linalg.lstsq(A, t, rcond=None)
+    fit = {"t0_us": round(float(t0), 3), "alpha_us_per_request": round(float(alpha), 5),
+           "max_rel_err": round(float(np.abs(A @ np.array([t0, alpha]) - t).max() / t.max()), 4),
+           "model": "T(b) = t0 + alpha (b - 1), one-token requests, one layer"}
+    return {"rows": rows, "batching_model_fit": fit}
 
 
 def run_schedulers(np):
