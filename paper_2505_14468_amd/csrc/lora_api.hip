@@ -317,6 +317,21 @@ DecodeGeom decode_geom(int64_t T, int32_t K, int32_t N, int64_t ext_rows_bound) 
     return g;
 }
 
+// A decode-sized batch takes the decode path unless the tiled GEMM is clearly cheaper: towards 128 rows and wide
+// outputs the partial tiles of the K slices (T x N x 4 bytes per slice, written and read) outgrow the weights.
+// Both sides are fits to measured layer times in microseconds (bf16, with adapters): the decode path moves its bytes
+// at ~3.6 TB/s behind ~8 us of fixed cost; the tiled path (64x64 tiles, shrink and expand launches ~15 us) is bound
+// by its chain of K stages or by the weights at ~3 TB/s.  4096 -> 11008: decode up to 96 rows (52.8 vs 55.4 us), tiled
+// from 112 (56.4 vs 59.8); 5120 -> 13824: tiled from 72 rows (65 vs 73 us); 4096 -> 4096 and 11008 -> 4096: decode
+// throughout (28 vs 43 us, 63 vs 93 us at 128 rows).
+bool decode_path_cheaper(int64_t T, int32_t K, int32_t N) {
+    const double w_mb = 2.0e-6 * (double)K * (double)N;
+    const double p_mb = 1.024e-3 * (double)((N + 15) / 16) * (double)((K / 8 + 63) / 64) * (double)decode_tblk(T);
+    const double t_decode = 8.0 + (w_mb + 2.0 * p_mb) / 3.6;
+    const double t_tiled = 15.0 + std::max(29.0 * (double)K / 4096.0, w_mb / 3.0 + 6.0);
+    return t_decode <= 1.08 * t_tiled;
+}
+
 // (ns / n_sets: the output widths of the projections one tiled launch covers; the decode path is chosen per projection,
 // with n_sets == 1, and covers several projections with its own launches)
 GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int32_t *ns, int n_sets, int32_t dtype) {
@@ -325,7 +340,7 @@ GemmChoice choose_gemm_sets(const lora_ctx *ctx, int64_t T, int32_t K, const int
     int forced = ctx ? ctx->opt_gemm_variant : -1;
     const bool fits = dtype == LORA_DTYPE_BF16 && T <= kDecodeMaxRows && n_sets == 1;
     if (forced == kGemmDecode && !fits) forced = -1;
-    const bool decode = forced == kGemmDecode || (forced < 0 && fits && T <= max_rows);
+    const bool decode = forced == kGemmDecode || (forced < 0 && fits && T <= max_rows && decode_path_cheaper(T, K, ns[0]));
     if (decode) {
         c.variant = kGemmDecode;
         c.tblk = decode_tblk(T);
