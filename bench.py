@@ -166,8 +166,8 @@ def run_projection(ctx, mods, wl, cfg_index, p, steps, warmup, cpu_seconds, opti
     rows_by_ad = dict(zip(*np.unique(ra_rows[ra_rows >= 0], return_counts=True)))
     v_elems = int(sum(int(wl.ranks[a]) * int(n) for a, n in rows_by_ad.items()))  # sum over rows of their rank
     rows_ad = int((ra_rows >= 0).sum())
-    decode = wl.dtype == "bf16" and T <= 128
     gemm_name = B.lora_gemm_kernel_name(h, T, K, N, rt.dtype_code(tdtype))
+    decode = gemm_name.startswith("decode")
     kernels = {}
     if decode:
         # first kernel streams W0 and the used A_a against X; second sums the slices, adds V B_a, stores Y
@@ -178,6 +178,10 @@ def run_projection(ctx, mods, wl, cfg_index, p, steps, warmup, cpu_seconds, opti
                              "roofline": _roof("hbm", b1, k1_us, wl.dtype)}
         kernels["reduce_expand"] = {"name": "decode_reduce", "us": round(k2_us, 3), "algorithmic_bytes": b2,
                                     "roofline": _roof("hbm", b2, k2_us, wl.dtype)}
+        if ex_us > 0:  # much adapter work: V by a launch of its own (counted with the first kernel), the term by the expand kernel
+            be = es * (r_used * N + v_elems)
+            kernels["expand"] = {"name": "expand", "us": round(ex_us, 3), "algorithmic_bytes": be, "algorithmic_flops": 2 * N * v_elems,
+                                 "roofline": _roof("hbm", be, ex_us, wl.dtype)}
         dom = "stream"
     else:
         bs = es * (r_used * K + rows_ad * K) + es * v_elems

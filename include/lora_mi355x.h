@@ -233,11 +233,13 @@ int lora_plan_status(lora_ctx *ctx, const lora_plan_t *plan, lora_stream_t strea
 size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_max, int32_t dtype);
 
 /* The workspace size that lets every batch take its fastest path: the size
- * above plus, for batches of more than 128 rows, room for the adapter term
- * in fp32 ([T, N]).  Batches of many small segments then compute that term
- * in a weight-streaming kernel of its own and the GEMM adds it before its
- * single rounding of Y; with a smaller workspace the term is computed inside
- * the GEMM (same result within fp32 summation order).  For batches of 129 to
+ * above plus room for the adapter term in fp32 ([T, N]; bf16 batches of any
+ * size, fp32 ones of more than 128 rows).  Batches of many small segments,
+ * and decode-sized batches with much adapter work, then compute that term
+ * in a weight-streaming kernel of its own and the GEMM (or the decode path's
+ * reduction) adds it before the single rounding of Y; with a smaller
+ * workspace the term is computed inside the GEMM / the reduction (same
+ * result within the rounding of the intermediate V and fp32 summation order).  For batches of 129 to
  * 1024 rows whose output tiles would leave most of the chip idle it also has
  * room for the fp32 partial outputs of a GEMM split along K (2 to 8 copies
  * of [T, N]; a second launch sums them in a fixed order, adds the adapter

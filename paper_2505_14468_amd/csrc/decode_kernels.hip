@@ -230,6 +230,9 @@ __global__ __launch_bounds__(TBLK * 64) void decode_reduce_kernel(DecodeArgs p0)
     const int status = p.plan.scalars[kScStatus];
     const int a0 = has ? p.plan.row_adapter[t] : -1;
     const int rx0 = has ? p.plan.row_ext[t] : 0;
+    const bool hasd = tv && p.D != nullptr;
+    const int a0d = hasd ? p.plan.row_adapter[t] : -1;
+    const int rx0d = hasd ? p.plan.row_ext[t] : 0;
     const bool gl = p.B != nullptr && lane < p.n_adapters;  // entry `lane` of the two tables, in the same round trip
     const void *b_guess = gl ? p.B[lane] : nullptr;
     const float s_guess = gl ? p.scale[lane] : 0.f;
@@ -338,6 +341,13 @@ __global__ __launch_bounds__(TBLK * 64) void decode_reduce_kernel(DecodeArgs p0)
 
     LORA_TS(p.trace, 2);  // base partial sums added
     if (!tv) return;
+    if (p.D != nullptr && a0d >= 0 && row_ext_rank(rx0d) > 0) {  // the adapter term, computed by the expand kernel
+        const float4 d = *reinterpret_cast<const float4 *>(p.D + (int64_t)t * p.ldd + min(n, (int)p.ldd - 4));
+        acc[0] += d.x;
+        acc[1] += d.y;
+        acc[2] += d.z;
+        acc[3] += d.w;
+    }
     E *yrow = static_cast<E *>(p.Y) + (int64_t)t * p.ldy;
     if (n + 3 < p.N) {
         store4(yrow + n, acc[0], acc[1], acc[2], acc[3]);
@@ -347,6 +357,47 @@ __global__ __launch_bounds__(TBLK * 64) void decode_reduce_kernel(DecodeArgs p0)
             if (n + e < p.N) store1(yrow + n + e, acc[e]);
     }
     LORA_TS(p.trace, 3);
+}
+
+// V[t, j .. j + 3] = scale_a * sum over the K slices (in order) of the extension rows' partial tiles, rounded to E: one
+// thread per row and quad of ranks.  For batches with much adapter work, whose term the expand kernel then computes from
+// V segment by segment instead of every workgroup of the reduction gathering V B_a row by row.
+template <int TBLK>
+__global__ __launch_bounds__(256) void decode_v_kernel(DecodeArgs p) {
+    typedef __bf16 E;
+    if (p.plan.scalars[kScStatus] != 0) return;
+    const int quads = p.r_max >> 2;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)p.T * quads) return;
+    const int t = (int)(idx / quads), j = (int)(idx % quads) * 4;
+    const int a = p.plan.row_adapter[t];
+    const int rx = p.plan.row_ext[t];
+    if (a < 0 || j >= row_ext_rank(rx)) return;
+    const float sc = p.scale[a];
+    const int e = row_ext_offset(rx) + j;
+    const float4 *src = reinterpret_cast<const float4 *>(p.P) + ((int64_t)(e >> 4) * p.ks * TBLK + (t >> 4)) * 64 + ((e & 15) >> 2) * 16 + (t & 15);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < p.ks; s0 += 8) {
+        float4 g[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) g[s] = src[(int64_t)min(s0 + s, p.ks - 1) * TBLK * 64];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const float m = s0 + s < p.ks ? 1.f : 0.f;
+            v.x += m * g[s].x;
+            v.y += m * g[s].y;
+            v.z += m * g[s].z;
+            v.w += m * g[s].w;
+        }
+    }
+    store4(static_cast<E *>(p.V) + (int64_t)t * p.r_max + j, v.x * sc, v.y * sc, v.z * sc, v.w * sc);
+}
+
+template <int TBLK>
+hipError_t launch_v_t(const DecodeArgs &a, hipStream_t stream, const KernelTimer *timer) {
+    const long threads = (long)a.T * (a.r_max >> 2);
+    if (threads <= 0) return hipSuccess;
+    return launch_kernel(decode_v_kernel<TBLK>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream, timer, a);
 }
 
 template <int TBLK, int MAXW>
@@ -479,6 +530,24 @@ hipError_t launch_decode_reduce(const DecodeArgs &a, int tblk, hipStream_t strea
             return launch_reduce_t<6>(a, stream, timer);
         case 8:
             return launch_reduce_t<8>(a, stream, timer);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_decode_v(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer) {
+    if (!decode_args_ok(a, tblk) || a.n_sets != 0 || a.V == nullptr || a.scale == nullptr || (a.r_max & 7) != 0) return hipErrorInvalidValue;
+    switch (tblk) {
+        case 1:
+            return launch_v_t<1>(a, stream, timer);
+        case 2:
+            return launch_v_t<2>(a, stream, timer);
+        case 4:
+            return launch_v_t<4>(a, stream, timer);
+        case 6:
+            return launch_v_t<6>(a, stream, timer);
+        case 8:
+            return launch_v_t<8>(a, stream, timer);
         default:
             return hipErrorInvalidValue;
     }

@@ -253,12 +253,19 @@ struct DecodeArgs {
     long long *trace = nullptr;  // phase stamps (trace builds only)
     int32_t n_sets = 0;    // > 0: the projections of the launch (W .. P, N, nbw, n_adapters above are then unused)
     DecodeSet set[kMaxGemmSets];
+    // Adapter term through the expand kernel (batches with much adapter work; one projection): launch_decode_v reduces
+    // the extension rows' partial tiles to V ([T, r_max] of E, original row order, scaled), the expand kernel turns V
+    // into the fp32 term D, and the reduction adds D instead of computing V B_a itself (B null).
+    void *V = nullptr;
+    const float *D = nullptr;
+    int64_t ldd = 0;
 };
 constexpr int kDecodeMaxRows = 128;
 constexpr int kDecodeMinWaves = 8, kDecodeMaxWaves = 12;
 hipError_t init_decode_kernels();
 hipError_t launch_decode_stream(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
 hipError_t launch_decode_reduce(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
+hipError_t launch_decode_v(const DecodeArgs &a, int tblk, hipStream_t stream, const KernelTimer *timer);
 
 // Dynamic-LDS grants of every kernel instantiation, for the current device (context creation).
 hipError_t init_gemm_tile_kernels();

@@ -428,7 +428,8 @@ WorkspaceLayout workspace_layout(int64_t T, int32_t K, int32_t N, int32_t r_max,
     w.total = off < 256 ? 256 : off;
     w.ldd = align_up((size_t)N, 8);  // (the GEMM's epilogue reads whole 8-column pieces of a row)
     w.d_off = w.total;
-    w.d_bytes = T > kDecodeMaxRows ? (size_t)T * w.ldd * sizeof(float) : 0;
+    // (also for decode-sized bf16 batches: the decode path hands batches with much adapter work to the expand kernel)
+    w.d_bytes = (T > kDecodeMaxRows || (dtype == LORA_DTYPE_BF16 && T > 0)) ? (size_t)T * w.ldd * sizeof(float) : 0;
     w.sk_off = align_up(w.d_off + w.d_bytes, 256);
     const SplitK sk = choose_split_k(T, K, N, dtype);
     w.sk_bytes = sk.s > 1 ? (size_t)sk.s * (size_t)T * w.ldd * sizeof(float) : 0;
@@ -496,6 +497,18 @@ PlanView view_of(const lora_plan_t *plan) {
 
 bool has_adapters(const lora_plan_t *plan, const lora_linear_desc *d) {
     return d->tbl != nullptr && plan->n_adapters > 0 && plan->r_max > 0;
+}
+
+// Decode path, one projection: when the reduction's own expand -- every row gathers its adapter's B_a for the
+// workgroup's 16 columns, and every workgroup re-reduces V -- would move more than ~24 MB through 16-byte gathers
+// (T x r_max x N x 2 bytes: 8 MB at 64 rows of rank 16 and 4096 columns), V is reduced once by a launch of its own
+// and the expand kernel streams each used B_a once, segment by segment.  Measured per layer, 64 rows on 64 adapters
+// of rank 128: 4096 -> 4096 95 -> 59 us, 5120 -> 13824 306 -> 130 us.  Needs the workspace of the preferred size.
+bool decode_adapters_heavy(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d) {
+    if (!has_adapters(plan, d)) return false;
+    if (ctx->opt_expand_split == 0) return false;
+    if (ctx->opt_expand_split == 1) return true;
+    return 2.0e-6 * (double)plan->T * (double)plan->r_max * (double)d->N > 24.0;
 }
 
 // The two launches of the decode path share one argument block.  n > 1: several projections of the same X, their
@@ -717,11 +730,38 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
     GemmChoice c = choose_gemm(ctx, plan->T, d->K, d->N, d->dtype);
     KernelTimer timer, etimer;
     const bool timed = next_timer(ctx, kProfGemm, &timer);
+    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     if (c.variant == kGemmDecode) {  // decode-sized: the second launch sums the slices, adds V B_a, stores Y
-        LORA_HIP(launch_decode_reduce(decode_args(ctx, plan, &d, 1, c), c.tblk, stream, timed ? &timer : nullptr));
+        DecodeArgs a = decode_args(ctx, plan, &d, 1, c);
+        if (d->workspace_bytes >= w.total_preferred && w.d_bytes > 0 && decode_adapters_heavy(ctx, plan, d)) {
+            // much adapter work: V once, the expand kernel for the term, the reduction only adds it
+            unsigned char *ws = static_cast<unsigned char *>(d->workspace);
+            a.V = ws + w.v_off;
+            KernelTimer vt;
+            const bool vtimed = timed && next_timer(ctx, kProfShrink, &vt);
+            LORA_HIP(launch_decode_v(a, c.tblk, stream, vtimed ? &vt : nullptr));
+            ExpandArgs e;
+            e.plan = a.plan;
+            e.V = a.V;
+            e.B = d->tbl->B;
+            e.D = reinterpret_cast<float *>(ws + w.d_off);
+            e.ldd = (int64_t)w.ldd;
+            e.r_max = plan->r_max;
+            e.N = d->N;
+            const int64_t seg_bound = std::min<int64_t>(std::min<int64_t>(plan->n_adapters, plan->n_req), plan->T);
+            e.max_units = (int32_t)(plan->T / plan->unit_rows + seg_bound);
+            e.unit_rows = plan->unit_rows;
+            e.col_groups = 0;
+            e.skip_long = 0;
+            const bool etimed = timed && next_timer(ctx, kProfExpand, &etimer);
+            LORA_HIP(launch_expand(e, d->dtype, stream, etimed ? &etimer : nullptr));
+            a.B = nullptr;
+            a.D = e.D;
+            a.ldd = e.ldd;
+        }
+        LORA_HIP(launch_decode_reduce(a, c.tblk, stream, timed ? &timer : nullptr));
         return LORA_OK;
     }
-    const WorkspaceLayout w = workspace_layout(plan->T, d->K, d->N, plan->r_max, d->dtype);
     SplitK sk = choose_split_k(plan->T, d->K, d->N, d->dtype);
     if (ctx->opt_gemm_split_k == 0 || (ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != kGemmTile128x128) ||
         d->workspace_bytes < w.total_preferred || (has_adapters(plan, d) && w.d_bytes == 0))
