@@ -838,7 +838,15 @@ int multi_kind(const lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_d
     int32_t ns[kMaxGemmSets];
     for (int i = 0; i < n; ++i) ns[i] = descs[i]->N;
     *c = choose_gemm(ctx, plan->T, descs[0]->K, descs[0]->N, descs[0]->dtype);
-    if (c->variant == kGemmDecode) return 2;
+    if (c->variant == kGemmDecode) {
+        // (much adapter work: each projection through its own launches and the expand kernel, see decode_adapters_heavy)
+        for (int i = 0; i < n; ++i) {
+            const WorkspaceLayout w = workspace_layout(plan->T, descs[i]->K, descs[i]->N, plan->r_max, descs[i]->dtype);
+            if (descs[i]->workspace_bytes >= w.total_preferred && decode_adapters_heavy(ctx, plan, descs[i])) return 0;
+            if (choose_gemm(ctx, plan->T, descs[i]->K, descs[i]->N, descs[i]->dtype).variant != kGemmDecode) return 0;
+        }
+        return 2;
+    }
     *c = choose_gemm_sets(ctx, plan->T, descs[0]->K, ns, n, descs[0]->dtype);
     if (c->variant == kGemmDecode) return 0;
     return 1;

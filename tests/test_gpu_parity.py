@@ -279,15 +279,18 @@ def test_decode_sized_multi_projections(T, n_proj):
     X = up[0][0]
     pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks, wl.r_max)
     bare = 1  # this projection goes without its adapter table
-    outs = rt.linear_multi(c, pl, X, [(u[1], None if q == bare else u[2]) for q, u in enumerate(up)])
-    torch.cuda.synchronize()
-    for q in range(n_proj):
-        got = rt.bits_from_tensor(outs[q])
-        single = rt.bits_from_tensor(rt.linear(c, pl, X, up[q][1], None if q == bare else up[q][2]))
+    for mode in (0, -1):  # 0: the reduction's own expand whatever the adapter work (the fused launches at every size)
+        c.set_option("expand_split", mode)
+        outs = rt.linear_multi(c, pl, X, [(u[1], None if q == bare else u[2]) for q, u in enumerate(up)])
         torch.cuda.synchronize()
-        assert np.array_equal(got, single), f"projection {q}"
-        if q != bare:
-            e = check_against_oracle(wl, to_f64(got), p=q)
+        for q in range(n_proj):
+            got = rt.bits_from_tensor(outs[q])
+            single = rt.bits_from_tensor(rt.linear(c, pl, X, up[q][1], None if q == bare else up[q][2]))
+            torch.cuda.synchronize()
+            assert np.array_equal(got, single), f"projection {q}"
+            if q != bare:
+                e = check_against_oracle(wl, to_f64(got), p=q)
+    reset_options()
     assert pl.status(c)[0] == 0
     print(f"{wl.name}: T={T} n_proj={n_proj} err/rms {e:.2e}", flush=True)
 
