@@ -426,6 +426,20 @@ def run_batch_sweep(ctx, mods, options):
     return {"rows": rows, "batching_model_fit": fit}
 
 
+def run_adapter_heavy_decode(ctx, mods, options):
+    """Beside the benchmark's configurations: configuration 4's layer (5120 -> 13824, adapters of rank 128) on a
+    decode-sized batch -- 64 one-token requests, each on an adapter of its own (the many-functions regime of the paper
+    at decode time).  HBM-bound: the figure of merit is whole_call.frac_of_hbm_peak."""
+    from workloads import make_custom
+    np = mods[0]
+    T = 64
+    wl = make_custom(seed=4242, dtype="bf16", K=5120, N=13824, ranks=[128] * T, scales=[0.5] * T, req_adapter=np.arange(T),
+                     req_ntok=np.ones(T, np.int64), name="adapter_heavy_decode_64x_rank128")
+    r = run_projection(ctx, mods, wl, 4, 0, 60, 15, 2.0, options)
+    return {k: r[k] for k in ("config", "ms_per_step", "ms_per_layer", "kernel_us", "whole_call", "adapter_path", "parity_max_err_over_rms",
+                              "cpu_baseline")}
+
+
 def run_schedulers(np):
     """Decision latency of the two host-side schedulers at the scale of the paper's deployment (hundreds of functions
     on a GPU; configuration 4's pool of 512 adapters): microseconds per call, single host thread."""
@@ -563,6 +577,7 @@ def main():
         out[k] = head[k]
     out["per_config"] = per_config
     out["batch_size_sweep_config1_shape"] = run_batch_sweep(ctx, mods, options)
+    out["adapter_heavy_decode"] = run_adapter_heavy_decode(ctx, mods, options)
     out["schedulers"] = run_schedulers(np)
     out["targets"] = {"prefill (configs 2, 3)": ">= 0.60 of bf16 MFMA peak", "decode / adapter-heavy (configs 1, 4)": ">= 0.70 of HBM peak (whole_call.frac_of_hbm_peak)"}
     print(json.dumps(out))
