@@ -11,6 +11,9 @@
 //   2. decode_reduce_kernel: one workgroup per 16 output columns sums the slices' partial tiles in slice order
 //      (fixed order: reproducible), gathers every row's V from the partial tiles of its adapter's rank block,
 //      scales it by s_a, adds V B_a in fp32 (V is never rounded here) and stores Y once.
+//   With much adapter work (many high-rank adapters in the batch) two launches go in between: decode_v_kernel
+//   reduces V once (rounded to bf16 like the shrink kernel's V), the expand kernel turns it into the fp32 adapter
+//   term segment by segment, and decode_reduce_kernel only adds that term.
 //
 // Same contraction as the tiled path:  Y[t, n] = sum_k X[t, k] W0[n, k] + s_a sum_j (sum_k X[t, k] A_a[j, k]) B_a[n, j].
 //
