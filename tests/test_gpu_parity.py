@@ -215,6 +215,38 @@ def test_linear_multi_projections_of_the_same_activations(dtype):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14, 15, 16])
+def test_random_shapes_ranks_and_batch_mixes(seed):
+    """Ten random cases per seed over dtype, K, N, batch size (decode-sized to a few thousand rows), adapter pool, ranks
+    and segment lengths, each on whatever launch path the library picks for it (printed), host- and device-built
+    plans alternating: every output element against the oracle at the stated tolerance."""
+    from gpu_common import ctx, gpu_linear, check_against_oracle, reset_options, B
+    reset_options()
+    rng = np.random.default_rng(seed)
+    for case in range(10):
+        dtype = "bf16" if rng.random() < 0.8 else "f32"
+        K = int(rng.choice([264, 520, 1032, 2056, 4104])) if dtype == "bf16" else int(rng.choice([264, 520, 1032]))
+        N = int(rng.choice([24, 72, 264, 520, 1100, 2056]))
+        T = int(rng.choice([rng.integers(1, 33), rng.integers(33, 129), rng.integers(129, 700), rng.integers(700, 2200)]))
+        n_ad = int(rng.choice([1, 2, 5, 17, 70]))
+        ranks = [int(min(rng.choice([8, 16, 24, 40, 64, 128]), (K // 64) * 8)) for _ in range(n_ad)]
+        scales = [float(rng.choice([0.25, 0.5, 1.0])) for _ in range(n_ad)]
+        lens, left = [], T
+        while left > 0:
+            n = int(min(left, rng.choice([1, 1, 2, 5, 17, 64, 200, 500])))
+            lens.append(n)
+            left -= n
+        if rng.random() < 0.3:
+            lens.insert(int(rng.integers(0, len(lens) + 1)), 0)  # a request without tokens
+        ids = rng.integers(-1, n_ad, size=len(lens))
+        wl = make_custom(seed=100 * seed + case, dtype=dtype, K=K, N=N, ranks=ranks, scales=scales, req_adapter=ids,
+                         req_ntok=np.asarray(lens), name=f"random_{seed}_{case}")
+        name = B.lora_gemm_kernel_name(ctx().handle, wl.T, K, N, 1 if dtype == "bf16" else 0)
+        print(f"{wl.name}: {dtype} T={wl.T} K={K} N={N} adapters={n_ad} r_max={max(ranks)} requests={len(lens)} {name}", end=" ", flush=True)
+        e = check_against_oracle(wl, gpu_linear(wl, device_plan=bool(case & 1)))
+        print(f"err/rms {e:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("dtype,K,N,T", [("bf16", 2312, 520, 129), ("bf16", 2312, 520, 384), ("bf16", 8200, 264, 200),
                                           ("bf16", 4096, 1100, 300), ("f32", 1032, 264, 150), ("f32", 2056, 520, 140)])
 def test_mid_sized_batches_split_along_k(dtype, K, N, T):
