@@ -249,10 +249,11 @@ size_t lora_linear_workspace_bytes_preferred(int64_t T, int32_t K, int32_t N, in
 /* a2, shrink: V[row, :r_a] = s_a * X[row, :] A_a for every row with an
  * adapter, written to the workspace (bf16 for the bf16 path, fp32 for fp32).
  * It is the first of the layer's two stages whatever the batch: for
- * decode-sized bf16 batches (T <= 128) the launch streams W0 and the used A_a
- * against X once, slice by slice of the contraction axis, and leaves fp32
- * partial sums of both X W0 and X A_a in the workspace (V is then never
- * rounded), so call it even when desc->tbl is NULL.
+ * decode-sized bf16 batches (T <= 128, unless the output is so wide that the
+ * tiled path is cheaper) the launch streams W0 and the used A_a against X
+ * once, slice by slice of the contraction axis, and leaves fp32 partial sums
+ * of both X W0 and X A_a in the workspace, so call it even when desc->tbl is
+ * NULL.
  * Asynchronous on `stream`.  No-op when T == 0. */
 int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
@@ -260,15 +261,20 @@ int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
  * store of Y: Y[row, :] = X[row, :] W0 + V[row, :r_a] B_a, V (and the copy of
  * X) taken from the workspace as lora_shrink() left them for the same plan,
  * desc->X and K (decode-sized bf16 batches: sums the partial sums lora_shrink()
- * left, adds V B_a in fp32 and stores Y).  Otherwise two forms, same result up
+ * left, adds V B_a in fp32 -- V never rounded -- and stores Y; with much
+ * adapter work and a workspace of the preferred size V is reduced and rounded
+ * to bf16 by a launch of its own and the term comes from the weight-streaming
+ * kernel below).  Otherwise two forms, same result up
  * to fp32 summation order: the expand
  * as extra K-steps of the GEMM's own MFMA loop (always, with a workspace of the
  * minimal size; and for segments of 64 rows and more up to rank 64), or -- with
  * a workspace of the preferred size and many small segments -- a
  * weight-streaming kernel of its own that leaves the term in fp32 in the
  * workspace ([T, N], written and read once), which the GEMM's epilogue adds to
- * its fp32 accumulators.  Either way every element of Y is rounded and written
- * exactly once. */
+ * its fp32 accumulators.  Batches of a few hundred rows whose tiles would leave
+ * most of the chip idle split the GEMM along K as well (see
+ * lora_linear_workspace_bytes_preferred).  Either way every element of Y is
+ * rounded and written exactly once. */
 int lora_gemm_expand(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *desc, lora_stream_t stream);
 
 /* The whole layer: lora_shrink() then lora_gemm_expand() on `stream`.  Returns
@@ -297,7 +303,9 @@ int lora_linear_static(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear
  * lora_linear_workspace_bytes[_preferred]).  Computes what n calls of
  * lora_linear compute (same formula per projection; fp32 summation order may
  * differ, as between tile shapes); every kernel runs as one launch whose grid
- * holds the work of all projections.
+ * holds the work of all projections (decode-sized batches: unless one of the
+ * projections has much adapter work or takes the tiled path -- then projection
+ * by projection).
  * Errors: those of lora_linear for any desc; INVALID_ARG also for n out of
  * range, descs that differ in X / ldx / K / dtype, or two descs with the same Y
  * or workspace. */
