@@ -312,14 +312,16 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     const int tid = threadIdx.x;
     LORA_TS(p0.trace, 0);
 
-    // several projections of the same X: the single-projection grid with the projections innermost -- the
-    // workgroups that read the same rows of X (one unit, one rank block, every projection) are neighbours in the
-    // grid and run together, so a row of X comes from HBM once and from L2 for the others
+    // several projections of the same X: the single-projection grid with the projections innermost, eight
+    // workgroups at a time -- workgroup ids go round-robin to the eight XCDs, so the workgroups that read the same
+    // rows of X (one unit, one rank block, every projection) get ids that differ by 8: the same XCD, one after the
+    // other, and a row of X comes from memory once and from that XCD's L2 for the others
     ShrinkArgs p = p0;
     int bid = blockIdx.x;
     if (p0.n_sets > 0) {
-        const int si = bid % p0.n_sets;
-        bid /= p0.n_sets;
+        const int q = bid >> 3;
+        const int si = q % p0.n_sets;
+        bid = (q / p0.n_sets) * 8 + (bid & 7);
         p.A = p0.set[si].A;
         p.scale = p0.set[si].scale;
         p.V = p0.set[si].V;
