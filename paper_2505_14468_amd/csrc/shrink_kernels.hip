@@ -338,8 +338,10 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     // fastest: the rank blocks past a small adapter's rank have nothing to do and exit at once, and with them
     // interleaved (period = rank_groups, a divisor of the eight XCDs the workgroups go to in turn) every unit with
     // work sits on the same XCDs and in the grid's second round.
+    // (full ranks: the rank blocks of a unit get ids 8 apart -- the same XCD, whose L2 then serves the unit's rows of X
+    // to all of them)
     const int mu8 = (p.max_units + 7) / 8 * 8;
-    const int unit_a = bid % mu8, unit_b = bid / p.rank_groups;
+    const int unit_a = bid % mu8, unit_b = ((bid >> 3) / p.rank_groups) * 8 + (bid & 7);
     const int4 rec_a = reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit_a];
     const int4 rec_b = p.rank_groups > 1 ? reinterpret_cast<const int4 *>(p.plan.unit_rec)[unit_b] : rec_a;
     // Guessed ahead, in the same round trip as the record: lane i reads entry i of the adapter tables and of the
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(kShWaves * 64) void shrink_kernel(ShrinkArgs p0) {
     const int n_seg = p.plan.scalars[kScNSeg], ext_total = p.plan.scalars[kScExtTotal];
     const bool full_ranks = p.rank_groups > 1 && (long long)ext_total * 4 >= 3ll * p.r_max * n_seg;
     const int unit = full_ranks ? unit_b : unit_a;
-    const int jg = full_ranks ? bid % p.rank_groups : bid / mu8;
+    const int jg = full_ranks ? (bid >> 3) % p.rank_groups : bid / mu8;
     const int4 rec = full_ranks ? rec_b : rec_a;
     if (status != 0 || unit >= n_units) return;  // (n_units <= max_units: the grid's padding to eight units ends here too)
     LORA_TS(p.trace, 1);  // work-list record read
