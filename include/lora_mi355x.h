@@ -240,7 +240,8 @@ size_t lora_linear_workspace_bytes(int64_t T, int32_t K, int32_t N, int32_t r_ma
  * reduction) adds it before the single rounding of Y; with a smaller
  * workspace the term is computed inside the GEMM / the reduction (same
  * result within the rounding of the intermediate V and fp32 summation order).  For batches of 129 to
- * 1024 rows whose output tiles would leave most of the chip idle it also has
+ * 1024 rows whose output tiles would leave most of the chip idle (and larger
+ * ones with K >= 10240 into few columns) it also has
  * room for the fp32 partial outputs of a GEMM split along K (2 to 8 copies
  * of [T, N]; a second launch sums them in a fixed order, adds the adapter
  * term and rounds Y once).  Returns 0 for invalid arguments. */
@@ -271,7 +272,7 @@ int lora_shrink(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *
  * a workspace of the preferred size and many small segments -- a
  * weight-streaming kernel of its own that leaves the term in fp32 in the
  * workspace ([T, N], written and read once), which the GEMM's epilogue adds to
- * its fp32 accumulators.  Batches of a few hundred rows whose tiles would leave
+ * its fp32 accumulators.  Batches whose tiles would leave
  * most of the chip idle split the GEMM along K as well (see
  * lora_linear_workspace_bytes_preferred).  Either way every element of Y is
  * rounded and written exactly once. */

@@ -604,7 +604,7 @@ hipError_t init_tiles() {
     if (e == hipSuccess) e = init_tile<E, 128, 128, 2, 2, true>();
     if (e == hipSuccess) e = init_tile<E, 256, 128, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 256, 4, 2>();
-    if (e == hipSuccess) e = init_tile<E, 256, 256, 2, 2>();
+    if (e == hipSuccess) e = init_tile<E, 256, 256, 2, 2, true>();
     if (e == hipSuccess) e = init_tile<E, 128, 192, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 192, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 224, 4, 1>();
@@ -623,7 +623,7 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
         case kGemmTile256x256:
             return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
         case kGemmTile256x256w4:
-            return launch_tile<E, 256, 256, 2, 2>(a, stream, timer);
+            return launch_tile<E, 256, 256, 2, 2, true>(a, stream, timer);
         case kGemmTile128x192:
             return launch_tile<E, 128, 192, 2, 2>(a, stream, timer);
         case kGemmTile256x192:

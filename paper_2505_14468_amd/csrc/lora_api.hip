@@ -392,27 +392,40 @@ struct WorkspaceLayout {
     size_t sk_off, sk_bytes;                      // partial outputs of a GEMM split along K (optional, inside total_preferred)
 };
 
-// Mid-sized batches whose 128x128 tiles would leave most CUs idle: the tiled GEMM is split along K as well, its
-// fp32 partial outputs summed by a second launch.  Depends on the shape alone (the workspace is sized from it).
+// Batches whose tiles alone would leave most CUs idle: the tiled GEMM is split along K as well, its fp32 partial
+// outputs summed by a second launch.  Depends on the shape alone (the workspace is sized from it).
 struct SplitK {
-    int s, k_chunk;
+    int s, k_chunk, variant;
 };
 SplitK choose_split_k(int64_t T, int32_t K, int32_t N, int32_t dtype) {
-    SplitK r{1, 0};
-    if (T <= kDecodeMaxRows || T > 1024) return r;  // (up to kDecodeMaxRows rows: the decode path, or a batch too small to matter)
-    const int64_t tiles = ((T + 127) / 128) * (((int64_t)N + 127) / 128);
-    // Worth it while the tiles alone leave most of the chip idle (measured at 4096 -> 4096: 129 rows 46.7 -> 37.8 us per
-    // layer, 256 rows 48.5 -> 42.7, 512 rows no gain; 11008 -> 4096, 512 rows: 126 -> 108 us; at 4096 -> 11008, 172
-    // tiles and more, the partial outputs cost more than the idle CUs: 72 -> 84 us).
-    if (tiles > 128 || (tiles > 96 && K < 8192)) return r;
+    SplitK r{1, 0, kGemmTile128x128};
+    if (T <= kDecodeMaxRows) return r;  // (the decode path, or a batch too small to matter)
     const int stage = dtype == LORA_DTYPE_BF16 ? 64 : 32;
-    int64_t s = (384 + tiles - 1) / tiles;  // about one and a half workgroups per CU (two of them fit one)
+    int64_t s = 0;
+    if (T <= 1024) {
+        // Mid-sized batches on 128x128 tiles.  Worth it while the tiles alone leave most of the chip idle (measured at
+        // 4096 -> 4096: 129 rows 46.7 -> 37.8 us per layer, 256 rows 48.5 -> 42.7, 512 rows no gain; 11008 -> 4096, 512
+        // rows: 126 -> 108 us; at 4096 -> 11008, 172 tiles and more, the partial outputs cost more than the idle CUs:
+        // 72 -> 84 us).
+        const int64_t tiles = ((T + 127) / 128) * (((int64_t)N + 127) / 128);
+        if (tiles > 128 || (tiles > 96 && K < 8192)) return r;
+        s = (384 + tiles - 1) / tiles;  // about one and a half workgroups per CU (two of them fit one)
+    } else {
+        // A long contraction axis into few columns (a down projection at a thousand-odd rows): 256x256 tiles, as many
+        // stretches of K as make one round of workgroups.  Measured per layer, 11008 -> 4096: 1100 rows 169 -> 154 us,
+        // 1216 rows 171 -> 157; with two stretches (1536 and 2048 rows: 192 -> 190, 198 -> 218) and at 8192 -> 4096 (three
+        // stretches, 1216 rows: 130 -> 130) the partial outputs cost what the idle CUs did, or more.
+        const int64_t tiles = ((T + 255) / 256) * (((int64_t)N + 255) / 256);
+        if (tiles > 85 || K < 10240) return r;
+        s = 256 / tiles;  // (the part's 256 CUs: the workspace size must not depend on the context)
+        r.variant = kGemmTile256x256w4;
+    }
     s = std::min<int64_t>(s, 8);
     s = std::min<int64_t>(s, K / (16 * stage));  // at least 16 stages per split
-    if (s < 2) return r;
+    if (s < 2) return SplitK{1, 0, kGemmTile128x128};
     r.k_chunk = (int)(((K + s - 1) / s + stage - 1) / stage * stage);
     r.s = (K + r.k_chunk - 1) / r.k_chunk;
-    if (r.s < 2) r = SplitK{1, 0};
+    if (r.s < 2) r = SplitK{1, 0, kGemmTile128x128};
     return r;
 }
 
@@ -763,10 +776,10 @@ int do_gemm(lora_ctx *ctx, const lora_plan_t *plan, const lora_linear_desc *d, h
         return LORA_OK;
     }
     SplitK sk = choose_split_k(plan->T, d->K, d->N, d->dtype);
-    if (ctx->opt_gemm_split_k == 0 || (ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != kGemmTile128x128) ||
+    if (ctx->opt_gemm_split_k == 0 || (ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != sk.variant) ||
         d->workspace_bytes < w.total_preferred || (has_adapters(plan, d) && w.d_bytes == 0))
-        sk = SplitK{1, 0};
-    if (sk.s > 1) c.variant = kGemmTile128x128;
+        sk = SplitK{1, 0, kGemmTile128x128};
+    if (sk.s > 1) c.variant = sk.variant;
     GemmSet g;
     bool split = false;
     const int rc = prepare_set(ctx, plan, d, c.variant, stream, timed ? &etimer : nullptr, &g, &split, nullptr, sk.s > 1);
@@ -1244,8 +1257,8 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
     // (with a workspace of the preferred size and an adapter table, or none)
     const SplitK sk = choose_split_k(T, K, N, dtype);
     if (c.variant != kGemmDecode && sk.s > 1 && !(ctx && ctx->opt_gemm_split_k == 0) &&
-        !(ctx && ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != kGemmTile128x128)) {
-        snprintf(buf, sizeof buf, "tile_128x128_splitk%d", sk.s);
+        !(ctx && ctx->opt_gemm_variant >= 0 && ctx->opt_gemm_variant != sk.variant)) {
+        snprintf(buf, sizeof buf, sk.variant == kGemmTile128x128 ? "tile_128x128_splitk%d" : "tile_256x256_splitk%d", sk.s);
         return buf;
     }
     switch (c.variant) {

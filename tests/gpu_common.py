@@ -9,6 +9,16 @@ from workloads import to_f64
 
 TOL = {"bf16": 2e-2, "f32": 1e-5}  # max |Y_gpu - Y_oracle| <= TOL * RMS(Y_oracle)
 
+
+def tol(dtype, K):
+    """Tolerance as a fraction of the output's RMS.  bf16: 2e-2.  fp32: 1e-5 up to K = 1111; beyond, the rounding of
+    K sequential fp32 additions (each within 2^-24 of the running sum) is what remains: an error of RMS
+    ~0.3 * sqrt(K) * 2^-24 * RMS(Y), its maximum over 10^5..10^6 outputs ~11 times that (rows of X differ in norm)
+    -- 3e-7 * sqrt(K), with margin 1.5 over what the unsplit kernels measure at K = 10264 (2.0e-5)."""
+    if dtype == "bf16":
+        return TOL["bf16"]
+    return max(TOL["f32"], 3e-7 * float(K) ** 0.5)
+
 _ctx = None
 
 
@@ -55,8 +65,9 @@ def check_against_oracle(wl, Y_gpu, p=0, rows=None):
     rms = float(np.sqrt((Y_ref ** 2).mean()))
     err = float(np.abs(got - Y_ref).max())
     assert np.isfinite(got).all()
-    assert err <= TOL[wl.dtype] * rms, f"max abs err {err:.3e} vs {TOL[wl.dtype]} * rms {rms:.3e} ({wl.name})"
+    t = tol(wl.dtype, wl.projections[p].K)
+    assert err <= t * rms, f"max abs err {err:.3e} vs {t} * rms {rms:.3e} ({wl.name})"
     return err / rms
 
 
-__all__ = ["B", "rt", "ctx", "reset_options", "gpu_linear", "check_against_oracle", "plan_reference", "TOL"]
+__all__ = ["B", "rt", "ctx", "reset_options", "gpu_linear", "check_against_oracle", "plan_reference", "TOL", "tol"]
