@@ -157,7 +157,7 @@ int lora_ctx_create(lora_ctx **out, int device_ordinal);
 int lora_ctx_destroy(lora_ctx *ctx);
 
 /* Overrides of the built-in kernel choices, for tests and measurements:
- * "gemm_variant" (0 tile 128x128, 1 256x128, 2 256x256 on 8 waves, 3 64x64,
+ * "gemm_variant" (0 tile 128x128, 1 256x128, 3 64x64,
  * 4 the decode path (bf16, up to 128 rows), 5 256x256 on 4 waves,
  * 9 128x192, 10 256x192, 11 256x224), "decode_waves" (waves per workgroup of
  * the decode path's streaming kernel: 8..12), "decode_max_rows" (0: never

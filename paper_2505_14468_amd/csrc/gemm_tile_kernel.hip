@@ -16,9 +16,9 @@
 // Tile: BM token rows x BN output columns, BK = 8 chunks (128 bytes) of the contraction axis
 // per stage, double-buffered in LDS, global -> registers -> LDS.  The base product is a
 // hand-written software pipeline: MFMA operands are read from LDS one use ahead, the last
-// k-step of a stage is split around the stage's barrier, and on 4 waves two register sets of
+// k-step of a stage is split around the stage's barrier, and two register sets of
 // staged operands keep the loads of the stage after next in flight while the next one is
-// written to LDS, a quarter per k-step.  MFMA orientation: M = output column n (W rows),
+// written to LDS, a quarter per k-step (4 waves per workgroup, one per SIMD, for every tile shape).  MFMA orientation: M = output column n (W rows),
 // N = token row t (X rows), so that every lane ends up with 4 consecutive n of one row.
 // LDS rows are 8 chunks long and XOR-swizzled by (row >> 1) & 7 so that both the 16-byte
 // stores (8 lanes per row) and the MFMA operand reads (32 rows, one chunk column) spread
@@ -65,9 +65,9 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     constexpr int RPP = NT / 8;                        // rows covered per load pass
     static_assert(XL >= 1 && WL >= 1 && NBT >= 1 && NBN >= 1, "tile too small for the workgroup");
     static_assert(kTabCap % NT == 0 && BM <= 256, "extension table layout");
-    // On 4 waves (up to 512 registers each) the base product runs as a deeper software pipeline, with two
-    // register sets of staged operands; on 8 waves the second set does not fit beside a 256x256 tile.
-    constexpr bool DEEP = XL + WL >= 4 && WM * WN <= 4;
+    // Every tile shape runs on 4 waves (up to 512 registers each): the base product keeps two register sets of
+    // staged operands (see the loop below).
+    static_assert(XL + WL >= 4 && WM * WN == 4, "the two-set pipeline deals a stage's loads to four k-steps of one wave per SIMD");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     chunk_t *sW = reinterpret_cast<chunk_t *>(smem);                 // [2][BN*8]
@@ -311,8 +311,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     // as its two MFMAs of this one are issued, the two X operands alternate between two register
     // sets.  The last k-step of a stage is split: half of its MFMAs go out before the stage's stores
     // and barrier, the other half after the barrier, behind the first operand reads of the next
-    // stage, whose latency they cover.  Global loads for the stage after next are issued right
-    // behind the barrier and have a whole stage to arrive.
+    // stage, whose latency they cover.
     const int KT = (Kloc + 8 * CE - 1) / (8 * CE);
     const int KT_full = Kloc / (8 * CE);  // stages that lie entirely inside K
     auto read_w = [&](int buf, int kk, int nb) { return sW[buf * BN * 8 + swz(wn0 + nb * 32 + l31, 2 * kk + lh)]; };
@@ -326,53 +325,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     for (int tb = 0; tb < NBT; ++tb) xf[0][tb] = read_x(0, 0, tb);
 #pragma unroll
     for (int nb = 0; nb < NBN; ++nb) wf[nb] = read_w(0, 0, nb);
-    // (more: a next stage exists; load2: so does the one after it, partial2: which is the partial one)
-    // The waves of a SIMD take turns at the address unit: a stage's loads of all waves at once keep every
-    // wave waiting at its load instructions (the unit takes one every ~16 cycles) with its MFMAs queued up
-    // behind them.  The first half of the waves requests stage kt + 2 right behind the barrier, the second
-    // half one k-step later -- while one wave of a SIMD waits to issue loads, the other issues MFMAs.
-    const bool late = __builtin_amdgcn_readfirstlane(wave) >= (WM * WN) / 2;
-    auto stage = [&](int kt, bool more, bool load2, bool partial2, bool load1, bool partial1) {
-        const int buf = kt & 1;
-#pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-            const int cur = kk & 1;
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb) xf[cur ^ 1][tb] = read_x(buf, kk + 1, tb);
-#pragma unroll
-            for (int nb = 0; nb < NBN; ++nb) {
-#pragma unroll
-                for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[cur][tb]);
-                wf[nb] = read_w(buf, kk + 1, nb);
-            }
-            if (kk == 0 && late && load1) load_base(kt + 1, partial1);
-        }
-        // k-step 3 (operands in xf[1], wf): first half, stores of the next stage, barrier, second half
-        constexpr int H = NBN > 1 ? NBN / 2 : 1;
-#pragma unroll
-        for (int nb = 0; nb < H; ++nb)
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
-        if (more) store_stage(buf ^ 1);
-        __syncthreads();
-        if (!late && load2) load_base(kt + 2, partial2);
-        if (more) {
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb) xf[0][tb] = read_x(buf ^ 1, 0, tb);
-#pragma unroll
-            for (int nb = 0; nb < H; ++nb) wf[nb] = read_w(buf ^ 1, 0, nb);
-        }
-#pragma unroll
-        for (int nb = H; nb < NBN; ++nb) {
-#pragma unroll
-            for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
-            if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
-        }
-    };
     bool ext_loaded = false;
     // (stage 1 was requested by every wave before the loop)
     int kt = 0;
-    if constexpr (DEEP) {
+    {
         // Two register sets of staged operands: while stage kt is multiplied, the loads of stage kt + 2 go out
         // into one set and the other set, which holds stage kt + 1, is written to the LDS buffer that stage
         // kt - 1 was read from -- a quarter of each per k-step, so neither the address unit nor LDS sees a
@@ -473,11 +429,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 stage_deep(kt + 1, xr, wr, xr2, wr2, kt + 2 < KT, kt + 3 < KT, kt + 3 >= KT_full);
             }
         }
-    } else if (KT_full > 2) {
-        stage(0, true, true, false, false, false);
-        for (kt = 1; kt + 2 < KT_full; ++kt) stage(kt, true, true, false, true, false);  // the steady state
     }
-    for (; kt < KT; ++kt) stage(kt, kt + 1 < KT, kt + 2 < KT, kt + 2 >= KT_full, kt >= 1 && kt + 1 < KT, kt + 1 >= KT_full);
     __syncthreads();  // (NBN == 1: the second half above is empty and reads of the last buffer end after its barrier)
 
     // ---- extension: sum over the concatenated ranks of this tile's adapters -----------------------
@@ -603,7 +555,6 @@ hipError_t init_tiles() {
     hipError_t e = init_tile<E, 64, 64, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 128, 128, 2, 2, true>();
     if (e == hipSuccess) e = init_tile<E, 256, 128, 2, 2>();
-    if (e == hipSuccess) e = init_tile<E, 256, 256, 4, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 256, 2, 2, true>();
     if (e == hipSuccess) e = init_tile<E, 128, 192, 2, 2>();
     if (e == hipSuccess) e = init_tile<E, 256, 192, 2, 2>();
@@ -620,8 +571,6 @@ hipError_t launch_variant(const GemmArgs &a, int variant, hipStream_t stream, co
             return launch_tile<E, 128, 128, 2, 2, true>(a, stream, timer);
         case kGemmTile256x128:
             return launch_tile<E, 256, 128, 2, 2>(a, stream, timer);
-        case kGemmTile256x256:
-            return launch_tile<E, 256, 256, 4, 2>(a, stream, timer);
         case kGemmTile256x256w4:
             return launch_tile<E, 256, 256, 2, 2, true>(a, stream, timer);
         case kGemmTile128x192:

@@ -184,7 +184,7 @@ hipError_t launch_expand(const ExpandArgs &a, int dtype, hipStream_t stream, con
 enum GemmVariant {
     kGemmTile128x128 = 0,
     kGemmTile256x128 = 1,
-    kGemmTile256x256 = 2,
+    // (2: not in use)
     kGemmTile64x64 = 3,
     kGemmDecode = 4,         // not a tile shape: the decode-sized path (decode_kernels.hip)
     kGemmTile256x256w4 = 5,  // 256x256 tile on 4 waves (128x128 per wave)

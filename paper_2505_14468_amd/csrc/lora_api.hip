@@ -962,7 +962,7 @@ int lora_ctx_destroy(lora_ctx *ctx) {
 int lora_ctx_set_option(lora_ctx *ctx, const char *name, int value) {
     if (!ctx || !name) return LORA_ERR_INVALID_ARG;
     if (!strcmp(name, "gemm_variant")) {
-        if (value >= kGemmVariantCount || (value >= 6 && value <= 8)) return LORA_ERR_INVALID_ARG;
+        if (value >= kGemmVariantCount || value == 2 || (value >= 6 && value <= 8)) return LORA_ERR_INVALID_ARG;
         ctx->opt_gemm_variant = value;
     } else if (!strcmp(name, "decode_waves")) {
         if (value >= 0 && (value < kDecodeMinWaves || value > kDecodeMaxWaves)) return LORA_ERR_INVALID_ARG;
@@ -1273,9 +1273,6 @@ const char *lora_gemm_kernel_name(lora_ctx *ctx, int64_t T, int32_t K, int32_t N
             break;
         case kGemmTile256x128:
             snprintf(buf, sizeof buf, "tile_256x128");
-            break;
-        case kGemmTile256x256:
-            snprintf(buf, sizeof buf, "tile_256x256");
             break;
         case kGemmTile256x256w4:
             snprintf(buf, sizeof buf, "tile_256x256w4");
