@@ -624,6 +624,31 @@ def test_worked_example_derived_by_hand_is_exact(dtype):
     reset_options()
 
 
+def test_layer_at_the_most_requests_and_adapter_slots():
+    """65536 one- and two-token requests on 65536 adapter slots (the header's maxima): ~98 000 rows, tens of thousands
+    of shrink units, 384 row tiles.  Small integers and power-of-two scales on a short contraction axis, so that every
+    intermediate is exact (V <= 256 in bf16) and the 7 million outputs must equal the oracle's, rounded once to bf16,
+    bit for bit -- a maximum error over that many Gaussian outputs would sit at the bf16 format's own rounding of the
+    largest of them (5.8 x RMS: 1.7e-2 x RMS)."""
+    from gpu_common import gpu_linear, reset_options
+    from oracle import oracle_workload
+    from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+    reset_options()
+    rng = np.random.default_rng(12)
+    R = n_ad = 65536
+    ranks = rng.choice([8, 16], size=n_ad)
+    ids = rng.permutation(n_ad)
+    ids[rng.integers(0, R, size=300)] = -1
+    lens = rng.integers(1, 3, size=R)
+    wl = make_custom(seed=4242, dtype="bf16", K=16, N=72, ranks=ranks, scales=rng.choice([0.25, 0.5], size=n_ad),
+                     req_adapter=ids, req_ntok=lens, name="max_requests_and_slots", integer_valued=True)
+    Y = gpu_linear(wl, device_plan=True)
+    Yo = oracle_workload(wl)
+    Yo = f32_from_bf16_bits(bf16_bits_from_f32(Yo.astype(np.float32))).astype(np.float64)
+    assert Y.shape == Yo.shape and np.array_equal(Y, Yo)
+    assert np.abs(Yo).max() > 100  # (the adapter term is there)
+
+
 def test_empty_batch_is_a_noop():
     import torch
     from gpu_common import ctx, rt

@@ -119,6 +119,20 @@ def test_plan_both_fill_paths_and_many_requests(fused_rows):
     _check_plan(ids, L, ranks, False, fused_rows=fused_rows)
 
 
+@pytest.mark.parametrize("device_plan", [False, True])
+def test_plan_at_the_documented_maxima(device_plan):
+    """LORA_MAX_REQUESTS requests on LORA_MAX_ADAPTERS adapter slots, ranks from 8 to LORA_MAX_RANK, almost every
+    request its own segment."""
+    rng = np.random.default_rng(11)
+    R = n_ad = 65536
+    ranks = rng.choice([8, 16, 512], size=n_ad, p=[0.6, 0.39, 0.01])
+    ids = rng.permutation(n_ad).astype(np.int32)
+    ids[rng.integers(0, R, size=500)] = -1
+    ids[rng.integers(0, R, size=500)] = ids[7]
+    L = rng.integers(0, 3, size=R)
+    _check_plan(ids, L, ranks, device_plan)
+
+
 def test_plan_edge_cases():
     _check_plan([], [], [8, 8], False)                      # empty batch
     _check_plan([0, 1], [0, 0], [8, 8], True)               # only zero-length requests
