@@ -500,6 +500,98 @@ def test_p5_exact_integers_on_gpu():
         assert np.array_equal(Y, Yo), dtype
 
 
+def _integer_batch(seed, T, n_ad):
+    rng = np.random.default_rng(seed)
+    lens, ids = [], []
+    left = T
+    while left > 0:
+        n = int(min(left, rng.choice([1, 2, 5, 40, 70, 150])))
+        lens.append(n)
+        ids.append(int(rng.integers(-1, n_ad)))
+        left -= n
+    return np.asarray(ids), np.asarray(lens)
+
+
+@pytest.mark.parametrize("T,K,N,variant", [(150, 1032, 264, None), (300, 2056, 520, None), (1100, 10264, 264, None),
+                                           (700, 1000, 300, "tile_64x64"), (700, 1000, 300, "tile_128x128"),
+                                           (700, 1000, 300, "tile_256x128"), (700, 1000, 300, "tile_256x256w4"),
+                                           (700, 1000, 300, "tile_128x192"), (700, 1000, 300, "tile_256x192"),
+                                           (700, 1000, 300, "tile_256x224")])
+def test_fp32_integer_inputs_are_exact_on_every_tiled_path(T, K, N, variant):
+    """Small integers and power-of-two scales in fp32: every product and every partial sum, in any order, is an
+    integer multiple of 1/8 far below 2^24, so shrink, expand kernel, in-GEMM extension, every tile shape and the
+    launches split along K must reproduce the oracle bit for bit -- a dropped or doubled piece of the contraction
+    axis, of a rank axis or of a segment cannot hide inside a tolerance."""
+    from gpu_common import ctx, gpu_linear, reset_options
+    from oracle import oracle_workload
+    reset_options()
+    ranks = (8, 16, 64, 128, 24)
+    ids, lens = _integer_batch(T + K, T, len(ranks))
+    wl = make_custom(seed=900 + T, dtype="f32", K=K, N=N, ranks=ranks, scales=(0.5, 0.25, 1.0, 0.125, 2.0),
+                     req_adapter=ids, req_ntok=lens, name=f"integers_f32_{T}_{K}_{N}_{variant}", integer_valued=True)
+    Yo = oracle_workload(wl)
+    assert np.abs(Yo).max() < 2 ** 22 and np.array_equal(Yo, Yo.astype(np.float32).astype(np.float64))
+    if variant:
+        ctx().set_option("gemm_variant", VARIANTS[variant])
+    for expand_split in (-1, 0):  # the expand kernel for the short segments where the host picks it / everything in the GEMM
+        ctx().set_option("expand_split", expand_split)
+        Y = gpu_linear(wl, device_plan=bool(T & 2))
+        assert np.array_equal(Y, Yo), (variant, expand_split)
+    reset_options()
+
+
+@pytest.mark.parametrize("T", [1, 17, 64, 128])
+def test_bf16_decode_path_integer_inputs_are_exact(T):
+    """The decode path keeps V in fp32, so with small integers and power-of-two scales its result is the exact one,
+    rounded once to bf16, at any length of the contraction axis (here 9 slices, the last one partial)."""
+    from gpu_common import ctx, gpu_linear, reset_options, B
+    from oracle import oracle_workload
+    from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+    reset_options()
+    ranks = (8, 16, 64, 24)
+    rng = np.random.default_rng(T)
+    ids = rng.integers(-1, len(ranks), size=T)
+    wl = make_custom(seed=950 + T, dtype="bf16", K=4104, N=520, ranks=ranks, scales=(0.5, 0.25, 1.0, 2.0),
+                     req_adapter=ids, req_ntok=np.ones(T, np.int64), name=f"integers_decode_{T}", integer_valued=True)
+    assert B.lora_gemm_kernel_name(ctx().handle, T, 4104, 520, 1).startswith("decode")
+    Yo = oracle_workload(wl)
+    Yo = f32_from_bf16_bits(bf16_bits_from_f32(Yo.astype(np.float32))).astype(np.float64)
+    assert np.array_equal(gpu_linear(wl, device_plan=bool(T & 1)), Yo)
+
+
+@pytest.mark.parametrize("dtype,T,K", [("f32", 500, 1000), ("f32", 140, 2056), ("bf16", 50, 2056), ("bf16", 128, 1544)])
+def test_linear_multi_integer_inputs_are_exact(dtype, T, K):
+    """lora_linear_multi on small integers: three projections of one X through the fused launches (fp32: shrink,
+    expand and tiled GEMM over the projections side by side; bf16 at up to 128 rows: the decode path's two launches)
+    equal the oracle bit for bit (bf16: the exact result rounded once)."""
+    import torch
+    from workloads.configs import Projection
+    from workloads import to_f64, bf16_bits_from_f32, f32_from_bf16_bits
+    from oracle import oracle_workload
+    from gpu_common import rt, ctx, reset_options
+    reset_options()
+    c = ctx()
+    ranks = (8, 16, 64, 24)
+    if dtype == "bf16":
+        rng = np.random.default_rng(T)
+        ids, lens = rng.integers(-1, len(ranks), size=T), np.ones(T, np.int64)
+    else:
+        ids, lens = _integer_batch(T, T, len(ranks))
+    wl = make_custom(seed=970 + T, dtype=dtype, K=K, N=520, ranks=ranks, scales=(0.5, 0.25, 1.0, 2.0), req_adapter=ids,
+                     req_ntok=lens, name=f"multi_integers_{dtype}_{T}", integer_valued=True)
+    wl.projections = [Projection("a", K, 520), Projection("b", K, 264), Projection("c", K, 1100)]
+    wl.shared_x = True
+    up = [rt.upload_workload(wl, q, c.device) for q in range(3)]
+    pl = rt.plan(c, wl.req_adapter, wl.req_ntok, wl.ranks, wl.r_max)
+    outs = rt.linear_multi(c, pl, up[0][0], [(u[1], u[2]) for u in up])
+    torch.cuda.synchronize()
+    for q in range(3):
+        Yo = oracle_workload(wl, q)
+        if dtype == "bf16":
+            Yo = f32_from_bf16_bits(bf16_bits_from_f32(Yo.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(to_f64(rt.bits_from_tensor(outs[q])), Yo), q
+
+
 def test_strided_inputs_and_adapter_eviction():
     """ld > width for X, W0 and Y; a NULL table slot that the batch uses is reported, not dereferenced."""
     import torch
