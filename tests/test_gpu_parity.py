@@ -540,6 +540,26 @@ def test_fp32_integer_inputs_are_exact_on_every_tiled_path(T, K, N, variant):
     reset_options()
 
 
+@pytest.mark.parametrize("variant", [None, "tile_64x64", "tile_128x128", "tile_256x128", "tile_256x256w4", "tile_128x192",
+                                     "tile_256x192", "tile_256x224"])
+def test_bf16_base_product_integer_inputs_are_exact(variant):
+    """The bf16 MFMA base product alone (every request without an adapter), 65 stages of K with a partial last one,
+    ragged rows and columns: the exact integer result rounded once to bf16, on every tile shape and split along K."""
+    from gpu_common import ctx, gpu_linear, reset_options
+    from oracle import oracle_workload
+    from workloads import bf16_bits_from_f32, f32_from_bf16_bits
+    reset_options()
+    T = 700 if variant else 300  # (300 rows: the host's own choice is the launch split along K)
+    wl = make_custom(seed=990, dtype="bf16", K=4104, N=300, ranks=(8,), scales=(1.0,), req_adapter=np.full(7, -1),
+                     req_ntok=np.asarray([T - 6, 1, 1, 1, 1, 1, 1]), name=f"integers_base_{variant}", integer_valued=True)
+    if variant:
+        ctx().set_option("gemm_variant", VARIANTS[variant])
+    Yo = oracle_workload(wl)
+    Yo = f32_from_bf16_bits(bf16_bits_from_f32(Yo.astype(np.float32))).astype(np.float64)
+    assert np.array_equal(gpu_linear(wl), Yo)
+    reset_options()
+
+
 @pytest.mark.parametrize("T", [1, 17, 64, 128])
 def test_bf16_decode_path_integer_inputs_are_exact(T):
     """The decode path keeps V in fp32, so with small integers and power-of-two scales its result is the exact one,
