@@ -440,6 +440,36 @@ def run_adapter_heavy_decode(ctx, mods, options):
                               "cpu_baseline")}
 
 
+def run_library_gemm(ctx, mods):
+    """Context for the base product's figures (--library-gemm, not part of the default run): the plain GEMM of the
+    vendor library (torch.nn.functional.linear, bf16, random operands of the workloads' scale) and this library's
+    lora_linear without an adapter table, one after the other on the same box, at the base shapes of configurations
+    2, 3 and 4.  The vendor GEMM is not used anywhere else."""
+    np, torch, B, rt = mods
+    dev = ctx.device
+    rows = []
+    for name, T, K, N in (("c2 up_proj", 7539, 4096, 11008), ("c3 q_proj", 1216, 4096, 4096), ("c3 q/k/v", 1216, 4096, 12288),
+                          ("c3 gate/up", 1216, 4096, 22016), ("c3 down_proj", 1216, 11008, 4096), ("c4 up_proj", 2048, 5120, 13824)):
+        g = torch.Generator(device=dev).manual_seed(T + K + N)
+        X = torch.randn((T, K), device=dev, generator=g).to(torch.bfloat16)
+        W = (torch.randn((N, K), device=dev, generator=g) * 0.02).to(torch.bfloat16)
+        Y = torch.empty((T, N), dtype=torch.bfloat16, device=dev)
+        pl = rt.plan(ctx, np.full(1, -1, np.int32), np.full(1, T, np.int32), np.full(1, 8, np.int32), 8)
+        ws = rt.workspace(T, K, N, 8, torch.bfloat16, dev)
+        iters = 40
+        t_lib = _timed(torch, lambda i: torch.nn.functional.linear(X, W), iters + 10)  # (warm-up)
+        t_lib = _timed(torch, lambda i: torch.nn.functional.linear(X, W), iters)
+        t_own = _timed(torch, lambda i: rt.linear(ctx, pl, X, W, None, Y=Y, ws=ws), iters + 10)
+        t_own = _timed(torch, lambda i: rt.linear(ctx, pl, X, W, None, Y=Y, ws=ws), iters)
+        ref = torch.nn.functional.linear(X, W).float()
+        err = float((Y.float() - ref).abs().max() / ref.pow(2).mean().sqrt())
+        fl = 2.0 * T * K * N
+        rows.append({"shape": name, "T": T, "K": K, "N": N, "vendor_gemm_us": round(t_lib * 1e6, 1), "vendor_gemm_tflops": round(fl / t_lib / 1e12, 1),
+                     "lora_linear_no_adapters_us": round(t_own * 1e6, 1), "lora_linear_no_adapters_tflops": round(fl / t_own / 1e12, 1),
+                     "kernel": B.lora_gemm_kernel_name(ctx.handle, T, K, N, 1), "max_abs_diff_over_rms": err})
+    return rows
+
+
 def run_schedulers(np):
     """Decision latency of the two host-side schedulers at the scale of the paper's deployment (hundreds of functions
     on a GPU; configuration 4's pool of 512 adapters): microseconds per call, single host thread."""
@@ -491,6 +521,8 @@ def main():
                          "(one function's own batch, the regime of the paper's section 6)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], help="tuning override name=value (lora_ctx_set_option)")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="time the vendor library's plain bf16 GEMM and lora_linear without adapters at the base shapes of configurations 2-4 and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 256 MiB device copy kernel 5 times and exit (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -517,6 +549,10 @@ def main():
     ctx = rt.Context(0)
     options = [(o.split("=")[0], int(o.split("=")[1])) for o in args.option]
     cpu_s = 0.0 if args.no_cpu_baseline else 4.0
+    if args.library_gemm:
+        print(json.dumps({"library_gemm_reference": run_library_gemm(ctx, mods), "dtype": "bf16", "data": "synthetic"}))
+        ctx.close()
+        return
     common = {"metric": METRIC, "n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
 
     if args.same_adapter > 0 or args.config >= 0:  # one workload alone
