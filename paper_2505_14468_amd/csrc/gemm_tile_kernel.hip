@@ -35,6 +35,8 @@
 // that share W0 / X panels in its own L2.
 #include <limits.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace lora {
@@ -365,6 +367,29 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             }
         };
         auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+        // Issue order inside a scheduling region: a wave issues in order, and an MFMA occupies the matrix core for 32
+        // cycles during which the wave can issue its other instructions for nothing -- but only if they sit BETWEEN the
+        // MFMAs in program order.  Left to itself the compiler emits the region's LDS reads, loads and LDS stores in
+        // runs of 4 to 12 in front of runs of MFMAs.  Here: every MFMA followed by its share of the region's nr LDS
+        // reads, then of its ngw (load, LDS store) pairs.
+        auto interleave = [](auto nm_c, auto nr_c, auto ngw_c) __attribute__((always_inline)) {
+            constexpr int nm = decltype(nm_c)::value, nr = decltype(nr_c)::value, ngw = decltype(ngw_c)::value;
+            constexpr int others = nr + 2 * ngw, dm = nm > 0 ? nm : 1;
+#pragma unroll
+            for (int i = 0; i < nm; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+#pragma unroll
+                for (int j = i * others / dm; j < (i + 1) * others / dm; ++j) {
+                    if (j < nr)
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+                    else if (((j - nr) & 1) == 0)
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one global load
+                    else
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // one LDS store
+                }
+            }
+        };
+        using std::integral_constant;
         // stage kt: set (lx, lw) receives stage kt + 2, set (sx, sw) holds stage kt + 1
         auto stage_deep = [&](int kq, chunk_t (&lx)[XL], chunk_t (&lw)[WL], chunk_t (&sx)[XL], chunk_t (&sw)[WL], bool more,
                               bool load2, bool partial2) {
@@ -382,6 +407,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 }
                 if (load2) gload_q(lx, lw, kq + 2, kk, partial2);
                 if (more) lstore_q(sx, sw, buf ^ 1, kk);
+                interleave(integral_constant<int, NBN * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, (NS + 3) / 4>{});
                 __builtin_amdgcn_sched_barrier(0);  // nothing moves between k-steps: register lifetimes stay as written
             }
             constexpr int H = NBN > 1 ? NBN / 2 : 1;
@@ -391,6 +417,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
             if (load2) gload_q(lx, lw, kq + 2, 3, partial2);
             if (more) lstore_q(sx, sw, buf ^ 1, 3);
+            interleave(integral_constant<int, H * NBT>{}, integral_constant<int, 0>{}, integral_constant<int, (NS + 3) / 4>{});
             __builtin_amdgcn_sched_barrier(0);
             lds_barrier();
             __builtin_amdgcn_sched_barrier(0);
@@ -406,6 +433,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
                 if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
             }
+            interleave(integral_constant<int, (NBN - H) * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_barrier(0);
         };
         for (; kt + 3 < KT_full; kt += 2) {  // the steady state, two stages per trip: the sets swap roles
             stage_deep(kt, xr2, wr2, xr, wr, true, true, false);  // (stage 1 came into the first set before the loop)
