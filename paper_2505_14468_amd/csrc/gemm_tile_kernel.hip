@@ -18,7 +18,8 @@
 // hand-written software pipeline: MFMA operands are read from LDS one use ahead, the last
 // k-step of a stage is split around the stage's barrier, and two register sets of
 // staged operands keep the loads of the stage after next in flight while the next one is
-// written to LDS, a quarter per k-step (4 waves per workgroup, one per SIMD, for every tile shape).  MFMA orientation: M = output column n (W rows),
+// written to LDS, a third in each of a stage's first three k-steps (4 waves per workgroup, one per SIMD, for
+// every tile shape); the issue order inside a k-step is fixed with scheduling groups: MFMA, other, MFMA, other.  MFMA orientation: M = output column n (W rows),
 // N = token row t (X rows), so that every lane ends up with 4 consecutive n of one row.
 // LDS rows are 8 chunks long and XOR-swizzled by (row >> 1) & 7 so that both the 16-byte
 // stores (8 lanes per row) and the MFMA operand reads (32 rows, one chunk column) spread
@@ -333,12 +334,17 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
     {
         // Two register sets of staged operands: while stage kt is multiplied, the loads of stage kt + 2 go out
         // into one set and the other set, which holds stage kt + 1, is written to the LDS buffer that stage
-        // kt - 1 was read from -- a quarter of each per k-step, so neither the address unit nor LDS sees a
-        // burst and a load has a whole stage to arrive.  The barrier waits for LDS traffic only, never for
-        // the loads in flight across it.
+        // kt - 1 was read from -- a third of each in each of the first three k-steps, so neither the address unit
+        // nor LDS sees a burst and a load has a whole stage to arrive (loads or stores bunched into one or two
+        // k-steps, for more time between a load and its store, cost 4 to 17 %).  The barrier waits for LDS traffic
+        // only, never for the loads in flight across it.
         chunk_t xr2[XL], wr2[WL];
-        // the XL + WL load slots of a stage (X slots first), dealt to the four k-steps as evenly as they divide
+        // the XL + WL load slots of a stage (X slots first), dealt to the first three k-steps as evenly as they divide: the
+        // last LDS store of a stage then has the first half of the fourth k-step's MFMAs behind it, and the wait for
+        // LDS in front of the stage's barrier finds it done
         constexpr int NS = XL + WL;
+        constexpr auto gk = [](int s_) { return s_ * 3 / NS; };  // k-step in which slot s_ is loaded (stage kt + 2) ...
+        constexpr auto wk = [](int s_) { return s_ * 3 / NS; };  // ... and stored to LDS (stage kt + 1): exactly one stage later
         auto gload_q = [&](chunk_t (&xs)[XL], chunk_t (&ws)[WL], int kq, int q, bool partial) {
             const bool kv = !partial || (kq * 8 + lc) * CE < Kloc;
             // (partial stage: all of the offset per lane -- the scalar one must be uniform; dropped loads read the row start)
@@ -346,7 +352,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             const int soff = partial ? 0 : kq * 128;
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                if (s * 4 / NS != q) continue;
+                if (gk(s) != q) continue;
                 if (s < XL) {
                     xs[s < XL ? s : 0] = buffer_load_chunk(Xd, xoff[s < XL ? s : 0] + adj, soff);
                     if (partial) xs[s < XL ? s : 0] = keep_if(kv, xs[s < XL ? s : 0]);
@@ -359,7 +365,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         auto lstore_q = [&](const chunk_t (&xs)[XL], const chunk_t (&ws)[WL], int buf, int q) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                if (s * 4 / NS != q) continue;
+                if (wk(s) != q) continue;
                 if (s < XL)
                     sX[buf * BM * 8 + swz(lrow + s * RPP, lc)] = xs[s < XL ? s : 0];
                 else
@@ -372,22 +378,31 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
         // MFMAs in program order.  Left to itself the compiler emits the region's LDS reads, loads and LDS stores in
         // runs of 4 to 12 in front of runs of MFMAs.  Here: every MFMA followed by its share of the region's nr LDS
         // reads, then of its ngw (load, LDS store) pairs.
-        auto interleave = [](auto nm_c, auto nr_c, auto ngw_c) __attribute__((always_inline)) {
-            constexpr int nm = decltype(nm_c)::value, nr = decltype(nr_c)::value, ngw = decltype(ngw_c)::value;
-            constexpr int others = nr + 2 * ngw, dm = nm > 0 ? nm : 1;
+        auto interleave = [](auto nm_c, auto nr_c, auto ng_c, auto nw_c) __attribute__((always_inline)) {
+            constexpr int nm = decltype(nm_c)::value, nr = decltype(nr_c)::value, ng = decltype(ng_c)::value, nw = decltype(nw_c)::value;
+            constexpr int others = nr + ng + nw, dm = nm > 0 ? nm : 1, pairs = ng < nw ? ng : nw;
 #pragma unroll
             for (int i = 0; i < nm; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
 #pragma unroll
                 for (int j = i * others / dm; j < (i + 1) * others / dm; ++j) {
-                    if (j < nr)
+                    // the region's reads first, then (load, store) pairs, then whichever of the two kinds is left over
+                    const int k = j - nr;
+                    const bool is_read = j < nr;
+                    const bool is_load = !is_read && (k < 2 * pairs ? (k & 1) == 0 : ng > nw);
+                    if (is_read)
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-                    else if (((j - nr) & 1) == 0)
+                    else if (is_load)
                         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one global load
                     else
                         __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // one LDS store
                 }
             }
+        };
+        constexpr auto count_k = [](auto f, int q) {
+            int n = 0;
+            for (int s_ = 0; s_ < NS; ++s_) n += f(s_) == q;
+            return n;
         };
         using std::integral_constant;
         // stage kt: set (lx, lw) receives stage kt + 2, set (sx, sw) holds stage kt + 1
@@ -407,7 +422,12 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 }
                 if (load2) gload_q(lx, lw, kq + 2, kk, partial2);
                 if (more) lstore_q(sx, sw, buf ^ 1, kk);
-                interleave(integral_constant<int, NBN * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, (NS + 3) / 4>{});
+                if (kk == 0)
+                    interleave(integral_constant<int, NBN * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, count_k(gk, 0)>{}, integral_constant<int, count_k(wk, 0)>{});
+                else if (kk == 1)
+                    interleave(integral_constant<int, NBN * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, count_k(gk, 1)>{}, integral_constant<int, count_k(wk, 1)>{});
+                else
+                    interleave(integral_constant<int, NBN * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, count_k(gk, 2)>{}, integral_constant<int, count_k(wk, 2)>{});
                 __builtin_amdgcn_sched_barrier(0);  // nothing moves between k-steps: register lifetimes stay as written
             }
             constexpr int H = NBN > 1 ? NBN / 2 : 1;
@@ -415,9 +435,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
             for (int nb = 0; nb < H; ++nb)
 #pragma unroll
                 for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
-            if (load2) gload_q(lx, lw, kq + 2, 3, partial2);
-            if (more) lstore_q(sx, sw, buf ^ 1, 3);
-            interleave(integral_constant<int, H * NBT>{}, integral_constant<int, 0>{}, integral_constant<int, (NS + 3) / 4>{});
             __builtin_amdgcn_sched_barrier(0);
             lds_barrier();
             __builtin_amdgcn_sched_barrier(0);
@@ -433,7 +450,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_tile_kernel(GemmArgs p, int 
                 for (int tb = 0; tb < NBT; ++tb) Elem<E>::mma32(acc[nb][tb], wf[nb], xf[1][tb]);
                 if (more) wf[nb] = read_w(buf ^ 1, 0, nb);
             }
-            interleave(integral_constant<int, (NBN - H) * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, 0>{});
+            interleave(integral_constant<int, (NBN - H) * NBT>{}, integral_constant<int, NBN + NBT>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{});
             __builtin_amdgcn_sched_barrier(0);
         };
         for (; kt + 3 < KT_full; kt += 2) {  // the steady state, two stages per trip: the sets swap roles
