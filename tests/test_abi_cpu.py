@@ -145,3 +145,29 @@ def test_kernel_selection_is_host_side():
     assert B.lora_gemm_kernel_name(None, 16, 4096, 4096, B.LORA_DTYPE_BF16).startswith("decode_tb1")
     assert B.lora_gemm_kernel_name(None, 9000, 4096, 11008, B.LORA_DTYPE_BF16).startswith("tile_")
     assert B.lora_gemm_kernel_name(None, 64, 256, 256, B.LORA_DTYPE_F32).startswith("tile_")
+
+
+def test_launch_paths_of_the_benchmark_shapes():
+    """The host's choice of launch path is a function of (rows, K, N, dtype) alone, so it can be pinned without a GPU:
+    the five benchmark configurations' shapes and the switch points of the batch-size sweep (decode path up to 128
+    rows, tiles split along K while they would leave most CUs idle, one-round tile shapes above)."""
+    bf16, f32 = B.LORA_DTYPE_BF16, B.LORA_DTYPE_F32
+    want = {(128, 256, 256, f32): "tile_64x64",                  # configuration 0
+            (64, 4096, 4096, bf16): "decode_tb4",                # configuration 1
+            (7539, 4096, 11008, bf16): "tile_256x224",           # configuration 2: 5.86 rounds instead of 5.04 of 256x256
+            (1216, 4096, 4096, bf16): "tile_128x192",            # configuration 3: q/k/v/o
+            (1216, 4096, 11008, bf16): "tile_256x224",           #                  gate, up
+            (1216, 11008, 4096, bf16): "tile_256x256_splitk3",   #                  down: a long K into few columns
+            (2048, 5120, 13824, bf16): "tile_256x224",           # configuration 4
+            (1, 4096, 4096, bf16): "decode_tb1", (128, 4096, 4096, bf16): "decode_tb8",
+            (96, 4096, 11008, bf16): "decode_tb6", (128, 4096, 11008, bf16): "tile_64x64",  # wide outputs near 128 rows: tiles
+            (256, 4096, 4096, bf16): "tile_128x128_splitk4", (1024, 4096, 4096, bf16): "tile_128x128",
+            (129, 4096, 4096, f32): "tile_128x128_splitk6"}
+    got = {k: B.lora_gemm_kernel_name(None, *k) for k in want}
+    assert got == want
+    # the preferred workspace has room for the partial outputs exactly where a split is chosen
+    for (T, K, N, dt), name in want.items():
+        extra = B.lora_linear_workspace_bytes_preferred(T, K, N, 64, dt) - B.lora_linear_workspace_bytes(T, K, N, 64, dt)
+        splits = int(name.split("splitk")[1]) if "splitk" in name else 0
+        d_bytes = T * ((N + 7) // 8 * 8) * 4 if (T > 128 or dt == bf16) else 0
+        assert abs(extra - (d_bytes + splits * T * ((N + 7) // 8 * 8) * 4)) <= 1024, (T, K, N, name, extra)
